@@ -1,0 +1,306 @@
+"""Plain, slow, fp64 numpy oracle of the pruned-prefill hot path.
+
+TEST INFRASTRUCTURE ONLY -- never imported by the product package.
+
+What is modelled (paper: "2D or 3D: Who Governs Salience in VLA Models?"):
+
+* The backbone is a LLaMA-2 7B decoder stack over the concatenation
+  [2D tokens | 3D tokens | language tokens] (Sec. 5.1 Setup; App. C "MVLA
+  Models").  The paper only names the backbone, so the layer below is the
+  public LLaMA-2 decoder layer: RMSNorm, rotary embedding (rotate-half
+  pairing), causal multi-head attention, SiLU-gated MLP, no biases.
+* Attention-score salience: the attention matrix is partitioned by token
+  modality and every visual token is scored by the L1 norm of its attention
+  column (Sec. 3.2, Eq. 3; the same norms enter Eq. 5).  Probabilities are
+  non-negative, so the L1 norm is a plain sum; "avg" is read as the mean over
+  the (head, text-query) rows.
+* Modality mass ratio M^{S2}_{2D} = |a_2D|_1 / (|a_2D|_1 + |a_3D|_1)  (Eq. 5),
+  the same normalised form as Eq. 1, used to split one keep budget into
+  per-modality budgets (Sec. 5.2: different pruning rates for 2D and 3D).
+* Selection: per modality keep the K_m highest-salience tokens, lower index
+  wins ties, kept indices ascending.  This replaces the mask generation of
+  Algorithm 1 by an exact budget; the mask semantics stay those of Eq. 10 /
+  Sec. 4.4: kept tokens go on to the later layers, the rest are discarded.
+* Temporal smoothing of an indicator (Sec. 4.3/4.4, Eqs. 7-9, Algorithm 1
+  "Action Iteration Stage").
+
+Every reduction is carried in float64.  Inputs are whatever values the caller
+hands over (for bf16 workloads: the bf16-rounded values widened to float64);
+nothing is rounded in between.
+
+Pins (tests/test_oracle_pins.py): brute-force subset enumeration and
+torch.topk for selection; closed forms for salience, budget, RMSNorm, RoPE,
+EMA; a loop-written O(n^2) attention and torch's scaled_dot_product_attention;
+an independently written torch-CPU decoder layer; keep-100% == unpruned.
+End-to-end selection *quality* against the paper's success rates and measured
+per-modality pruning rates is parity unpinned (needs the simulator and the
+model checkpoint).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+__all__ = [
+    "rmsnorm", "rope_rotate_half", "attention_probs", "decoder_layer",
+    "score_only", "salience", "modality_budget", "select_topk", "compact",
+    "keep_count", "pruned_prefill", "ema_indicator",
+]
+
+F64 = np.float64
+
+
+# --------------------------------------------------------------------------
+# Backbone layer (App. C: LLaMA-2 7B backbone; public LLaMA-2 layer maths)
+# --------------------------------------------------------------------------
+def rmsnorm(x, gain, eps):
+    """u_i = x_i * gain_i / sqrt(mean_j(x_j^2) + eps), over the last axis."""
+    x = np.asarray(x, F64)
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + eps) * np.asarray(gain, F64)
+
+
+def rope_rotate_half(t, pos, base=10000.0):
+    """Rotary embedding with rotate-half pairing.
+
+    t: [S, H, dh]; pos: [S] integer position ids.  Element i of the first half
+    is paired with element i + dh/2; the pair is rotated by the angle
+    pos * base**(-2 i / dh).
+    """
+    t = np.asarray(t, F64)
+    S, H, dh = t.shape
+    half = dh // 2
+    inv_freq = base ** (-2.0 * np.arange(half, dtype=F64) / dh)
+    ang = np.asarray(pos, F64)[:, None] * inv_freq[None, :]      # [S, half]
+    c = np.cos(ang)[:, None, :]
+    s = np.sin(ang)[:, None, :]
+    a = t[..., :half]
+    b = t[..., half:]
+    return np.concatenate([a * c - b * s, b * c + a * s], axis=-1)
+
+
+def attention_probs(q, k, causal=True, key_bias=None, q_row0=0):
+    """Row-softmax attention probabilities for one sample.
+
+    q: [Sq, H, dh] (rows q_row0 .. q_row0+Sq-1 of the sequence), k: [S, H, dh].
+    logits[h, i, j] = q_i . k_j / sqrt(dh) (+ key_bias[j]); with `causal`,
+    query row r only sees keys j <= r.  Returns [H, Sq, S].
+    """
+    q = np.asarray(q, F64)
+    k = np.asarray(k, F64)
+    Sq, H, dh = q.shape
+    S = k.shape[0]
+    # logits[h] = q[:, h, :] @ k[:, h, :].T
+    logits = np.matmul(q.transpose(1, 0, 2), k.transpose(1, 2, 0)) / np.sqrt(F64(dh))
+    if key_bias is not None:
+        logits = logits + np.asarray(key_bias, F64)[None, None, :]
+    if causal:
+        rows = q_row0 + np.arange(Sq)[:, None]
+        cols = np.arange(S)[None, :]
+        logits = np.where(cols <= rows, logits, -np.inf)
+    m = np.max(logits, axis=-1, keepdims=True)
+    e = np.exp(logits - m)
+    return e / np.sum(e, axis=-1, keepdims=True)
+
+
+def _silu(z):
+    return z / (1.0 + np.exp(-z))
+
+
+def _qk(x, pos, w, H, eps, base, rows=None):
+    """Normalised input -> rotated q (optionally only `rows`) and k, plus u."""
+    u = rmsnorm(x, w["g_attn"], eps)
+    S, D = u.shape
+    dh = D // H
+    uq = u if rows is None else u[rows]
+    pq = pos if rows is None else np.asarray(pos)[rows]
+    q = (uq @ np.asarray(w["wq"], F64).T).reshape(-1, H, dh)
+    k = (u @ np.asarray(w["wk"], F64).T).reshape(S, H, dh)
+    return rope_rotate_half(q, pq, base), rope_rotate_half(k, pos, base), u
+
+
+def decoder_layer(x, pos, w, H, eps=1e-5, base=10000.0, n_query_tail=0,
+                  key_bias=None):
+    """One LLaMA-2 decoder layer on one sample.
+
+    x: [S, D]; pos: [S]; w: dict of wq, wk, wv, wo [D, D], w_gate, w_up [F, D],
+    w_down [D, F] -- all stored [out_features, in_features] so a projection is
+    x @ W.T -- and RMSNorm gains g_attn, g_mlp [D].
+
+    Returns (y, probs): y [S, D]; probs [H, n_query_tail, S] are the attention
+    probabilities of the last n_query_tail rows (the language-token queries),
+    with `key_bias` added to *those* logits only (the layer's own attention is
+    never biased), or None when n_query_tail == 0.
+    """
+    x = np.asarray(x, F64)
+    S, D = x.shape
+    dh = D // H
+    q, k, u = _qk(x, pos, w, H, eps, base)
+    v = (u @ np.asarray(w["wv"], F64).T).reshape(S, H, dh)
+    A = attention_probs(q, k, causal=True)                        # [H, S, S]
+    o = np.matmul(A, v.transpose(1, 0, 2)).transpose(1, 0, 2).reshape(S, D)
+    x1 = x + o @ np.asarray(w["wo"], F64).T
+    t = rmsnorm(x1, w["g_mlp"], eps)
+    gate = t @ np.asarray(w["w_gate"], F64).T
+    up = t @ np.asarray(w["w_up"], F64).T
+    y = x1 + (_silu(gate) * up) @ np.asarray(w["w_down"], F64).T
+    probs = None
+    if n_query_tail > 0:
+        r0 = S - n_query_tail
+        probs = attention_probs(q[r0:], k, causal=True, key_bias=key_bias,
+                                q_row0=r0)
+    return y, probs
+
+
+def score_only(x, pos, w, H, n_query_tail, eps=1e-5, base=10000.0,
+               key_bias=None):
+    """Scoring pass when pruning happens before any layer has run: the first
+    layer's norm, q (tail rows) and k projections, RoPE and causal softmax --
+    nothing else.  Returns [H, n_query_tail, S]."""
+    x = np.asarray(x, F64)
+    S = x.shape[0]
+    r0 = S - n_query_tail
+    q, k, _ = _qk(x, pos, w, H, eps, base, rows=np.arange(r0, S))
+    return attention_probs(q, k, causal=True, key_bias=key_bias, q_row0=r0)
+
+
+# --------------------------------------------------------------------------
+# Pruning step
+# --------------------------------------------------------------------------
+def salience(probs, n_vis):
+    """Attention-score salience of every visual token (Sec. 3.2, Eq. 3).
+
+    probs: [B, H, Nq, S] row-softmaxed attention of the language-token
+    queries.  sal[b, j] = mean over (h, q) of probs[b, h, q, j], j < n_vis:
+    the L1 norm of token j's attention column, averaged over the rows.
+    """
+    p = np.asarray(probs, F64)
+    B, H, Nq, S = p.shape
+    return np.sum(p[:, :, :, :n_vis], axis=(1, 2)) / F64(H * Nq)
+
+
+def keep_count(keep_permille, n_vis):
+    """K = round-half-up(keep * n_vis) in integers (keep given in 1/1000)."""
+    return (int(keep_permille) * int(n_vis) + 500) // 1000
+
+
+def modality_budget(sal, n2, n3, k_total, min2=0, min3=0):
+    """Split k_total between the 2D and 3D segments by salience mass (Eq. 5).
+
+    sal: [B, n2+n3].  m2 = sum(sal[:n2]) / sum(sal);  K2 = floor(K*m2 + 1/2),
+    clamped to [max(min2, K-n3), min(n2, K-min3)];  K3 = K - K2.  A sample
+    with zero total mass falls back to m2 = n2 / (n2+n3).
+    Returns (k2k3 int32 [B,2], mass float64 [B,2]).
+    """
+    s = np.asarray(sal, F64)
+    B = s.shape[0]
+    assert s.shape[1] == n2 + n3 and 0 <= k_total <= n2 + n3
+    assert min2 + min3 <= k_total or k_total == 0
+    k2k3 = np.zeros((B, 2), np.int32)
+    mass = np.zeros((B, 2), F64)
+    for b in range(B):
+        a2 = np.sum(s[b, :n2])
+        a3 = np.sum(s[b, n2:])
+        m2 = a2 / (a2 + a3) if (a2 + a3) > 0.0 else F64(n2) / F64(n2 + n3)
+        k2 = int(np.floor(k_total * m2 + 0.5))
+        lo = max(min2, k_total - n3)
+        hi = min(n2, k_total - min3)
+        k2 = min(max(k2, lo), hi)
+        k2k3[b] = (k2, k_total - k2)
+        mass[b] = (m2, 1.0 - m2)
+    return k2k3, mass
+
+
+def select_topk(sal, k2k3, n2, n3, n_text):
+    """Per-modality top-k with lower-index-wins ties, output ascending.
+
+    The definition is written out literally: in each modality segment order
+    the tokens by (salience descending, index ascending) with a stable sort,
+    take the first K_m, then list the taken indices in ascending order.  All
+    n_text language tokens follow (never pruned; Eq. 10 defines masks for the
+    two visual modalities only).  Returns int32 [B, K2+K3+n_text].
+    """
+    s = np.asarray(sal)
+    B = s.shape[0]
+    assert not np.any(np.isnan(s)) and not np.any(np.isinf(s))
+    rows = []
+    for b in range(B):
+        k2, k3 = int(k2k3[b][0]), int(k2k3[b][1])
+        keep = []
+        for start, n, k in ((0, n2, k2), (n2, n3, k3)):
+            seg = s[b, start:start + n]
+            order = np.argsort(-seg, kind="stable")     # ties keep index order
+            keep.append(np.sort(order[:k]) + start)
+        keep.append(np.arange(n2 + n3, n2 + n3 + n_text))
+        rows.append(np.concatenate(keep))
+    return np.stack(rows).astype(np.int32)
+
+
+def compact(h, pos, kept_idx):
+    """h'[b,i,:] = h[b, kept_idx[b,i], :],  pos'[b,i] = pos[b, kept_idx[b,i]]
+    (Sec. 4.4: tokens with mask 1 proceed, tokens with mask 0 are dropped)."""
+    h = np.asarray(h)
+    pos = np.asarray(pos)
+    B = h.shape[0]
+    ho = np.stack([h[b, kept_idx[b]] for b in range(B)])
+    po = np.stack([pos[b, kept_idx[b]] for b in range(B)])
+    return ho, po
+
+
+def pruned_prefill(x, pos, layers, H, n2, n3, n_text, k_total, p,
+                   eps=1e-5, base=10000.0, key_bias=None, min2=0, min3=0):
+    """Whole path on a batch: p layers on all S tokens (the last of them, or a
+    scoring pass when p == 0, yields the language-query probabilities), the
+    pruning step, then the remaining layers on the kept tokens with their
+    original position ids.
+
+    x: [B, S, D]; pos: [B, S]; layers: list of weight dicts.
+    Returns dict(y, pos, kept_idx, k2k3, sal, probs).
+    """
+    x = np.asarray(x, F64)
+    B, S, D = x.shape
+    n_vis = n2 + n3
+    assert S == n_vis + n_text
+    h = x.copy()
+    probs = [None] * B
+    for li in range(p):
+        tail = n_text if li == p - 1 else 0
+        for b in range(B):
+            kb = None if key_bias is None else key_bias[b]
+            h[b], pr = decoder_layer(h[b], pos[b], layers[li], H, eps, base,
+                                     tail, kb)
+            if tail:
+                probs[b] = pr
+    if p == 0:
+        for b in range(B):
+            kb = None if key_bias is None else key_bias[b]
+            probs[b] = score_only(h[b], pos[b], layers[0], H, n_text, eps,
+                                  base, kb)
+    probs = np.stack(probs)
+    sal = salience(probs, n_vis).astype(np.float32)
+    k2k3, _ = modality_budget(sal, n2, n3, k_total, min2, min3)
+    kept = select_topk(sal, k2k3, n2, n3, n_text)
+    h, pos2 = compact(h, pos, kept)
+    h = h.copy()
+    for li in range(p, len(layers)):
+        for b in range(B):
+            h[b], _ = decoder_layer(h[b], pos2[b], layers[li], H, eps, base)
+    return dict(y=h, pos=pos2, kept_idx=kept, k2k3=k2k3, sal=sal, probs=probs)
+
+
+# --------------------------------------------------------------------------
+# Action-iteration smoothing (Sec. 4.3, Eq. 7; Sec. 4.4, Eqs. 8-9; Alg. 1)
+# --------------------------------------------------------------------------
+def ema_indicator(x_hat_prev, x_t, t, k=7, beta=0.85):
+    """Smoothed indicator at step t (1-based).
+
+    t == 1: the observation itself (cold start; no pruning happens there).
+    1 < t < k: running mean  ((t-1)/t) * prev + x_t / t          (Eq. 8).
+    t >= k:  beta * prev + (1 - beta) * x_t                      (Eq. 9).
+    """
+    x_t = np.asarray(x_t, F64)
+    if t == 1:
+        return x_t.copy()
+    prev = np.asarray(x_hat_prev, F64)
+    if t < k:
+        return prev * (F64(t - 1) / F64(t)) + x_t / F64(t)
+    return beta * prev + (1.0 - beta) * x_t

@@ -1,0 +1,380 @@
+"""CPU pins of the oracle against things that are not the oracle: brute force,
+closed forms, invariants, library routines and values the paper prints."""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+rng = np.random.default_rng
+
+
+# ---------------------------------------------------------------- selection
+def _brute_force_topk(seg, k):
+    """Among all k-subsets: maximal value sum, then lexicographically smallest
+    ascending index tuple.  Values are small integers so sums are exact."""
+    best = None
+    for c in itertools.combinations(range(len(seg)), k):
+        key = (-sum(int(seg[i]) for i in c), c)
+        if best is None or key < best:
+            best = key
+    return list(best[1])
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_select_matches_subset_enumeration(seed):
+    r = rng(seed)
+    n2, n3, nt = 9, 11, 3
+    sal = r.integers(0, 4, size=(2, n2 + n3)).astype(np.float32)  # many ties
+    k2k3 = np.array([[r.integers(0, n2 + 1), r.integers(0, n3 + 1)] for _ in range(2)])
+    # both samples must share K = K2+K3 for a rectangular result
+    k2k3[1, 0] = min(n2, k2k3[0].sum())
+    k2k3[1, 1] = k2k3[0].sum() - k2k3[1, 0]
+    if k2k3[1, 1] > n3:
+        pytest.skip("infeasible draw")
+    out = O.select_topk(sal, k2k3, n2, n3, nt)
+    for b in range(2):
+        exp = _brute_force_topk(sal[b, :n2], int(k2k3[b, 0]))
+        exp += [n2 + i for i in _brute_force_topk(sal[b, n2:], int(k2k3[b, 1]))]
+        exp += list(range(n2 + n3, n2 + n3 + nt))
+        assert out[b].tolist() == exp
+
+
+def test_select_distinct_values_equals_torch_topk():
+    r = rng(1)
+    n2, n3, nt, k2, k3 = 300, 500, 7, 120, 77
+    sal = r.permutation(n2 + n3).astype(np.float32)[None] / 7.0
+    out = O.select_topk(sal, np.array([[k2, k3]]), n2, n3, nt)[0]
+    t = torch.from_numpy(sal[0])
+    e2 = torch.topk(t[:n2], k2).indices.sort().values
+    e3 = torch.topk(t[n2:], k3).indices.sort().values + n2
+    exp = torch.cat([e2, e3, torch.arange(n2 + n3, n2 + n3 + nt)])
+    assert out.tolist() == exp.tolist()
+
+
+def test_select_tie_rules():
+    n2, n3 = 8, 8
+    flat = np.ones((1, 16), np.float32)
+    assert O.select_topk(flat, [[3, 5]], n2, n3, 0)[0].tolist() == [0, 1, 2, 8, 9, 10, 11, 12]
+    # duplicates straddling the K-th place: value 5 at 1,4,6 ; K=3 keeps 9 and the two lowest 5s
+    s = np.array([[1, 5, 9, 0, 5, 2, 5, 3] + [0] * 8], np.float32)
+    assert O.select_topk(s, [[3, 0]], n2, n3, 0)[0].tolist() == [1, 2, 4]
+    # +0 and -0 tie: lower index wins
+    z = np.array([[-0.0, 0.0, -1, -1, -1, -1, -1, -1] + [0] * 8], np.float32)
+    assert O.select_topk(z, [[1, 0]], n2, n3, 0)[0].tolist() == [0]
+    z2 = np.array([[0.0, -0.0, -1, -1, -1, -1, -1, -1] + [0] * 8], np.float32)
+    assert O.select_topk(z2, [[1, 0]], n2, n3, 0)[0].tolist() == [0]
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_select_invariants(seed):
+    r = rng(100 + seed)
+    n2, n3, nt, K, B = 64, 96, 5, 70, 4
+    sal = np.floor(r.lognormal(size=(B, n2 + n3)) * 4).astype(np.float32)
+    k2k3, mass = O.modality_budget(sal, n2, n3, K)
+    out = O.select_topk(sal, k2k3, n2, n3, nt)
+    assert out.shape == (B, K + nt) and out.dtype == np.int32
+    for b in range(B):
+        row = out[b]
+        assert np.all(np.diff(row) > 0)
+        assert np.sum(row < n2) == k2k3[b, 0]
+        assert np.sum((row >= n2) & (row < n2 + n3)) == k2k3[b, 1]
+        assert row[-nt:].tolist() == list(range(n2 + n3, n2 + n3 + nt))
+        assert k2k3[b].sum() == K
+        # every dropped token scores no higher than every kept one of its modality
+        for lo, hi in ((0, n2), (n2, n2 + n3)):
+            kept = [i for i in row if lo <= i < hi]
+            drop = [i for i in range(lo, hi) if i not in set(kept)]
+            if kept and drop:
+                assert sal[b, drop].max() <= sal[b, kept].min()
+
+
+# ---------------------------------------------------------------- budget
+def test_budget_closed_forms():
+    n2 = n3 = 10
+    s = np.zeros((1, 20)); s[0, :n2] = 1.0
+    assert O.modality_budget(s, n2, n3, 6)[0].tolist() == [[6, 0]]
+    assert O.modality_budget(s, n2, n3, 14)[0].tolist() == [[10, 4]]   # overflow handed to 3D
+    s[:] = 1.0
+    assert O.modality_budget(s, n2, n3, 8)[0].tolist() == [[4, 4]]
+    assert O.modality_budget(s, n2, n3, 7)[0].tolist() == [[4, 3]]     # 3.5 rounds half up
+    assert O.modality_budget(s, n2, n3, 20)[0].tolist() == [[10, 10]]  # keep everything
+    s[:] = 0.0
+    assert O.modality_budget(s, 5, 15, 8)[0].tolist() == [[2, 6]]      # zero mass: by count
+    s = np.zeros((1, 20)); s[0, n2:] = 3.0
+    assert O.modality_budget(s, n2, n3, 6, min2=2)[0].tolist() == [[2, 4]]
+    assert O.modality_budget(s, n2, n3, 14)[0].tolist() == [[4, 10]]   # overflow handed to 2D
+    s = np.zeros((1, 20)); s[0, :n2] = 1.0
+    assert O.modality_budget(s, n2, n3, 6, min3=1)[0].tolist() == [[5, 1]]
+
+
+def test_budget_swap_symmetry_and_mass_normalisation():
+    r = rng(7)
+    n = 32
+    sal = r.lognormal(size=(3, 2 * n))
+    k, m = O.modality_budget(sal, n, n, 21)
+    swapped = np.concatenate([sal[:, n:], sal[:, :n]], axis=1)
+    k2, m2 = O.modality_budget(swapped, n, n, 21)
+    assert np.allclose(m.sum(1), 1.0) and np.allclose(m[:, ::-1], m2)
+    for b in range(3):
+        frac = 21 * m[b, 0] - math.floor(21 * m[b, 0])
+        if abs(frac - 0.5) > 1e-9:
+            assert k[b].tolist() == k2[b, ::-1].tolist()
+
+
+def test_budget_reproduces_table1_split():
+    rows = [l.split() for l in open(os.path.join(GOLD, "table1_modality_mass.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) == 15
+    for task, case, m2, m3 in rows:
+        m2, m3 = float(m2), float(m3)
+        assert abs(m2 + m3 - 100.0) < 0.011
+        # two "tokens" whose norms are the printed percentages
+        _, mass = O.modality_budget(np.array([[m2, m3]]), 1, 1, 1)
+        assert abs(mass[0, 0] - m2 / (m2 + m3)) < 1e-15
+        assert abs(mass[0].sum() - 1.0) < 1e-15
+
+
+def test_keep_count_integer_rounding():
+    assert O.keep_count(400, 512) == 205
+    assert O.keep_count(300, 1792) == 538
+    assert [O.keep_count(k, 2560) for k in (1000, 700, 500, 300, 150)] == \
+        [2560, 1792, 1280, 768, 384]
+    assert O.keep_count(500, 128) == 64
+
+
+# ---------------------------------------------------------------- salience
+def test_salience_one_hot_counts_and_row_mass():
+    B, H, Nq, S, nv = 2, 3, 4, 10, 7
+    p = np.zeros((B, H, Nq, S))
+    r = rng(3)
+    cols = r.integers(0, S, size=(B, H, Nq))
+    for b, h, q in itertools.product(range(B), range(H), range(Nq)):
+        p[b, h, q, cols[b, h, q]] = 1.0
+    sal = O.salience(p, nv)
+    for b in range(B):
+        for j in range(nv):
+            assert sal[b, j] == np.sum(cols[b] == j) / (H * Nq)
+    pr = r.random((B, H, Nq, S)); pr /= pr.sum(-1, keepdims=True)
+    assert np.allclose(O.salience(pr, S).sum(1), 1.0, atol=1e-14)
+
+
+def test_salience_uniform_attention_closed_form():
+    """Zero query weights make every causal row uniform, so a visual column j
+    receives 1/(n_vis+q+1) from text query q."""
+    r = rng(5)
+    n2, n3, nt, D, H = 6, 5, 4, 16, 2
+    S = n2 + n3 + nt
+    w = dict(wq=np.zeros((D, D)), wk=r.normal(size=(D, D)), g_attn=np.ones(D))
+    x = r.normal(size=(S, D))
+    probs = O.score_only(x, np.arange(S), w, H, nt)
+    sal = O.salience(probs[None], n2 + n3)[0]
+    expect = sum(1.0 / (n2 + n3 + q + 1) for q in range(nt)) / nt
+    assert np.allclose(sal, expect, rtol=1e-13)
+
+
+# ---------------------------------------------------------------- attention
+def _naive_attention(q, k, v, causal):
+    S, H, dh = k.shape
+    out = np.zeros_like(q)
+    P = np.zeros((H, q.shape[0], S))
+    for h in range(H):
+        for i in range(q.shape[0]):
+            lim = i + 1 if causal else S
+            lg = [sum(q[i, h, d] * k[j, h, d] for d in range(dh)) / math.sqrt(dh)
+                  for j in range(lim)]
+            m = max(lg)
+            e = [math.exp(l - m) for l in lg]
+            z = sum(e)
+            for j in range(lim):
+                P[h, i, j] = e[j] / z
+                for d in range(dh):
+                    out[i, h, d] += P[h, i, j] * v[j, h, d]
+    return P, out
+
+
+def test_attention_against_loops_and_sdpa():
+    r = rng(11)
+    S, H, dh = 13, 2, 8
+    q, k, v = (r.normal(size=(S, H, dh)) for _ in range(3))
+    P = O.attention_probs(q, k, causal=True)
+    Pn, on = _naive_attention(q, k, v, True)
+    assert np.allclose(P, Pn, atol=1e-14)
+    o = np.matmul(P, v.transpose(1, 0, 2)).transpose(1, 0, 2)
+    assert np.allclose(o, on, atol=1e-13)
+    tq, tk, tv = (torch.from_numpy(a).permute(1, 0, 2)[None] for a in (q, k, v))
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True)
+    assert np.allclose(o, ref[0].permute(1, 0, 2).numpy(), atol=1e-12)
+    # tail rows with a key bias == softmax of biased logits, rows offset correctly
+    bias = r.normal(size=S)
+    Pt = O.attention_probs(q[-3:], k, causal=True, key_bias=bias, q_row0=S - 3)
+    for h in range(H):
+        for i in range(3):
+            row = S - 3 + i
+            lg = (k[:row + 1, h] @ q[row, h]) / math.sqrt(dh) + bias[:row + 1]
+            e = np.exp(lg - lg.max())
+            assert np.allclose(Pt[h, i, :row + 1], e / e.sum(), atol=1e-14)
+            assert np.all(Pt[h, i, row + 1:] == 0)
+
+
+# ---------------------------------------------------------------- layer parts
+def test_rmsnorm_closed_form():
+    g = np.array([1.0, -2.0, 0.5, 3.0])
+    x = np.full((2, 4), -7.0)
+    u = O.rmsnorm(x, g, 0.0)
+    assert np.allclose(u, -g)                      # constant vector -> sign * gain
+    x = rng(0).normal(size=(3, 64))
+    u = O.rmsnorm(x, np.ones(64), 1e-5)
+    assert np.allclose((u * u).mean(-1), (x * x).mean(-1) / ((x * x).mean(-1) + 1e-5))
+
+
+def test_rope_properties():
+    r = rng(2)
+    S, H, dh = 6, 2, 8
+    t = r.normal(size=(S, H, dh))
+    assert np.allclose(O.rope_rotate_half(t, np.zeros(S, int)), t)      # pos 0: identity
+    pos = np.array([0, 1, 5, 17, 100, 2623])
+    rt = O.rope_rotate_half(t, pos)
+    half = dh // 2
+    assert np.allclose(rt[..., :half] ** 2 + rt[..., half:] ** 2,
+                       t[..., :half] ** 2 + t[..., half:] ** 2)          # pair norms kept
+    # explicit angle for one element: pair (1, 1+half) of token 3
+    th = 17 * 10000.0 ** (-2.0 * 1 / dh)
+    a, b = t[3, 0, 1], t[3, 0, 1 + half]
+    assert math.isclose(rt[3, 0, 1], a * math.cos(th) - b * math.sin(th), rel_tol=1e-12)
+    assert math.isclose(rt[3, 0, 1 + half], b * math.cos(th) + a * math.sin(th), rel_tol=1e-12)
+    # relative-position property: <R_m q, R_n k> depends on m-n only
+    q, k = r.normal(size=(1, 1, dh)), r.normal(size=(1, 1, dh))
+    d1 = np.sum(O.rope_rotate_half(q, [9]) * O.rope_rotate_half(k, [4]))
+    d2 = np.sum(O.rope_rotate_half(q, [105]) * O.rope_rotate_half(k, [100]))
+    assert math.isclose(d1, d2, rel_tol=1e-10)
+
+
+def _rand_layer(r, D, F, scale=0.05):
+    return dict(wq=r.normal(size=(D, D)) * scale, wk=r.normal(size=(D, D)) * scale,
+                wv=r.normal(size=(D, D)) * scale, wo=r.normal(size=(D, D)) * scale,
+                w_gate=r.normal(size=(F, D)) * scale, w_up=r.normal(size=(F, D)) * scale,
+                w_down=r.normal(size=(D, F)) * scale,
+                g_attn=1 + 0.02 * r.normal(size=D), g_mlp=1 + 0.02 * r.normal(size=D))
+
+
+def test_layer_degenerate_weights():
+    r = rng(4)
+    S, D, H, F = 9, 16, 2, 24
+    w = _rand_layer(r, D, F)
+    x = r.normal(size=(S, D))
+    pos = np.arange(S)
+    w0 = dict(w, wo=np.zeros((D, D)), w_down=np.zeros((D, F)))
+    assert np.array_equal(O.decoder_layer(x, pos, w0, H)[0], x)
+    wg = dict(w, w_gate=np.zeros((F, D)))
+    y_attn_only = O.decoder_layer(x, pos, wg, H)[0]
+    y_no_mlp = O.decoder_layer(x, pos, dict(w, w_down=np.zeros((D, F))), H)[0]
+    assert np.allclose(y_attn_only, y_no_mlp, atol=1e-15)     # SiLU(0) = 0 kills the MLP
+
+
+def _torch_layer(x, pos, w, H, eps, base):
+    """Independent decoder layer written with torch CPU fp64 ops."""
+    T = lambda a: torch.from_numpy(np.asarray(a, np.float64))
+    x = T(x); S, D = x.shape; dh = D // H
+
+    def norm(v, g):
+        return v * torch.rsqrt(v.pow(2).mean(-1, keepdim=True) + eps) * T(g)
+
+    def rot(t):
+        inv = 1.0 / (base ** (torch.arange(0, dh, 2, dtype=torch.float64) / dh))
+        fr = torch.outer(torch.tensor(pos, dtype=torch.float64), inv)
+        emb = torch.cat([fr, fr], -1)[None]                   # [1,S,dh]
+        t1, t2 = t[..., :dh // 2], t[..., dh // 2:]
+        return t * emb.cos() + torch.cat([-t2, t1], -1) * emb.sin()
+
+    lin = torch.nn.functional.linear
+    u = norm(x, w["g_attn"])
+    q = lin(u, T(w["wq"])).view(S, H, dh).transpose(0, 1)
+    k = lin(u, T(w["wk"])).view(S, H, dh).transpose(0, 1)
+    v = lin(u, T(w["wv"])).view(S, H, dh).transpose(0, 1)
+    o = torch.nn.functional.scaled_dot_product_attention(rot(q)[None], rot(k)[None], v[None],
+                                                         is_causal=True)[0]
+    x1 = x + lin(o.transpose(0, 1).reshape(S, D), T(w["wo"]))
+    t = norm(x1, w["g_mlp"])
+    y = x1 + lin(torch.nn.functional.silu(lin(t, T(w["w_gate"]))) * lin(t, T(w["w_up"])),
+                 T(w["w_down"]))
+    return y.numpy()
+
+
+def test_layer_against_independent_torch_layer_on_tiny_config():
+    from paper_2604_09244_amd import workloads as W
+    wl = W.WORKLOADS["tiny"]
+    x, pos = W.hidden_states(wl)
+    w = {k: v.to(torch.float64).numpy() for k, v in W.layer_weights(wl, 0).items()}
+    xs = x[0].to(torch.float64).numpy()
+    y, _ = O.decoder_layer(xs, pos[0].numpy(), w, wl.H, wl.rms_eps, wl.rope_base)
+    yt = _torch_layer(xs, pos[0].numpy(), w, wl.H, wl.rms_eps, wl.rope_base)
+    assert np.allclose(y, yt, atol=1e-11)
+    # non-contiguous position ids (what the kept tokens carry after pruning)
+    pp = np.sort(rng(0).choice(2000, size=wl.S, replace=False))
+    y2, _ = O.decoder_layer(xs, pp, w, wl.H)
+    assert np.allclose(y2, _torch_layer(xs, pp, w, wl.H, 1e-5, 10000.0), atol=1e-11)
+
+
+# ---------------------------------------------------------------- pipeline
+def test_keep_everything_equals_unpruned_forward():
+    r = rng(9)
+    n2, n3, nt, D, H, F, B = 7, 6, 3, 16, 2, 24, 2
+    S = n2 + n3 + nt
+    layers = [_rand_layer(r, D, F) for _ in range(3)]
+    x = r.normal(size=(B, S, D))
+    pos = np.tile(np.arange(S), (B, 1))
+    for p in (0, 1, 2):
+        out = O.pruned_prefill(x, pos, layers, H, n2, n3, nt, n2 + n3, p)
+        ref = x.copy()
+        for b in range(B):
+            for w in layers:
+                ref[b] = O.decoder_layer(ref[b], pos[b], w, H)[0]
+        assert np.array_equal(out["y"], ref)
+        assert out["kept_idx"].tolist() == [list(range(S))] * B
+        assert out["k2k3"].tolist() == [[n2, n3]] * B
+
+
+def test_pruned_pipeline_structure():
+    r = rng(10)
+    n2, n3, nt, D, H, F, B, K = 8, 8, 3, 16, 2, 24, 2, 7
+    S = n2 + n3 + nt
+    layers = [_rand_layer(r, D, F, 0.3) for _ in range(2)]
+    x = r.normal(size=(B, S, D))
+    pos = np.tile(np.arange(S), (B, 1))
+    out = O.pruned_prefill(x, pos, layers, H, n2, n3, nt, K, 1)
+    assert out["y"].shape == (B, K + nt, D)
+    for b in range(B):
+        assert np.array_equal(out["pos"][b], out["kept_idx"][b])       # pos ids are carried
+        # the probabilities behind the salience are those of layer 0's text rows
+        _, pr = O.decoder_layer(x[b], pos[b], layers[0], H, n_query_tail=nt)
+        assert np.allclose(out["probs"][b], pr)
+        assert np.allclose(pr.sum(-1), 1.0)
+
+
+# ---------------------------------------------------------------- EMA (Eqs. 8, 9)
+def test_ema_warmup_is_running_mean_and_steady_state_is_geometric():
+    r = rng(12)
+    xs = r.random((12, 5))
+    k, beta = 7, 0.85
+    hat = None
+    for t in range(1, 13):
+        hat = O.ema_indicator(hat, xs[t - 1], t, k, beta)
+        if t < k:
+            assert np.allclose(hat, xs[:t].mean(0), atol=1e-15)          # Eq. 8 closed form
+    c = np.full(5, 0.3)
+    assert np.allclose(O.ema_indicator(c, c, 9, k, beta), c)              # fixed point of Eq. 9
+    hat = np.zeros(5)
+    for n in range(1, 6):                                                 # unit step input
+        hat = O.ema_indicator(hat, np.ones(5), k + n, k, beta)
+        assert np.allclose(hat, 1 - beta ** n)
+
+
+def test_overhead_definition_from_table4():
+    name, cost_ms, lat_s, pct = open(os.path.join(GOLD, "table4_overhead.txt")).read().split("\n")[2].split()
+    assert round(float(cost_ms) / 1000 / float(lat_s) * 100, 1) == float(pct)
