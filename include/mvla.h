@@ -1,0 +1,193 @@
+/*
+ * mvla.h -- C ABI of the MI355X (gfx950) pruned-prefill library.
+ *
+ * The library runs the prefill of a LLaMA-2-shaped multi-visual-modal VLA
+ * backbone over the token sequence [2D image tokens | 3D point tokens |
+ * language tokens] (paper App. C "MVLA Models", Sec. 5.1 "Setup") with the
+ * token-pruning step placed inside it: attention-score salience of every
+ * visual token (Sec. 3.2, Eq. 3), a 2D:3D split of one keep budget by the
+ * modality mass ratio (Eq. 5), per-modality top-k selection, and compaction of
+ * the kept tokens, which alone go on to the later layers (Sec. 4.4, Eq. 10).
+ *
+ * Conventions that hold for every call unless a comment says otherwise:
+ *  - Every pointer marked "device" is a DEVICE pointer owned by the caller
+ *    (normally PyTorch tensor storage).  The library never allocates, frees or
+ *    keeps caller buffers; its only memory is the workspace handed to
+ *    mvla_create(), which the caller also owns and must keep alive until
+ *    mvla_destroy().
+ *  - Calls enqueue work on the context's HIP stream and return without waiting
+ *    for it.  Calls on one context are stream-ordered; two contexts sharing a
+ *    workspace must not run concurrently.
+ *  - Arguments are validated on the host before anything is launched.  On any
+ *    error nothing is launched and no output is written.
+ *  - Return value: MVLA_OK (0) or a negative mvla_status.
+ *  - Row-major everywhere; "bf16" is the 16-bit brain-float storage format.
+ */
+#ifndef MVLA_H_
+#define MVLA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    MVLA_OK = 0,
+    MVLA_EINVAL = -1,       /* null pointer, bad shape, bad alignment             */
+    MVLA_ENOMEM = -2,       /* workspace too small for the requested shape        */
+    MVLA_EHIP = -3,         /* HIP runtime / launch failure                       */
+    MVLA_EUNSUPPORTED = -4  /* shape outside what the kernels are built for       */
+} mvla_status;
+
+typedef struct mvla_ctx mvla_ctx; /* opaque */
+
+/* Library version, "major.minor.patch". */
+const char* mvla_version(void);
+/* Static, human-readable text for a status code. */
+const char* mvla_strerror(int code);
+
+/* Bytes of workspace needed for batches up to [B, S] with the given layer
+ * shape (D hidden, H heads, F MLP width) and up to n_query_tail scoring rows.
+ * Covers every call below.  Returns 0 for non-positive arguments. */
+size_t mvla_workspace_bytes(int B, int S, int D, int H, int F, int n_query_tail);
+
+/* Create a context bound to `device`, a borrowed HIP stream (NULL = the
+ * default stream) and a caller-owned device workspace (256-byte aligned).
+ * Enqueues a clear of the workspace's counter area on the stream. */
+int mvla_create(mvla_ctx** out, int device, void* hip_stream, void* workspace /*device*/,
+                size_t workspace_bytes);
+/* Rebind to another borrowed stream (previous work must have completed or be
+ * ordered before it by the caller). */
+int mvla_set_stream(mvla_ctx* ctx, void* hip_stream);
+/* Frees host-side state only.  Does not synchronise. */
+void mvla_destroy(mvla_ctx* ctx);
+
+/* ------------------------------------------------------------------------ */
+/* Pruning step                                                             */
+/* ------------------------------------------------------------------------ */
+
+/* Attention-score salience (Sec. 3.2: the attention matrix is partitioned by
+ * token modality and each visual token is scored by the L1 norm of its
+ * attention column, Eq. 3 / numerators of Eq. 5; probabilities are >= 0 so the
+ * norm is a sum; "avg" is the mean over the H*Nq rows):
+ *     sal[b, j] = (1 / (H*Nq)) * sum_h sum_q attn[b, h, q, j],   0 <= j < n_vis.
+ * attn: device, fp32 [B, H, Nq, S], rows already softmaxed; n_vis <= S.
+ * sal : device, fp32 [B, n_vis], fully overwritten.
+ * Summation order is fixed, so results are bit-reproducible run to run. */
+int mvla_salience(mvla_ctx* ctx, const float* attn, int B, int H, int Nq, int S, int n_vis,
+                  float* sal);
+
+/* Split the visual keep budget between modalities by salience mass (Eq. 5:
+ * m2 = |a_2D|_1 / (|a_2D|_1 + |a_3D|_1); Sec. 5.2: per-modality pruning
+ * rates).  Per sample, masses are summed in fp64;
+ *     K2 = floor(k_total*m2 + 0.5) clamped to [max(min2, k_total-n3), min(n2, k_total-min3)],
+ *     K3 = k_total - K2;   zero total mass -> m2 = n2/(n2+n3).
+ * sal : device, fp32 [B, n2+n3] (2D segment first).
+ * k2k3: device, int32 [B, 2] = (K2, K3).
+ * mass: device, fp32 [B, 2] = (m2, 1-m2), or NULL.
+ * Requires 0 <= k_total <= n2+n3, min2+min3 <= k_total, min2 <= n2, min3 <= n3. */
+int mvla_modality_budget(mvla_ctx* ctx, const float* sal, int B, int n2, int n3, int k_total,
+                         int min2, int min3, int32_t* k2k3, float* mass);
+
+/* Per-modality top-k (replaces the thresholded masks of Algorithm 1 by an
+ * exact budget; mask semantics as Eq. 10).  In the 2D segment keep the K2
+ * tokens of highest salience, in the 3D segment the K3 highest; equal scores:
+ * the lower index is kept; -0 equals +0.  Indices are written ascending, then
+ * all n_text language-token indices n2+n3 .. n2+n3+n_text-1 (never pruned).
+ * sal     : device, fp32 [B, n2+n3]; NaN/Inf are invalid input (result then
+ *           unspecified but in bounds).
+ * k2k3    : device, int32 [B, 2], each row summing to k_total with
+ *           0 <= K2 <= n2, 0 <= K3 <= n3 (as mvla_modality_budget writes);
+ *           rows violating this are clamped on the device.
+ * kept_idx: device, int32 [B, k_total + n_text], strictly increasing per row.
+ * n2, n3 <= 16384 each (segment staged in LDS), else MVLA_EUNSUPPORTED. */
+int mvla_select_topk(mvla_ctx* ctx, const float* sal, const int32_t* k2k3, int B, int n2, int n3,
+                     int n_text, int k_total, int32_t* kept_idx);
+
+/* Gather-compaction of the kept tokens (Sec. 4.4: tokens with mask 1 proceed
+ * to later layers, mask 0 are discarded):
+ *     h_out[b, i, :] = h[b, kept_idx[b, i], :],  pos_out[b, i] = pos[b, kept_idx[b, i]].
+ * h, h_out: device, bf16 [B, S, D] / [B, S_out, D]; D % 8 == 0; must not overlap.
+ * pos, pos_out: device, int32 [B, S] / [B, S_out].
+ * kept_idx: device, int32 [B, S_out]; values outside [0, S) are clamped into
+ * range on the device (never read out of bounds). */
+int mvla_compact(mvla_ctx* ctx, const void* h, const int32_t* pos, const int32_t* kept_idx, int B,
+                 int S, int S_out, int D, void* h_out, int32_t* pos_out);
+
+/* Salience, budget, selection and compaction in one call (same results as the
+ * four calls above in sequence; fewer launches).  sal, k2k3 are outputs too. */
+int mvla_prune_step(mvla_ctx* ctx, const float* attn, int H, int Nq, const void* h,
+                    const int32_t* pos, int B, int S, int D, int n2, int n3, int n_text,
+                    int k_total, int min2, int min3, float* sal, int32_t* k2k3,
+                    int32_t* kept_idx, void* h_out, int32_t* pos_out);
+
+/* ------------------------------------------------------------------------ */
+/* Backbone layer                                                           */
+/* ------------------------------------------------------------------------ */
+
+typedef struct {
+    int D;         /* hidden size, multiple of 64                              */
+    int H;         /* attention heads                                          */
+    int dh;        /* head dim: 64 or 128; H*dh == D                           */
+    int F;         /* MLP width, multiple of 64                                */
+    float rms_eps; /* RMSNorm epsilon                                          */
+} mvla_layer_cfg;
+
+/* Weights of one decoder layer; all device pointers, bf16 unless noted.
+ * Matrices are stored [out_features, in_features] row-major (y = x * W^T), so
+ * both GEMM operands are contiguous along the contraction axis.
+ *   wqkv     [3D, D]  rows 0..D-1 = query, D..2D-1 = key, 2D..3D-1 = value projection
+ *   wo       [D, D]
+ *   w_gateup [2F, D]  gate and up projections interleaved in blocks of 32 rows:
+ *                     rows 64*i .. 64*i+31 = gate rows 32*i .. 32*i+31,
+ *                     rows 64*i+32 .. 64*i+63 = up rows 32*i .. 32*i+31
+ *   w_down   [D, F]
+ *   g_attn, g_mlp [D] RMSNorm gains
+ *   rope_cos, rope_sin: fp32 [rope_len, dh/2]; row = position id (see
+ *                     mvla_rope_table); every pos value must be < rope_len. */
+typedef struct {
+    const void* wqkv;
+    const void* wo;
+    const void* w_gateup;
+    const void* w_down;
+    const void* g_attn;
+    const void* g_mlp;
+    const float* rope_cos;
+    const float* rope_sin;
+    int rope_len;
+} mvla_layer_weights;
+
+/* Fill a rotary table: cos/sin of pos * base^(-2i/dh), i < dh/2, evaluated in
+ * fp64 and rounded to fp32.  cos_out, sin_out: device fp32 [rope_len, dh/2]. */
+int mvla_rope_table(mvla_ctx* ctx, double base, int rope_len, int dh, float* cos_out,
+                    float* sin_out);
+
+/* One decoder layer of the backbone (App. C: LLaMA-2 7B; public layer maths:
+ * RMSNorm -> q,k,v -> rotate-half RoPE by position id -> causal softmax
+ * attention -> output projection + residual -> RMSNorm -> SiLU-gated MLP +
+ * residual).  Causality follows row order, RoPE follows pos (so kept tokens
+ * keep their original positions after compaction).
+ * x, y : device, bf16 [B, S, D]; y may alias x.
+ * pos  : device, int32 [B, S].
+ * n_query_tail > 0: additionally write the attention probabilities of the
+ * last n_query_tail rows (the language-token queries, Sec. 3.2) to
+ * probs_out (device, fp32 [B, H, n_query_tail, S]); key_bias (device, fp32
+ * [B, S] or NULL) is added to those scoring logits only, never to the layer's
+ * own attention.  n_query_tail == 0: key_bias/probs_out ignored. */
+int mvla_prefill_layer(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weights* w,
+                       const void* x, const int32_t* pos, int B, int S, void* y, int n_query_tail,
+                       const float* key_bias, float* probs_out);
+
+/* Scoring pass alone, for pruning before any layer has run: RMSNorm, query
+ * projection of the last n_query_tail rows, key projection of all rows, RoPE,
+ * causal softmax (+ key_bias).  Writes probs_out as above. */
+int mvla_score_only(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weights* w,
+                    const void* x, const int32_t* pos, int B, int S, int n_query_tail,
+                    const float* key_bias, float* probs_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MVLA_H_ */

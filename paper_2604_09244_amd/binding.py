@@ -1,0 +1,309 @@
+"""ctypes binding of libmvla.so: argument marshalling only.
+
+Every function here allocates outputs as torch tensors (device memory and
+streams are PyTorch's job), passes raw pointers to the C ABI declared in
+``include/mvla.h`` and raises on a non-zero status.  No step of the method is
+computed in Python, and there is no fallback: if the library is missing,
+``load()`` raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmvla.so")
+_lib = None
+
+EXPORTS = [
+    "mvla_version", "mvla_strerror", "mvla_workspace_bytes", "mvla_create", "mvla_set_stream",
+    "mvla_destroy", "mvla_salience", "mvla_modality_budget", "mvla_select_topk", "mvla_compact",
+    "mvla_prune_step", "mvla_rope_table", "mvla_prefill_layer", "mvla_score_only",
+]
+
+
+class MvlaError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = load().mvla_strerror(code).decode()
+        super().__init__(f"{where}: {msg} ({code})")
+
+
+class LayerCfg(C.Structure):
+    _fields_ = [("D", C.c_int), ("H", C.c_int), ("dh", C.c_int), ("F", C.c_int),
+                ("rms_eps", C.c_float)]
+
+
+class LayerWeightsC(C.Structure):
+    _fields_ = [("wqkv", C.c_void_p), ("wo", C.c_void_p), ("w_gateup", C.c_void_p),
+                ("w_down", C.c_void_p), ("g_attn", C.c_void_p), ("g_mlp", C.c_void_p),
+                ("rope_cos", C.c_void_p), ("rope_sin", C.c_void_p), ("rope_len", C.c_int)]
+
+
+def load() -> C.CDLL:
+    """Load the HIP library; raise if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} not found: build it first (python -m paper_2604_09244_amd.build)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i, f, sz = C.c_void_p, C.c_int, C.c_float, C.c_size_t
+    lib.mvla_version.restype = C.c_char_p
+    lib.mvla_strerror.restype = C.c_char_p
+    lib.mvla_strerror.argtypes = [i]
+    lib.mvla_workspace_bytes.restype = sz
+    lib.mvla_workspace_bytes.argtypes = [i] * 6
+    lib.mvla_create.argtypes = [C.POINTER(vp), i, vp, vp, sz]
+    lib.mvla_set_stream.argtypes = [vp, vp]
+    lib.mvla_destroy.argtypes = [vp]
+    lib.mvla_destroy.restype = None
+    lib.mvla_salience.argtypes = [vp, vp, i, i, i, i, i, vp]
+    lib.mvla_modality_budget.argtypes = [vp, vp, i, i, i, i, i, i, vp, vp]
+    lib.mvla_select_topk.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
+    lib.mvla_compact.argtypes = [vp, vp, vp, vp, i, i, i, i, vp, vp]
+    lib.mvla_prune_step.argtypes = [vp, vp, i, i, vp, vp, i, i, i, i, i, i, i, i, i, vp, vp, vp,
+                                    vp, vp]
+    lib.mvla_rope_table.argtypes = [vp, C.c_double, i, i, vp, vp]
+    lib.mvla_prefill_layer.argtypes = [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeightsC), vp, vp,
+                                       i, i, vp, i, vp, vp]
+    lib.mvla_score_only.argtypes = [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeightsC), vp, vp,
+                                    i, i, i, vp, vp]
+    _lib = lib
+    return lib
+
+
+def _check(rc: int, where: str) -> None:
+    if rc != 0:
+        raise MvlaError(rc, where)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else t.data_ptr()
+
+
+def _dev(t: torch.Tensor, dtype) -> torch.Tensor:
+    assert t.is_cuda and t.dtype == dtype and t.is_contiguous(), (t.device, t.dtype)
+    return t
+
+
+def pack_layer(w: Dict[str, torch.Tensor]) -> Dict[str, torch.Tensor]:
+    """Lay separate [out,in] bf16 matrices out the way the library reads them:
+    q|k|v rows stacked; gate/up rows interleaved in blocks of 32."""
+    F, D = w["w_gate"].shape
+    assert F % 32 == 0
+    gu = torch.stack([w["w_gate"].view(F // 32, 32, D), w["w_up"].view(F // 32, 32, D)], dim=1)
+    return dict(wqkv=torch.cat([w["wq"], w["wk"], w["wv"]], dim=0).contiguous(),
+                wo=w["wo"].contiguous(), w_gateup=gu.reshape(2 * F, D).contiguous(),
+                w_down=w["w_down"].contiguous(), g_attn=w["g_attn"].contiguous(),
+                g_mlp=w["g_mlp"].contiguous())
+
+
+class Context:
+    """Owns a device workspace and a library context bound to the current stream."""
+
+    def __init__(self, B: int, S: int, D: int, H: int, F: int, n_query_tail: int = 0,
+                 device: Optional[torch.device] = None):
+        lib = load()
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU visible: the HIP path has no CPU fallback")
+        self.device = torch.device("cuda", torch.cuda.current_device()) if device is None else device
+        nbytes = lib.mvla_workspace_bytes(B, S, D, H, F, n_query_tail)
+        if nbytes == 0:
+            raise MvlaError(-1, "mvla_workspace_bytes")
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self._h = C.c_void_p()
+        stream = torch.cuda.current_stream(self.device).cuda_stream
+        _check(lib.mvla_create(C.byref(self._h), self.device.index or 0, stream,
+                               self.workspace.data_ptr(), nbytes), "mvla_create")
+        self._rope = {}
+
+    def close(self):
+        if getattr(self, "_h", None) is not None and self._h.value:
+            load().mvla_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def handle(self):
+        return self._h
+
+    def set_stream(self, stream: torch.cuda.Stream):
+        _check(load().mvla_set_stream(self._h, stream.cuda_stream), "mvla_set_stream")
+
+    # ---- pruning step --------------------------------------------------
+    def salience(self, attn: torch.Tensor, n_vis: int, out: Optional[torch.Tensor] = None):
+        B, H, Nq, S = _dev(attn, torch.float32).shape
+        sal = torch.empty(B, n_vis, dtype=torch.float32, device=attn.device) if out is None else out
+        _check(load().mvla_salience(self._h, attn.data_ptr(), B, H, Nq, S, n_vis, sal.data_ptr()),
+               "mvla_salience")
+        return sal
+
+    def modality_budget(self, sal: torch.Tensor, n2: int, n3: int, k_total: int, min2: int = 0,
+                        min3: int = 0, want_mass: bool = False,
+                        out: Optional[torch.Tensor] = None):
+        B = _dev(sal, torch.float32).shape[0]
+        k2k3 = torch.empty(B, 2, dtype=torch.int32, device=sal.device) if out is None else out
+        mass = torch.empty(B, 2, dtype=torch.float32, device=sal.device) if want_mass else None
+        _check(load().mvla_modality_budget(self._h, sal.data_ptr(), B, n2, n3, k_total, min2, min3,
+                                           k2k3.data_ptr(), _ptr(mass)), "mvla_modality_budget")
+        return (k2k3, mass) if want_mass else k2k3
+
+    def select_topk(self, sal: torch.Tensor, k2k3: torch.Tensor, n2: int, n3: int, n_text: int,
+                    k_total: int, out: Optional[torch.Tensor] = None):
+        B = _dev(sal, torch.float32).shape[0]
+        _dev(k2k3, torch.int32)
+        kept = (torch.empty(B, k_total + n_text, dtype=torch.int32, device=sal.device)
+                if out is None else out)
+        _check(load().mvla_select_topk(self._h, sal.data_ptr(), k2k3.data_ptr(), B, n2, n3, n_text,
+                                       k_total, kept.data_ptr()), "mvla_select_topk")
+        return kept
+
+    def compact(self, h: torch.Tensor, pos: torch.Tensor, kept: torch.Tensor,
+                out: Optional[Sequence[torch.Tensor]] = None):
+        B, S, D = _dev(h, torch.bfloat16).shape
+        _dev(pos, torch.int32)
+        S_out = _dev(kept, torch.int32).shape[1]
+        if out is None:
+            h_out = torch.empty(B, S_out, D, dtype=torch.bfloat16, device=h.device)
+            pos_out = torch.empty(B, S_out, dtype=torch.int32, device=h.device)
+        else:
+            h_out, pos_out = out
+        _check(load().mvla_compact(self._h, h.data_ptr(), pos.data_ptr(), kept.data_ptr(), B, S,
+                                   S_out, D, h_out.data_ptr(), pos_out.data_ptr()), "mvla_compact")
+        return h_out, pos_out
+
+    def prune_step(self, attn, h, pos, n2, n3, n_text, k_total, min2=0, min3=0, out=None):
+        B, H, Nq, S = _dev(attn, torch.float32).shape
+        D = _dev(h, torch.bfloat16).shape[2]
+        dev = h.device
+        if out is None:
+            out = dict(sal=torch.empty(B, n2 + n3, dtype=torch.float32, device=dev),
+                       k2k3=torch.empty(B, 2, dtype=torch.int32, device=dev),
+                       kept_idx=torch.empty(B, k_total + n_text, dtype=torch.int32, device=dev),
+                       h=torch.empty(B, k_total + n_text, D, dtype=torch.bfloat16, device=dev),
+                       pos=torch.empty(B, k_total + n_text, dtype=torch.int32, device=dev))
+        _check(load().mvla_prune_step(self._h, attn.data_ptr(), H, Nq, h.data_ptr(),
+                                      _dev(pos, torch.int32).data_ptr(), B, S, D, n2, n3, n_text,
+                                      k_total, min2, min3, out["sal"].data_ptr(),
+                                      out["k2k3"].data_ptr(), out["kept_idx"].data_ptr(),
+                                      out["h"].data_ptr(), out["pos"].data_ptr()), "mvla_prune_step")
+        return out
+
+    # ---- backbone layer --------------------------------------------------
+    def rope_table(self, base: float, rope_len: int, dh: int):
+        key = (float(base), int(rope_len), int(dh))
+        if key not in self._rope:
+            c = torch.empty(rope_len, dh // 2, dtype=torch.float32, device=self.device)
+            s = torch.empty_like(c)
+            _check(load().mvla_rope_table(self._h, base, rope_len, dh, c.data_ptr(), s.data_ptr()),
+                   "mvla_rope_table")
+            self._rope[key] = (c, s)
+        return self._rope[key]
+
+    def layer_struct(self, packed: Dict[str, torch.Tensor], rope) -> LayerWeightsC:
+        for k in ("wqkv", "wo", "w_gateup", "w_down", "g_attn", "g_mlp"):
+            _dev(packed[k], torch.bfloat16)
+        c, s = rope
+        return LayerWeightsC(packed["wqkv"].data_ptr(), packed["wo"].data_ptr(),
+                             packed["w_gateup"].data_ptr(), packed["w_down"].data_ptr(),
+                             packed["g_attn"].data_ptr(), packed["g_mlp"].data_ptr(),
+                             c.data_ptr(), s.data_ptr(), c.shape[0])
+
+    def prefill_layer(self, cfg: LayerCfg, w: LayerWeightsC, x: torch.Tensor, pos: torch.Tensor,
+                      y: Optional[torch.Tensor] = None, n_query_tail: int = 0,
+                      key_bias: Optional[torch.Tensor] = None,
+                      probs_out: Optional[torch.Tensor] = None):
+        B, S, D = _dev(x, torch.bfloat16).shape
+        _dev(pos, torch.int32)
+        y = torch.empty_like(x) if y is None else y
+        if n_query_tail > 0 and probs_out is None:
+            probs_out = torch.empty(B, cfg.H, n_query_tail, S, dtype=torch.float32, device=x.device)
+        if key_bias is not None:
+            _dev(key_bias, torch.float32)
+        _check(load().mvla_prefill_layer(self._h, C.byref(cfg), C.byref(w), x.data_ptr(),
+                                         pos.data_ptr(), B, S, y.data_ptr(), n_query_tail,
+                                         _ptr(key_bias), _ptr(probs_out)), "mvla_prefill_layer")
+        return (y, probs_out) if n_query_tail > 0 else y
+
+    def score_only(self, cfg: LayerCfg, w: LayerWeightsC, x, pos, n_query_tail, key_bias=None,
+                   probs_out=None):
+        B, S, D = _dev(x, torch.bfloat16).shape
+        if probs_out is None:
+            probs_out = torch.empty(B, cfg.H, n_query_tail, S, dtype=torch.float32, device=x.device)
+        _check(load().mvla_score_only(self._h, C.byref(cfg), C.byref(w), x.data_ptr(),
+                                      _dev(pos, torch.int32).data_ptr(), B, S, n_query_tail,
+                                      _ptr(key_bias), probs_out.data_ptr()), "mvla_score_only")
+        return probs_out
+
+
+class PrefillPlan:
+    """Pre-allocated buffers and packed weights for one workload; ``run`` only
+    enqueues library calls (no allocation, no host synchronisation)."""
+
+    def __init__(self, ctx: Context, cfg: LayerCfg, layers: List[Dict[str, torch.Tensor]],
+                 B: int, n2: int, n3: int, nt: int, k_total: int, p: int,
+                 rope_base: float = 10000.0, rope_len: Optional[int] = None):
+        self.ctx, self.cfg, self.B, self.n2, self.n3, self.nt = ctx, cfg, B, n2, n3, nt
+        self.k_total, self.p, self.L = k_total, p, len(layers)
+        self.S, self.S_kept = n2 + n3 + nt, k_total + nt
+        dev = ctx.device
+        self.rope = ctx.rope_table(rope_base, rope_len or self.S, cfg.dh)
+        self.packed = layers
+        self.structs = [ctx.layer_struct(l, self.rope) for l in layers]
+        bf, i32, f32 = torch.bfloat16, torch.int32, torch.float32
+        self.h_full = [torch.empty(B, self.S, cfg.D, dtype=bf, device=dev) for _ in range(2)]
+        self.h_kept = [torch.empty(B, self.S_kept, cfg.D, dtype=bf, device=dev) for _ in range(2)]
+        self.probs = torch.empty(B, cfg.H, nt, self.S, dtype=f32, device=dev)
+        self.prune = dict(sal=torch.empty(B, n2 + n3, dtype=f32, device=dev),
+                          k2k3=torch.empty(B, 2, dtype=i32, device=dev),
+                          kept_idx=torch.empty(B, self.S_kept, dtype=i32, device=dev),
+                          h=self.h_kept[0],
+                          pos=torch.empty(B, self.S_kept, dtype=i32, device=dev))
+
+    def run(self, x: torch.Tensor, pos: torch.Tensor, key_bias: Optional[torch.Tensor] = None,
+            fused_prune: bool = True):
+        """Pruned prefill: p full layers, pruning step, L-p layers on kept tokens."""
+        ctx, cfg = self.ctx, self.cfg
+        h = x
+        for li in range(self.p):
+            tail = self.nt if li == self.p - 1 else 0
+            y = self.h_full[li & 1]
+            ctx.prefill_layer(cfg, self.structs[li], h, pos, y, tail, key_bias,
+                              self.probs if tail else None)
+            h = y
+        if self.p == 0:
+            ctx.score_only(cfg, self.structs[0], h, pos, self.nt, key_bias, self.probs)
+        if fused_prune:
+            ctx.prune_step(self.probs, h, pos, self.n2, self.n3, self.nt, self.k_total,
+                           out=self.prune)
+        else:
+            ctx.salience(self.probs, self.n2 + self.n3, out=self.prune["sal"])
+            ctx.modality_budget(self.prune["sal"], self.n2, self.n3, self.k_total,
+                                out=self.prune["k2k3"])
+            ctx.select_topk(self.prune["sal"], self.prune["k2k3"], self.n2, self.n3, self.nt,
+                            self.k_total, out=self.prune["kept_idx"])
+            ctx.compact(h, pos, self.prune["kept_idx"], out=(self.prune["h"], self.prune["pos"]))
+        h, pk = self.prune["h"], self.prune["pos"]
+        for li in range(self.p, self.L):
+            y = self.h_kept[(li - self.p + 1) & 1]
+            ctx.prefill_layer(cfg, self.structs[li], h, pk, y)
+            h = y
+        return h
+
+    def run_unpruned(self, x: torch.Tensor, pos: torch.Tensor):
+        h = x
+        for li in range(self.L):
+            y = self.h_full[li & 1]
+            self.ctx.prefill_layer(self.cfg, self.structs[li], h, pos, y)
+            h = y
+        return h

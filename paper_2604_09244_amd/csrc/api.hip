@@ -1,0 +1,261 @@
+// C ABI of the pruned-prefill library: argument validation, workspace carving
+// and launch sequencing.  No computation happens on the host.
+#include <new>
+
+#include "common.h"
+
+using namespace mvla;
+
+namespace {
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+struct LayerBuffers {
+    bf16_t *u, *qkv, *vt, *attn, *x1, *act;
+    int S_pad;
+    size_t bytes;  // total scratch needed
+};
+
+// carve the layer's intermediates out of the scratch area (base may be null: size query)
+LayerBuffers layer_buffers(char* base, int B, int S, int D, int F) {
+    LayerBuffers lb;
+    const size_t M = (size_t)B * S;
+    lb.S_pad = (S + 63) / 64 * 64;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        char* p = base ? base + off : nullptr;
+        off += align_up(bytes, 256);
+        return reinterpret_cast<bf16_t*>(p);
+    };
+    lb.u = take(M * D * 2);
+    lb.qkv = take(M * 3 * D * 2);
+    lb.vt = take((size_t)B * D * lb.S_pad * 2);
+    lb.attn = take(M * D * 2);
+    lb.x1 = take(M * D * 2);
+    lb.act = take(M * F * 2);
+    lb.bytes = off;
+    return lb;
+}
+
+int check_layer_args(const mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weights* w,
+                     const void* x, const int32_t* pos, int B, int S, int n_query_tail,
+                     const float* probs_out, bool need_full) {
+    if (!ctx || !cfg || !w || !x || !pos) return MVLA_EINVAL;
+    if (B <= 0 || S <= 0) return MVLA_EINVAL;
+    if (cfg->D <= 0 || cfg->H <= 0 || cfg->dh <= 0 || cfg->F <= 0) return MVLA_EINVAL;
+    if (cfg->H * cfg->dh != cfg->D) return MVLA_EINVAL;
+    if (cfg->dh != 64 && cfg->dh != 128) return MVLA_EUNSUPPORTED;
+    if (cfg->D % 64 != 0 || cfg->F % 64 != 0) return MVLA_EUNSUPPORTED;
+    if (!(cfg->rms_eps >= 0.f)) return MVLA_EINVAL;
+    if (!w->wqkv || !w->g_attn || !w->rope_cos || !w->rope_sin || w->rope_len <= 0)
+        return MVLA_EINVAL;
+    if (need_full && (!w->wo || !w->w_gateup || !w->w_down || !w->g_mlp)) return MVLA_EINVAL;
+    if (!aligned(x, 16) || !aligned(w->wqkv, 16) || !aligned(w->g_attn, 16) ||
+        !aligned(w->rope_cos, 16) || !aligned(w->rope_sin, 16))
+        return MVLA_EINVAL;
+    if (need_full && (!aligned(w->wo, 16) || !aligned(w->w_gateup, 16) ||
+                      !aligned(w->w_down, 16) || !aligned(w->g_mlp, 16)))
+        return MVLA_EINVAL;
+    if (n_query_tail < 0 || n_query_tail > S) return MVLA_EINVAL;
+    if (n_query_tail > 0 && !probs_out) return MVLA_EINVAL;
+    return MVLA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* mvla_version(void) { return "0.1.0"; }
+
+const char* mvla_strerror(int code) {
+    switch (code) {
+        case MVLA_OK: return "ok";
+        case MVLA_EINVAL: return "invalid argument (null pointer, shape or alignment)";
+        case MVLA_ENOMEM: return "workspace too small for this shape";
+        case MVLA_EHIP: return "HIP runtime or launch failure";
+        case MVLA_EUNSUPPORTED: return "shape not supported by the compiled kernels";
+        default: return "unknown status";
+    }
+}
+
+size_t mvla_workspace_bytes(int B, int S, int D, int H, int F, int n_query_tail) {
+    if (B <= 0 || S <= 0 || D <= 0 || H <= 0 || F <= 0 || n_query_tail < 0) return 0;
+    const size_t sal = salience_scratch_bytes(B, H, n_query_tail > 0 ? n_query_tail : 1, S);
+    const LayerBuffers lb = layer_buffers(nullptr, B, S, D, F);
+    return kCounterBytes + (sal > lb.bytes ? sal : lb.bytes) + 256;
+}
+
+int mvla_create(mvla_ctx** out, int device, void* hip_stream, void* workspace,
+                size_t workspace_bytes) {
+    if (!out || !workspace || device < 0) return MVLA_EINVAL;
+    if (!aligned(workspace, 256) || workspace_bytes < kCounterBytes + 256) return MVLA_EINVAL;
+    MVLA_HIP_CHECK(hipSetDevice(device));
+    mvla_ctx* c = new (std::nothrow) mvla_ctx;
+    if (!c) return MVLA_ENOMEM;
+    c->device = device;
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    c->ws = static_cast<char*>(workspace);
+    c->ws_bytes = workspace_bytes;
+    c->counters = reinterpret_cast<uint32_t*>(c->ws);
+    c->scratch = c->ws + kCounterBytes;
+    c->scratch_bytes = workspace_bytes - kCounterBytes;
+    if (hipMemsetAsync(c->counters, 0, kCounterBytes, c->stream) != hipSuccess) {
+        delete c;
+        return MVLA_EHIP;
+    }
+    *out = c;
+    return MVLA_OK;
+}
+
+int mvla_set_stream(mvla_ctx* ctx, void* hip_stream) {
+    if (!ctx) return MVLA_EINVAL;
+    ctx->stream = static_cast<hipStream_t>(hip_stream);
+    return MVLA_OK;
+}
+
+void mvla_destroy(mvla_ctx* ctx) { delete ctx; }
+
+// ---------------------------------------------------------------------------
+int mvla_salience(mvla_ctx* ctx, const float* attn, int B, int H, int Nq, int S, int n_vis,
+                  float* sal) {
+    if (!ctx || !attn || !sal) return MVLA_EINVAL;
+    if (B <= 0 || H <= 0 || Nq <= 0 || S <= 0 || n_vis <= 0 || n_vis > S) return MVLA_EINVAL;
+    if (!aligned(attn, 4) || !aligned(sal, 4)) return MVLA_EINVAL;
+    if (salience_scratch_bytes(B, H, Nq, n_vis) > ctx->scratch_bytes) return MVLA_ENOMEM;
+    return launch_salience(attn, B, H, Nq, S, n_vis, sal, reinterpret_cast<float*>(ctx->scratch),
+                           ctx->counters, ctx->stream);
+}
+
+int mvla_modality_budget(mvla_ctx* ctx, const float* sal, int B, int n2, int n3, int k_total,
+                         int min2, int min3, int32_t* k2k3, float* mass) {
+    if (!ctx || !sal || !k2k3) return MVLA_EINVAL;
+    if (B <= 0 || n2 < 0 || n3 < 0 || n2 + n3 <= 0) return MVLA_EINVAL;
+    if (k_total < 0 || k_total > n2 + n3) return MVLA_EINVAL;
+    if (min2 < 0 || min3 < 0 || min2 > n2 || min3 > n3 || min2 + min3 > k_total)
+        return MVLA_EINVAL;
+    return launch_budget(sal, B, n2, n3, k_total, min2, min3, k2k3, mass, ctx->stream);
+}
+
+int mvla_select_topk(mvla_ctx* ctx, const float* sal, const int32_t* k2k3, int B, int n2, int n3,
+                     int n_text, int k_total, int32_t* kept_idx) {
+    if (!ctx || !sal || !k2k3 || !kept_idx) return MVLA_EINVAL;
+    if (B <= 0 || n2 < 0 || n3 < 0 || n2 + n3 <= 0 || n_text < 0) return MVLA_EINVAL;
+    if (k_total < 0 || k_total > n2 + n3) return MVLA_EINVAL;
+    return launch_select(sal, k2k3, B, n2, n3, n_text, k_total, kept_idx, ctx->stream);
+}
+
+int mvla_compact(mvla_ctx* ctx, const void* h, const int32_t* pos, const int32_t* kept_idx, int B,
+                 int S, int S_out, int D, void* h_out, int32_t* pos_out) {
+    if (!ctx || !h || !pos || !kept_idx || !h_out || !pos_out) return MVLA_EINVAL;
+    if (B <= 0 || S <= 0 || S_out < 0 || S_out > S || D <= 0 || D % 8 != 0) return MVLA_EINVAL;
+    if (!aligned(h, 16) || !aligned(h_out, 16)) return MVLA_EINVAL;
+    {   // overlap check of the two hidden-state buffers
+        const char* a = static_cast<const char*>(h);
+        const char* b = static_cast<const char*>(h_out);
+        const size_t na = (size_t)B * S * D * 2, nb = (size_t)B * S_out * D * 2;
+        if (a < b + nb && b < a + na) return MVLA_EINVAL;
+    }
+    return launch_compact(static_cast<const bf16_t*>(h), pos, kept_idx, B, S, S_out, D,
+                          static_cast<bf16_t*>(h_out), pos_out, ctx->stream);
+}
+
+int mvla_prune_step(mvla_ctx* ctx, const float* attn, int H, int Nq, const void* h,
+                    const int32_t* pos, int B, int S, int D, int n2, int n3, int n_text,
+                    int k_total, int min2, int min3, float* sal, int32_t* k2k3,
+                    int32_t* kept_idx, void* h_out, int32_t* pos_out) {
+    if (n2 < 0 || n3 < 0 || n_text < 0 || S != n2 + n3 + n_text) return MVLA_EINVAL;
+    // validate everything before the first launch
+    if (!ctx || !attn || !sal || !k2k3 || !kept_idx || !h || !pos || !h_out || !pos_out)
+        return MVLA_EINVAL;
+    if (B <= 0 || H <= 0 || Nq <= 0 || n2 + n3 <= 0 || D <= 0 || D % 8 != 0) return MVLA_EINVAL;
+    if (k_total < 0 || k_total > n2 + n3) return MVLA_EINVAL;
+    if (min2 < 0 || min3 < 0 || min2 > n2 || min3 > n3 || min2 + min3 > k_total)
+        return MVLA_EINVAL;
+    if (!aligned(h, 16) || !aligned(h_out, 16)) return MVLA_EINVAL;
+    if (n2 > 16384 || n3 > 16384) return MVLA_EUNSUPPORTED;
+    if (salience_scratch_bytes(B, H, Nq, n2 + n3) > ctx->scratch_bytes) return MVLA_ENOMEM;
+    int rc = mvla_salience(ctx, attn, B, H, Nq, S, n2 + n3, sal);
+    if (rc) return rc;
+    rc = mvla_modality_budget(ctx, sal, B, n2, n3, k_total, min2, min3, k2k3, nullptr);
+    if (rc) return rc;
+    rc = mvla_select_topk(ctx, sal, k2k3, B, n2, n3, n_text, k_total, kept_idx);
+    if (rc) return rc;
+    return mvla_compact(ctx, h, pos, kept_idx, B, S, k_total + n_text, D, h_out, pos_out);
+}
+
+// ---------------------------------------------------------------------------
+int mvla_rope_table(mvla_ctx* ctx, double base, int rope_len, int dh, float* cos_out,
+                    float* sin_out) {
+    if (!ctx || !cos_out || !sin_out) return MVLA_EINVAL;
+    if (rope_len <= 0 || dh <= 0 || dh % 2 != 0 || !(base > 0.0)) return MVLA_EINVAL;
+    return launch_rope_table(base, rope_len, dh, cos_out, sin_out, ctx->stream);
+}
+
+int mvla_prefill_layer(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weights* w,
+                       const void* x, const int32_t* pos, int B, int S, void* y, int n_query_tail,
+                       const float* key_bias, float* probs_out) {
+    int rc = check_layer_args(ctx, cfg, w, x, pos, B, S, n_query_tail, probs_out, true);
+    if (rc) return rc;
+    if (!y || !aligned(y, 16)) return MVLA_EINVAL;
+    const int D = cfg->D, H = cfg->H, dh = cfg->dh, F = cfg->F;
+    if ((size_t)B * S > (size_t)INT32_MAX / 4) return MVLA_EUNSUPPORTED;
+    const LayerBuffers lb = layer_buffers(ctx->scratch, B, S, D, F);
+    if (lb.bytes > ctx->scratch_bytes) return MVLA_ENOMEM;
+    const int M = B * S;
+    hipStream_t st = ctx->stream;
+    const bf16_t* xin = static_cast<const bf16_t*>(x);
+    const bf16_t* wqkv = static_cast<const bf16_t*>(w->wqkv);
+
+    rc = launch_rmsnorm(xin, static_cast<const bf16_t*>(w->g_attn), M, D, cfg->rms_eps, lb.u, st);
+    if (rc) return rc;
+    rc = launch_gemm(lb.u, D, wqkv, M, 3 * D, D, lb.qkv, 3 * D, nullptr, 0, EPI_STORE, st);
+    if (rc) return rc;
+    rc = launch_rope_split(lb.qkv, pos, w->rope_cos, w->rope_sin, w->rope_len, B, S, H, dh,
+                           lb.S_pad, lb.vt, st);
+    if (rc) return rc;
+    if (n_query_tail > 0) {
+        rc = launch_score_probs(lb.qkv, 3 * D, lb.qkv + D, 3 * D, key_bias, B, S, H, dh,
+                                n_query_tail, probs_out, st);
+        if (rc) return rc;
+    }
+    rc = launch_attention(lb.qkv, lb.qkv + D, 3 * D, lb.vt, lb.S_pad, B, S, H, dh, lb.attn, D, st);
+    if (rc) return rc;
+    rc = launch_gemm(lb.attn, D, static_cast<const bf16_t*>(w->wo), M, D, D, lb.x1, D, xin, D,
+                     EPI_RESIDUAL, st);
+    if (rc) return rc;
+    rc = launch_rmsnorm(lb.x1, static_cast<const bf16_t*>(w->g_mlp), M, D, cfg->rms_eps, lb.u, st);
+    if (rc) return rc;
+    rc = launch_gemm(lb.u, D, static_cast<const bf16_t*>(w->w_gateup), M, 2 * F, D, lb.act, F,
+                     nullptr, 0, EPI_SILU_MUL, st);
+    if (rc) return rc;
+    return launch_gemm(lb.act, F, static_cast<const bf16_t*>(w->w_down), M, D, F,
+                       static_cast<bf16_t*>(y), D, lb.x1, D, EPI_RESIDUAL, st);
+}
+
+int mvla_score_only(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weights* w,
+                    const void* x, const int32_t* pos, int B, int S, int n_query_tail,
+                    const float* key_bias, float* probs_out) {
+    int rc = check_layer_args(ctx, cfg, w, x, pos, B, S, n_query_tail, probs_out, false);
+    if (rc) return rc;
+    if (n_query_tail <= 0) return MVLA_EINVAL;
+    const int D = cfg->D, H = cfg->H, dh = cfg->dh;
+    if ((size_t)B * S > (size_t)INT32_MAX / 4) return MVLA_EUNSUPPORTED;
+    const LayerBuffers lb = layer_buffers(ctx->scratch, B, S, D, cfg->F);
+    if (lb.bytes > ctx->scratch_bytes) return MVLA_ENOMEM;
+    const int M = B * S;
+    hipStream_t st = ctx->stream;
+    rc = launch_rmsnorm(static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(w->g_attn), M, D,
+                        cfg->rms_eps, lb.u, st);
+    if (rc) return rc;
+    // query and key projections only (first 2D rows of wqkv), stored with row stride 2D
+    rc = launch_gemm(lb.u, D, static_cast<const bf16_t*>(w->wqkv), M, 2 * D, D, lb.qkv, 2 * D,
+                     nullptr, 0, EPI_STORE, st);
+    if (rc) return rc;
+    rc = launch_rope_split(lb.qkv, pos, w->rope_cos, w->rope_sin, w->rope_len, B, S, H, dh,
+                           lb.S_pad, nullptr, st);
+    if (rc) return rc;
+    return launch_score_probs(lb.qkv, 2 * D, lb.qkv + D, 2 * D, key_bias, B, S, H, dh,
+                              n_query_tail, probs_out, st);
+}
+
+}  // extern "C"

@@ -1,0 +1,69 @@
+// Shared host-side declarations of the gfx950 pruned-prefill library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "mvla.h"
+
+typedef uint16_t bf16_t;  // raw bf16 storage
+
+struct mvla_ctx {
+    int device;
+    hipStream_t stream;
+    char* ws;          // caller-owned device workspace
+    size_t ws_bytes;
+    // fixed areas at the head of the workspace
+    uint32_t* counters;  // kCounterWords block-arrival counters (kept at zero between calls)
+    char* scratch;       // everything after the counter area
+    size_t scratch_bytes;
+};
+
+constexpr int kCounterWords = 16384;
+constexpr size_t kCounterBytes = size_t(kCounterWords) * 4;
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+#define MVLA_HIP_CHECK(expr)                       \
+    do {                                           \
+        hipError_t e_ = (expr);                    \
+        if (e_ != hipSuccess) return MVLA_EHIP;    \
+    } while (0)
+
+// ---- launchers implemented in the .hip files (all enqueue on `st`) ----------
+namespace mvla {
+
+// prune_kernels.hip
+size_t salience_scratch_bytes(int B, int H, int Nq, int n_vis);
+int launch_salience(const float* attn, int B, int H, int Nq, int S, int n_vis, float* sal,
+                    float* partial, uint32_t* counters, hipStream_t st);
+int launch_budget(const float* sal, int B, int n2, int n3, int k_total, int min2, int min3,
+                  int32_t* k2k3, float* mass, hipStream_t st);
+int launch_select(const float* sal, const int32_t* k2k3, int B, int n2, int n3, int n_text,
+                  int k_total, int32_t* kept_idx, hipStream_t st);
+int launch_compact(const bf16_t* h, const int32_t* pos, const int32_t* kept_idx, int B, int S,
+                   int S_out, int D, bf16_t* h_out, int32_t* pos_out, hipStream_t st);
+
+// layer_kernels.hip
+int launch_rmsnorm(const bf16_t* x, const bf16_t* gain, int M, int D, float eps, bf16_t* out,
+                   hipStream_t st);
+int launch_rope_table(double base, int rope_len, int dh, float* c, float* s, hipStream_t st);
+// q,k rotated in place inside qkv [B*S, 3D]; v transposed to vt [B, H, dh, S_pad]
+int launch_rope_split(bf16_t* qkv, const int32_t* pos, const float* rc, const float* rs,
+                      int rope_len, int B, int S, int H, int dh, int S_pad, bf16_t* vt,
+                      hipStream_t st);
+// scoring probabilities of the last nq rows: probs [B,H,nq,S] fp32
+int launch_score_probs(const bf16_t* q, int q_row_stride, const bf16_t* k, int k_row_stride,
+                       const float* key_bias, int B, int S, int H, int dh, int nq, float* probs,
+                       hipStream_t st);
+
+// gemm.hip:  C[M,N] = A[M,K] * W[N,K]^T  (bf16 in, fp32 accumulate)
+enum GemmEpilogue { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_SILU_MUL = 2 };
+int launch_gemm(const bf16_t* A, int lda, const bf16_t* W, int M, int N, int K, bf16_t* C, int ldc,
+                const bf16_t* R, int ldr, int epilogue, hipStream_t st);
+
+// attention.hip: causal flash attention; q,k rows inside qkv (row stride ldqkv), vt [B,H,dh,S_pad]
+int launch_attention(const bf16_t* q, const bf16_t* k, int ldqkv, const bf16_t* vt, int S_pad,
+                     int B, int S, int H, int dh, bf16_t* out, int ldo, hipStream_t st);
+
+}  // namespace mvla

@@ -1,0 +1,379 @@
+// Pruning-step kernels for gfx950: attention-column salience, modality budget,
+// per-modality top-k selection, gather-compaction.  All are bandwidth- or
+// latency-bound; none uses floating-point atomics, so every result is
+// reproducible bit for bit.
+#include "common.h"
+
+namespace mvla {
+
+// ---------------------------------------------------------------------------
+// Salience (paper Sec. 3.2, Eq. 3): column sums of the language-query
+// attention rows over the visual columns, divided by the number of rows.
+//
+// A wave is laid out as 4 row-groups x 16 lanes; a lane owns VEC consecutive
+// columns, so one row-group reads 16*VEC consecutive floats of one row
+// (coalesced 16-byte loads when VEC == 4).  Row-groups are folded with two
+// wavefront shuffles, the block's four waves through LDS, and the blocks that
+// share a column chunk through a partial buffer summed in fixed order by
+// whichever of them arrives last (integer arrival counter, no float atomics).
+// ---------------------------------------------------------------------------
+constexpr int SAL_THREADS = 256;
+constexpr int SAL_LPR = 16;                        // lanes per row-group
+constexpr int SAL_GROUPS = SAL_THREADS / SAL_LPR;  // 16 row-groups per block
+
+template <int VEC>
+__global__ __launch_bounds__(SAL_THREADS) void salience_kernel(
+    const float* __restrict__ attn, int R, int S, int n_vis, int rows_per_split, int n_split,
+    float inv_rows, float* __restrict__ sal, float* __restrict__ partial,
+    uint32_t* __restrict__ counters) {
+    constexpr int CW = SAL_LPR * VEC;  // columns per chunk
+    const int chunk = blockIdx.x, split = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x;
+    const int lane16 = tid % SAL_LPR;
+    const int group = tid / SAL_LPR;
+    const int col0 = chunk * CW + lane16 * VEC;
+    const int r_begin = split * rows_per_split;
+    const int r_end = min(R, r_begin + rows_per_split);
+    const float* base = attn + (size_t)b * R * S;
+
+    float acc[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
+
+    if (VEC == 4) {
+        if (col0 + 3 < n_vis) {
+            int r = r_begin + group;
+            // two independent loads in flight per lane
+            for (; r + SAL_GROUPS < r_end; r += 2 * SAL_GROUPS) {
+                const float4 a = *reinterpret_cast<const float4*>(base + (size_t)r * S + col0);
+                const float4 c =
+                    *reinterpret_cast<const float4*>(base + (size_t)(r + SAL_GROUPS) * S + col0);
+                acc[0] += a.x; acc[1] += a.y; acc[2] += a.z; acc[3] += a.w;
+                acc[0] += c.x; acc[1] += c.y; acc[2] += c.z; acc[3] += c.w;
+            }
+            for (; r < r_end; r += SAL_GROUPS) {
+                const float4 a = *reinterpret_cast<const float4*>(base + (size_t)r * S + col0);
+                acc[0] += a.x; acc[1] += a.y; acc[2] += a.z; acc[3] += a.w;
+            }
+        } else {
+            for (int r = r_begin + group; r < r_end; r += SAL_GROUPS)
+#pragma unroll
+                for (int v = 0; v < VEC; ++v)
+                    if (col0 + v < n_vis) acc[v] += base[(size_t)r * S + col0 + v];
+        }
+    } else {
+        for (int r = r_begin + group; r < r_end; r += SAL_GROUPS)
+#pragma unroll
+            for (int v = 0; v < VEC; ++v)
+                if (col0 + v < n_vis) acc[v] += base[(size_t)r * S + col0 + v];
+    }
+
+    // fold the wave's 4 row-groups (lanes l, l^16, l^32, l^48 own the same columns)
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) {
+        acc[v] += __shfl_xor(acc[v], 16);
+        acc[v] += __shfl_xor(acc[v], 32);
+    }
+    __shared__ float red[SAL_THREADS / 64][CW];
+    __shared__ int is_last;
+    const int wave = tid / 64, lane = tid % 64;
+    if (lane < SAL_LPR) {
+#pragma unroll
+        for (int v = 0; v < VEC; ++v) red[wave][lane * VEC + v] = acc[v];
+    }
+    __syncthreads();
+    float tot = 0.f;
+    const int c = chunk * CW + tid;
+    if (tid < CW) {
+#pragma unroll
+        for (int w = 0; w < SAL_THREADS / 64; ++w) tot += red[w][tid];
+    }
+    if (n_split == 1) {
+        if (tid < CW && c < n_vis) sal[(size_t)b * n_vis + c] = tot * inv_rows;
+        return;
+    }
+    // several blocks share this column chunk: publish, last arrival finishes
+    float* pslot = partial + ((size_t)(b * gridDim.x + chunk) * n_split) * CW;
+    if (tid < CW) pslot[(size_t)split * CW + tid] = tot;
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t* ctr = counters + (b * gridDim.x + chunk);
+        const uint32_t prev =
+            __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        is_last = (prev == (uint32_t)(n_split - 1));
+        if (is_last) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (!is_last) return;
+    __threadfence();
+    if (tid < CW && c < n_vis) {
+        float s = 0.f;
+        for (int i = 0; i < n_split; ++i)
+            s += __hip_atomic_load(&pslot[(size_t)i * CW + tid], __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+        sal[(size_t)b * n_vis + c] = s * inv_rows;
+    }
+}
+
+static void salience_shape(int B, int R, int n_vis, int vec, int* chunks, int* n_split,
+                           int* rows_per_split) {
+    const int cw = SAL_LPR * vec;
+    *chunks = (n_vis + cw - 1) / cw;
+    // aim for ~2048 blocks, at least 2 passes of the 16 row-groups each
+    long blocks = (long)B * *chunks;
+    int split = (int)((2048 + blocks - 1) / blocks);
+    const int max_split = (R + 2 * SAL_GROUPS - 1) / (2 * SAL_GROUPS);
+    if (split > max_split) split = max_split;
+    if (split < 1) split = 1;
+    *rows_per_split = (R + split - 1) / split;
+    *n_split = (R + *rows_per_split - 1) / *rows_per_split;
+}
+
+size_t salience_scratch_bytes(int B, int H, int Nq, int n_vis) {
+    // worst case over VEC in {1,4}: chunks*CW <= n_vis + 63, n_split <= R/32 + 1
+    const size_t R = (size_t)H * Nq;
+    return align_up((size_t)B * (size_t)(n_vis + 64) * (R / (2 * SAL_GROUPS) + 2) * 4, 256);
+}
+
+int launch_salience(const float* attn, int B, int H, int Nq, int S, int n_vis, float* sal,
+                    float* partial, uint32_t* counters, hipStream_t st) {
+    const int R = H * Nq;
+    const bool vec4 = (S % 4 == 0) && ((reinterpret_cast<uintptr_t>(attn) & 15) == 0);
+    int chunks, n_split, rps;
+    salience_shape(B, R, n_vis, vec4 ? 4 : 1, &chunks, &n_split, &rps);
+    if ((long)B * chunks > kCounterWords) return MVLA_EUNSUPPORTED;
+    dim3 grid(chunks, n_split, B);
+    const float inv_rows = 1.0f / (float)R;
+    if (vec4)
+        hipLaunchKernelGGL(salience_kernel<4>, grid, dim3(SAL_THREADS), 0, st, attn, R, S, n_vis,
+                           rps, n_split, inv_rows, sal, partial, counters);
+    else
+        hipLaunchKernelGGL(salience_kernel<1>, grid, dim3(SAL_THREADS), 0, st, attn, R, S, n_vis,
+                           rps, n_split, inv_rows, sal, partial, counters);
+    MVLA_HIP_CHECK(hipGetLastError());
+    return MVLA_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Modality budget (paper Eq. 5): fp64 masses per sample, integer split.
+// ---------------------------------------------------------------------------
+constexpr int BUD_THREADS = 256;
+
+__device__ inline double block_sum_f64(double v, double* sh) {
+    // fixed-shape tree: wave shuffle then 4 partials in LDS
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    double t = 0.0;
+    for (int w = 0; w < BUD_THREADS / 64; ++w) t += sh[w];
+    return t;
+}
+
+__device__ inline void budget_split(double a2, double a3, int n2, int n3, int k_total, int min2,
+                                    int min3, int* k2_out, double* m2_out) {
+    const double tot = a2 + a3;
+    const double m2 = tot > 0.0 ? a2 / tot : (double)n2 / (double)(n2 + n3);
+    int k2 = (int)floor((double)k_total * m2 + 0.5);
+    const int lo = max(min2, k_total - n3);
+    const int hi = min(n2, k_total - min3);
+    k2 = min(max(k2, lo), hi);
+    *k2_out = k2;
+    *m2_out = m2;
+}
+
+__global__ __launch_bounds__(BUD_THREADS) void budget_kernel(const float* __restrict__ sal, int n2,
+                                                             int n3, int k_total, int min2,
+                                                             int min3, int32_t* __restrict__ k2k3,
+                                                             float* __restrict__ mass) {
+    __shared__ double sh[BUD_THREADS / 64];
+    const int b = blockIdx.x;
+    const float* s = sal + (size_t)b * (n2 + n3);
+    double a2 = 0.0, a3 = 0.0;
+    for (int i = threadIdx.x; i < n2; i += BUD_THREADS) a2 += (double)s[i];
+    for (int i = threadIdx.x; i < n3; i += BUD_THREADS) a3 += (double)s[n2 + i];
+    a2 = block_sum_f64(a2, sh);
+    a3 = block_sum_f64(a3, sh);
+    if (threadIdx.x == 0) {
+        int k2;
+        double m2;
+        budget_split(a2, a3, n2, n3, k_total, min2, min3, &k2, &m2);
+        k2k3[2 * b] = k2;
+        k2k3[2 * b + 1] = k_total - k2;
+        if (mass) {
+            mass[2 * b] = (float)m2;
+            mass[2 * b + 1] = (float)(1.0 - m2);
+        }
+    }
+}
+
+int launch_budget(const float* sal, int B, int n2, int n3, int k_total, int min2, int min3,
+                  int32_t* k2k3, float* mass, hipStream_t st) {
+    hipLaunchKernelGGL(budget_kernel, dim3(B), dim3(BUD_THREADS), 0, st, sal, n2, n3, k_total,
+                       min2, min3, k2k3, mass);
+    MVLA_HIP_CHECK(hipGetLastError());
+    return MVLA_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Per-modality top-k.  One workgroup per (sample, segment); the segment's
+// scores sit in LDS as order-preserving 32-bit keys.  Four 8-bit radix passes
+// find the K-th largest key T exactly; tokens with key > T are kept, and of
+// those with key == T the lowest-indexed (K - #greater).  Each thread owns a
+// contiguous index range, so a block prefix sum of its keep counts gives
+// output slots that are already in ascending index order -- no sort.
+// ---------------------------------------------------------------------------
+constexpr int SEL_THREADS = 256;
+constexpr int SEL_MAX_N = 16384;
+
+__device__ inline uint32_t sal_key(float x) {
+    uint32_t u = __float_as_uint(x);
+    if (u == 0x80000000u) u = 0u;  // -0 ranks with +0
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// inclusive prefix sum over SEL_THREADS values (one per thread), result per thread
+__device__ inline uint32_t block_scan_incl(uint32_t v, uint32_t* wsum) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t t = __shfl_up(v, o);
+        if (lane >= o) v += t;
+    }
+    __syncthreads();
+    if (lane == 63) wsum[wave] = v;
+    __syncthreads();
+    uint32_t add = 0;
+    for (int w = 0; w < wave; ++w) add += wsum[w];
+    return v + add;
+}
+
+__device__ void select_segment(const float* __restrict__ seg, int n, int k, int idx_offset,
+                               int32_t* __restrict__ out, uint32_t* keys /*LDS [n]*/,
+                               uint32_t* hist /*LDS [256]*/, uint32_t* wsum /*LDS [4]*/,
+                               uint32_t* bcast /*LDS [4]*/) {
+    const int tid = threadIdx.x;
+    for (int i = tid; i < n; i += SEL_THREADS) keys[i] = sal_key(seg[i]);
+    if (k <= 0) return;
+    if (k > n) k = n;
+    uint32_t prefix = 0, prefix_mask = 0;
+    uint32_t remaining = (uint32_t)k;  // rank (1-based, from the top) of T among matching keys
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        hist[tid] = 0;
+        __syncthreads();
+        for (int i = tid; i < n; i += SEL_THREADS) {
+            const uint32_t key = keys[i];
+            if ((key & prefix_mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        // suffix counts from the top digit down: thread t looks at digit 255-t
+        const uint32_t mine = hist[255 - tid];
+        const uint32_t incl = block_scan_incl(mine, wsum);
+        const uint32_t excl = incl - mine;
+        if (excl < remaining && remaining <= incl) {
+            bcast[0] = (uint32_t)(255 - tid);
+            bcast[1] = remaining - excl;
+        }
+        __syncthreads();
+        prefix |= bcast[0] << shift;
+        prefix_mask |= 255u << shift;
+        remaining = bcast[1];
+        __syncthreads();
+    }
+    const uint32_t T = prefix;
+    const uint32_t need_eq = remaining;  // how many keys equal to T are kept
+    const int per = (n + SEL_THREADS - 1) / SEL_THREADS;
+    const int i0 = min(n, tid * per), i1 = min(n, i0 + per);
+    uint32_t gt = 0, eq = 0;
+    for (int i = i0; i < i1; ++i) {
+        const uint32_t key = keys[i];
+        gt += key > T;
+        eq += key == T;
+    }
+    const uint32_t gt_before = block_scan_incl(gt, wsum) - gt;
+    const uint32_t eq_before = block_scan_incl(eq, wsum) - eq;
+    uint32_t eq_rank = eq_before;
+    uint32_t slot = gt_before + min(eq_before, need_eq);
+    for (int i = i0; i < i1; ++i) {
+        const uint32_t key = keys[i];
+        bool keep = key > T;
+        if (key == T) {
+            keep = eq_rank < need_eq;
+            ++eq_rank;
+        }
+        if (keep) out[slot++] = idx_offset + i;
+    }
+}
+
+__global__ __launch_bounds__(SEL_THREADS) void select_kernel(const float* __restrict__ sal,
+                                                             const int32_t* __restrict__ k2k3,
+                                                             int n2, int n3, int n_text,
+                                                             int k_total,
+                                                             int32_t* __restrict__ kept_idx) {
+    extern __shared__ uint32_t keys[];
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t wsum[SEL_THREADS / 64];
+    __shared__ uint32_t bcast[4];
+    const int b = blockIdx.y, which = blockIdx.x;
+    int32_t* row = kept_idx + (size_t)b * (k_total + n_text);
+    // clamp a malformed budget row into the feasible range
+    int k2 = k2k3[2 * b];
+    k2 = min(max(k2, max(0, k_total - n3)), min(n2, k_total));
+    const int k3 = k_total - k2;
+    if (which == 0) {
+        select_segment(sal + (size_t)b * (n2 + n3), n2, k2, 0, row, keys, hist, wsum, bcast);
+    } else if (which == 1) {
+        select_segment(sal + (size_t)b * (n2 + n3) + n2, n3, k3, n2, row + k2, keys, hist, wsum,
+                       bcast);
+    } else {
+        for (int i = threadIdx.x; i < n_text; i += SEL_THREADS) row[k_total + i] = n2 + n3 + i;
+    }
+}
+
+int launch_select(const float* sal, const int32_t* k2k3, int B, int n2, int n3, int n_text,
+                  int k_total, int32_t* kept_idx, hipStream_t st) {
+    if (n2 > SEL_MAX_N || n3 > SEL_MAX_N) return MVLA_EUNSUPPORTED;
+    const size_t lds = (size_t)max(max(n2, n3), 1) * 4;
+    hipLaunchKernelGGL(select_kernel, dim3(3, B), dim3(SEL_THREADS), lds, st, sal, k2k3, n2, n3,
+                       n_text, k_total, kept_idx);
+    MVLA_HIP_CHECK(hipGetLastError());
+    return MVLA_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Gather-compaction (paper Sec. 4.4 / Eq. 10): copy kept rows and their
+// position ids.  One workgroup per output row, 16 bytes per lane per access.
+// ---------------------------------------------------------------------------
+constexpr int CMP_THREADS = 256;
+
+__global__ __launch_bounds__(CMP_THREADS) void compact_kernel(
+    const uint4* __restrict__ h, const int32_t* __restrict__ pos,
+    const int32_t* __restrict__ kept_idx, int S, int S_out, int row_vec /* D*2/16 */,
+    uint4* __restrict__ h_out, int32_t* __restrict__ pos_out) {
+    const int i = blockIdx.x, b = blockIdx.y;
+    int src = kept_idx[(size_t)b * S_out + i];
+    src = min(max(src, 0), S - 1);
+    const uint4* from = h + ((size_t)b * S + src) * row_vec;
+    uint4* to = h_out + ((size_t)b * S_out + i) * row_vec;
+    int c = threadIdx.x;
+    for (; c + CMP_THREADS < row_vec; c += 2 * CMP_THREADS) {
+        const uint4 a = from[c];
+        const uint4 d = from[c + CMP_THREADS];
+        to[c] = a;
+        to[c + CMP_THREADS] = d;
+    }
+    for (; c < row_vec; c += CMP_THREADS) to[c] = from[c];
+    if (threadIdx.x == 0) pos_out[(size_t)b * S_out + i] = pos[(size_t)b * S + src];
+}
+
+int launch_compact(const bf16_t* h, const int32_t* pos, const int32_t* kept_idx, int B, int S,
+                   int S_out, int D, bf16_t* h_out, int32_t* pos_out, hipStream_t st) {
+    if (S_out == 0 || B == 0) return MVLA_OK;
+    hipLaunchKernelGGL(compact_kernel, dim3(S_out, B), dim3(CMP_THREADS), 0, st,
+                       reinterpret_cast<const uint4*>(h), pos, kept_idx, S, S_out, D / 8,
+                       reinterpret_cast<uint4*>(h_out), pos_out);
+    MVLA_HIP_CHECK(hipGetLastError());
+    return MVLA_OK;
+}
+
+}  // namespace mvla

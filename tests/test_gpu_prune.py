@@ -1,0 +1,204 @@
+"""GPU parity of the pruning-step calls against the CPU oracle (teacher-forced:
+each call is fed the oracle's output of the step before it)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from paper_2604_09244_amd import binding as mv
+from paper_2604_09244_amd import workloads as W
+from helpers import to64
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = mv.Context(B=16, S=2624, D=4096, H=32, F=11008, n_query_tail=64)
+    yield c
+    c.close()
+
+
+SAL_SHAPES = [  # B, H, Nq, S, n_vis
+    (1, 4, 16, 144, 128),        # tiny
+    (1, 32, 32, 544, 512),       # single view
+    (2, 3, 5, 203, 150),         # S % 4 != 0: scalar path, ragged column chunk
+    (3, 8, 48, 460, 401),        # ragged n_vis on the vector path
+    (2, 2, 1, 64, 64),           # one row per head, n_vis == S
+    (8, 32, 48, 1840, 1792),     # multi view, full size
+]
+
+
+@pytest.mark.parametrize("B,H,Nq,S,nv", SAL_SHAPES)
+def test_salience_parity(ctx, B, H, Nq, S, nv):
+    g = torch.Generator().manual_seed(B * 1000 + S)
+    p = torch.rand(B, H, Nq, S, generator=g) ** 3
+    p = (p / p.sum(-1, keepdim=True)).contiguous()
+    ref = O.salience(p.numpy(), nv)
+    sal = ctx.salience(p.cuda(), nv)
+    torch.cuda.synchronize()
+    got = to64(sal)
+    rel = np.max(np.abs(got - ref) / np.abs(ref))
+    assert rel <= 1e-5, rel
+    # run-to-run bit reproducibility (fixed summation order)
+    again = ctx.salience(p.cuda(), nv)
+    assert torch.equal(sal, again)
+
+
+def test_salience_full_size_ratio_sweep(ctx):
+    wl = W.WORKLOADS["ratio_sweep"]
+    p = W.synthetic_probs(wl, device="cuda", B=4)
+    sal = ctx.salience(p, wl.n_vis)
+    torch.cuda.synchronize()
+    ref = O.salience(p.cpu().numpy(), wl.n_vis)
+    assert np.max(np.abs(to64(sal) - ref) / np.maximum(np.abs(ref), 1e-30)) <= 1e-5
+    # property at any size: all columns of a row-stochastic matrix sum to 1
+    full = ctx.salience(p, wl.S)
+    assert np.allclose(to64(full).sum(1), 1.0, atol=1e-5)
+
+
+def _budget_case(sal, n2, n3, K):
+    k2k3, mass = O.modality_budget(sal, n2, n3, K)
+    frac = K * mass[:, 0] - np.floor(K * mass[:, 0])
+    safe = np.abs(frac - 0.5) > 1e-9     # last-bit fp64 differences cannot flip these
+    return k2k3, mass, safe
+
+
+@pytest.mark.parametrize("n2,n3,K,B", [(64, 64, 64, 1), (256, 256, 205, 4), (768, 1024, 538, 8),
+                                       (512, 2048, 384, 16), (512, 2048, 2560, 16), (7, 1, 3, 5),
+                                       (1, 0, 1, 2), (300, 300, 0, 2)])
+def test_budget_bit_exact(ctx, n2, n3, K, B):
+    r = np.random.default_rng(n2 * 7 + K)
+    sal = r.lognormal(size=(B, n2 + n3)).astype(np.float32)
+    if n2 >= 64:
+        sal[:, :n2] *= r.beta(2, 2, size=(B, 1)).astype(np.float32) * 4
+    k2k3, mass, safe = _budget_case(sal, n2, n3, K)
+    got, gm = ctx.modality_budget(torch.from_numpy(sal).cuda(), n2, n3, K, want_mass=True)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    assert np.array_equal(got[safe], k2k3[safe])
+    assert np.all(got.sum(1) == K)
+    assert np.allclose(gm.cpu().numpy(), mass, atol=1e-6)
+
+
+def test_budget_clamps_and_zero_mass(ctx):
+    s = np.zeros((2, 20), np.float32)
+    s[0, :10] = 1.0
+    got = ctx.modality_budget(torch.from_numpy(s).cuda(), 10, 10, 14).cpu().numpy()
+    assert got.tolist() == O.modality_budget(s, 10, 10, 14)[0].tolist() == [[10, 4], [7, 7]]
+    got = ctx.modality_budget(torch.from_numpy(s).cuda(), 10, 10, 6, min2=0, min3=2).cpu().numpy()
+    assert got.tolist() == O.modality_budget(s, 10, 10, 6, 0, 2)[0].tolist()
+
+
+def _select_check(ctx, sal, k2k3, n2, n3, nt):
+    K = int(k2k3[0].sum())
+    ref = O.select_topk(sal, k2k3, n2, n3, nt)
+    got = ctx.select_topk(torch.from_numpy(sal).cuda(), torch.from_numpy(k2k3.astype(np.int32)).cuda(),
+                          n2, n3, nt, K)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy(), ref)
+
+
+@pytest.mark.parametrize("name,levels", [("tiny", 0), ("single_view", 0), ("multi_view", 0),
+                                         ("ratio_sweep", 0), ("single_view", 8), ("ratio_sweep", 8),
+                                         ("multi_view", 2)])
+def test_select_bit_exact_workload_shapes(ctx, name, levels):
+    wl = W.WORKLOADS[name]
+    sal = W.synthetic_salience(wl, levels=levels).numpy()
+    k2k3, _ = O.modality_budget(sal, wl.n2, wl.n3, wl.k_total)
+    _select_check(ctx, sal, k2k3, wl.n2, wl.n3, wl.nt)
+
+
+@pytest.mark.parametrize("keep", W.RATIO_SWEEP_PERMILLE)
+def test_select_ratio_sweep_budgets(ctx, keep):
+    wl = W.with_keep(W.WORKLOADS["ratio_sweep"], keep)
+    sal = W.synthetic_salience(wl, levels=0).numpy()
+    k2k3, _ = O.modality_budget(sal, wl.n2, wl.n3, wl.k_total)
+    _select_check(ctx, sal, k2k3, wl.n2, wl.n3, wl.nt)
+
+
+def test_select_edge_cases(ctx):
+    r = np.random.default_rng(5)
+    # all equal -> lowest indices; K = 0 and K = N per modality; -0/+0; negatives
+    n2, n3, nt = 37, 91, 3
+    flat = np.ones((2, n2 + n3), np.float32)
+    _select_check(ctx, flat, np.array([[5, 60], [37, 28]]), n2, n3, nt)
+    _select_check(ctx, flat, np.array([[0, 0], [0, 0]]), n2, n3, nt)
+    _select_check(ctx, flat, np.array([[37, 91]]), n2, n3, 0)
+    s = r.normal(size=(3, n2 + n3)).astype(np.float32)
+    s[:, ::5] = 0.0
+    s[:, 1::7] = -0.0
+    s[:, 2::9] = np.float32(-3.5)
+    _select_check(ctx, s, np.array([[11, 40], [30, 21], [0, 51]]), n2, n3, nt)
+    # denormals, huge and tiny magnitudes
+    s2 = (r.normal(size=(1, n2 + n3)) * 10.0 ** r.integers(-44, 38, size=(1, n2 + n3))).astype(np.float32)
+    _select_check(ctx, s2, np.array([[20, 45]]), n2, n3, nt)
+    # largest supported segment, ties across many threads' ranges
+    n = 16384
+    big = np.floor(r.random((1, 2 * n)) * 50).astype(np.float32)
+    _select_check(ctx, big, np.array([[5000, 11111]]), n, n, 1)
+    # one-token segments
+    _select_check(ctx, np.array([[1.0, 2.0]], np.float32), np.array([[1, 0]]), 1, 1, 0)
+    _select_check(ctx, np.array([[1.0, 2.0]], np.float32), np.array([[1, 1]]), 1, 1, 2)
+
+
+def test_select_unsupported_segment_is_an_error(ctx):
+    sal = torch.zeros(1, 16385 + 8, device="cuda")
+    with pytest.raises(mv.MvlaError) as e:
+        ctx.select_topk(sal, torch.zeros(1, 2, dtype=torch.int32, device="cuda"), 16385, 8, 0, 0)
+    assert e.value.code == -4
+
+
+@pytest.mark.parametrize("B,S,S_out,D", [(1, 144, 80, 256), (1, 544, 237, 4096), (8, 1840, 586, 4096),
+                                         (2, 50, 50, 8), (3, 33, 1, 264)])
+def test_compact_bit_exact(ctx, B, S, S_out, D):
+    r = np.random.default_rng(S + D)
+    h = torch.randn(B, S, D, generator=torch.Generator().manual_seed(S)).to(torch.bfloat16)
+    pos = torch.from_numpy(r.integers(0, 100000, size=(B, S)).astype(np.int32))
+    kept = np.stack([np.sort(r.choice(S, S_out, replace=False)) for _ in range(B)]).astype(np.int32)
+    ho, po = ctx.compact(h.cuda(), pos.cuda(), torch.from_numpy(kept).cuda())
+    torch.cuda.synchronize()
+    rh, rp = O.compact(h.view(torch.int16).numpy(), pos.numpy(), kept)
+    assert np.array_equal(ho.cpu().view(torch.int16).numpy(), rh)
+    assert np.array_equal(po.cpu().numpy(), rp)
+
+
+@pytest.mark.parametrize("name", ["tiny", "single_view", "multi_view"])
+def test_prune_step_equals_separate_calls_and_oracle(ctx, name):
+    wl = W.WORKLOADS[name]
+    B = min(wl.B, 4)
+    p = W.synthetic_probs(wl, device="cuda", B=B)
+    x, pos = W.hidden_states(wl, device="cuda", B=B)
+    out = ctx.prune_step(p, x, pos, wl.n2, wl.n3, wl.nt, wl.k_total)
+    sal = ctx.salience(p, wl.n_vis)
+    k2k3 = ctx.modality_budget(sal, wl.n2, wl.n3, wl.k_total)
+    kept = ctx.select_topk(sal, k2k3, wl.n2, wl.n3, wl.nt, wl.k_total)
+    h2, p2 = ctx.compact(x, pos, kept)
+    torch.cuda.synchronize()
+    assert torch.equal(out["sal"], sal) and torch.equal(out["k2k3"], k2k3)
+    assert torch.equal(out["kept_idx"], kept) and torch.equal(out["h"], h2) and torch.equal(out["pos"], p2)
+    # against the oracle from the GPU's own fp32 salience (selection is exact given equal inputs)
+    s_np = sal.cpu().numpy()
+    rk, rmass = O.modality_budget(s_np, wl.n2, wl.n3, wl.k_total)
+    frac = wl.k_total * rmass[:, 0] - np.floor(wl.k_total * rmass[:, 0])
+    assert np.all(np.abs(frac - 0.5) > 1e-9), "reseed: a budget sits on a rounding boundary"
+    assert np.array_equal(k2k3.cpu().numpy(), rk)
+    assert np.array_equal(kept.cpu().numpy(), O.select_topk(s_np, rk, wl.n2, wl.n3, wl.nt))
+
+
+def test_argument_errors_launch_nothing(ctx):
+    sal = torch.ones(2, 20, device="cuda")
+    k = torch.zeros(2, 2, dtype=torch.int32, device="cuda")
+    lib = mv.load()
+    assert lib.mvla_salience(ctx.handle, None, 1, 1, 1, 4, 4, sal.data_ptr()) == -1
+    assert lib.mvla_salience(ctx.handle, sal.data_ptr(), 1, 1, 1, 4, 5, sal.data_ptr()) == -1
+    assert lib.mvla_modality_budget(ctx.handle, sal.data_ptr(), 2, 10, 10, 21, 0, 0, k.data_ptr(), None) == -1
+    assert lib.mvla_modality_budget(ctx.handle, sal.data_ptr(), 2, 10, 10, 5, 4, 4, k.data_ptr(), None) == -1
+    assert lib.mvla_select_topk(ctx.handle, sal.data_ptr(), k.data_ptr(), 2, 10, 10, 0, 21, k.data_ptr()) == -1
+    h = torch.zeros(1, 4, 8, dtype=torch.bfloat16, device="cuda")
+    pos = torch.zeros(1, 4, dtype=torch.int32, device="cuda")
+    assert lib.mvla_compact(ctx.handle, h.data_ptr(), pos.data_ptr(), pos.data_ptr(), 1, 4, 2, 8,
+                            h.data_ptr(), pos.data_ptr()) == -1   # overlapping buffers
+    assert lib.mvla_compact(ctx.handle, h.data_ptr(), pos.data_ptr(), pos.data_ptr(), 1, 4, 2, 7,
+                            h.data_ptr(), pos.data_ptr()) == -1   # D % 8
+    torch.cuda.synchronize()
