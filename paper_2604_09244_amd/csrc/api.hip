@@ -11,7 +11,8 @@ namespace {
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
 struct LayerBuffers {
-    bf16_t *u, *qkv, *vt, *attn, *x1, *act;
+    bf16_t *u, *qkv, *vt, *attn, *act;
+    float* x1;  // residual stream after attention, kept in fp32
     int S_pad;
     size_t bytes;  // total scratch needed
 };
@@ -31,7 +32,7 @@ LayerBuffers layer_buffers(char* base, int B, int S, int D, int F) {
     lb.qkv = take(M * 3 * D * 2);
     lb.vt = take((size_t)B * D * lb.S_pad * 2);
     lb.attn = take(M * D * 2);
-    lb.x1 = take(M * D * 2);
+    lb.x1 = reinterpret_cast<float*>(take(M * D * 4));
     lb.act = take(M * F * 2);
     lb.bytes = off;
     return lb;
@@ -221,15 +222,16 @@ int mvla_prefill_layer(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_laye
     rc = launch_attention(lb.qkv, lb.qkv + D, 3 * D, lb.vt, lb.S_pad, B, S, H, dh, lb.attn, D, st);
     if (rc) return rc;
     rc = launch_gemm(lb.attn, D, static_cast<const bf16_t*>(w->wo), M, D, D, lb.x1, D, xin, D,
-                     EPI_RESIDUAL, st);
+                     EPI_RES_BF16_TO_F32, st);
     if (rc) return rc;
-    rc = launch_rmsnorm(lb.x1, static_cast<const bf16_t*>(w->g_mlp), M, D, cfg->rms_eps, lb.u, st);
+    rc = launch_rmsnorm_f32(lb.x1, static_cast<const bf16_t*>(w->g_mlp), M, D, cfg->rms_eps, lb.u,
+                            st);
     if (rc) return rc;
     rc = launch_gemm(lb.u, D, static_cast<const bf16_t*>(w->w_gateup), M, 2 * F, D, lb.act, F,
                      nullptr, 0, EPI_SILU_MUL, st);
     if (rc) return rc;
     return launch_gemm(lb.act, F, static_cast<const bf16_t*>(w->w_down), M, D, F,
-                       static_cast<bf16_t*>(y), D, lb.x1, D, EPI_RESIDUAL, st);
+                       y, D, lb.x1, D, EPI_RES_F32_TO_BF16, st);
 }
 
 int mvla_score_only(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weights* w,

@@ -47,6 +47,8 @@ int launch_compact(const bf16_t* h, const int32_t* pos, const int32_t* kept_idx,
 // layer_kernels.hip
 int launch_rmsnorm(const bf16_t* x, const bf16_t* gain, int M, int D, float eps, bf16_t* out,
                    hipStream_t st);
+int launch_rmsnorm_f32(const float* x, const bf16_t* gain, int M, int D, float eps, bf16_t* out,
+                       hipStream_t st);
 int launch_rope_table(double base, int rope_len, int dh, float* c, float* s, hipStream_t st);
 // q,k rotated in place inside qkv [B*S, 3D]; v transposed to vt [B, H, dh, S_pad]
 int launch_rope_split(bf16_t* qkv, const int32_t* pos, const float* rc, const float* rs,
@@ -58,9 +60,12 @@ int launch_score_probs(const bf16_t* q, int q_row_stride, const bf16_t* k, int k
                        hipStream_t st);
 
 // gemm.hip:  C[M,N] = A[M,K] * W[N,K]^T  (bf16 in, fp32 accumulate)
-enum GemmEpilogue { EPI_STORE = 0, EPI_RESIDUAL = 1, EPI_SILU_MUL = 2 };
-int launch_gemm(const bf16_t* A, int lda, const bf16_t* W, int M, int N, int K, bf16_t* C, int ldc,
-                const bf16_t* R, int ldr, int epilogue, hipStream_t st);
+// EPI_STORE: C bf16.  EPI_RES_BF16_TO_F32: C fp32 = acc + R(bf16).  EPI_RES_F32_TO_BF16:
+// C bf16 = acc + R(fp32).  EPI_SILU_MUL: C bf16 [M, N/2] = SiLU(gate) * up.
+enum GemmEpilogue { EPI_STORE = 0, EPI_RES_BF16_TO_F32 = 1, EPI_RES_F32_TO_BF16 = 2,
+                    EPI_SILU_MUL = 3 };
+int launch_gemm(const bf16_t* A, int lda, const bf16_t* W, int M, int N, int K, void* C, int ldc,
+                const void* R, int ldr, int epilogue, hipStream_t st);
 
 // attention.hip: causal flash attention; q,k rows inside qkv (row stride ldqkv), vt [B,H,dh,S_pad]
 int launch_attention(const bf16_t* q, const bf16_t* k, int ldqkv, const bf16_t* vt, int S_pad,

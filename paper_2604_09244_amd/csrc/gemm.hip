@@ -7,8 +7,11 @@
 // in flight from HBM into registers and is written to stage s^1 afterwards.
 // Wave (wm, wn) owns a (BM/WM) x (BN/WN) sub-tile made of 32x32 MFMA tiles.
 //
-// Epilogues: plain bf16 store; residual add; SiLU(gate)*up, where gate and up
-// columns alternate in blocks of 32 so that both sit in the same lane.
+// Epilogues: plain bf16 store; residual add (bf16 residual in, fp32 out -- or
+// fp32 residual in, bf16 out: the residual stream between the two halves of a
+// layer stays in fp32, so it is rounded to bf16 once per layer); SiLU(gate)*up,
+// where gate and up columns alternate in blocks of 32 so that both sit in the
+// same lane.
 #include "common.h"
 #include "mfma.h"
 
@@ -38,7 +41,7 @@ __device__ __forceinline__ bool tile_coords(int tiles_m, int tiles_n, int* tm, i
 template <int BM, int BN, int WM, int WN, int EPI>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ W, int M, int N, int K,
-    bf16_t* __restrict__ C, int ldc, const bf16_t* __restrict__ R, int ldr, int tiles_m,
+    void* __restrict__ Cv, int ldc, const void* __restrict__ Rv, int ldr, int tiles_m,
     int tiles_n) {
     constexpr int NT = WM * WN * 64;
     constexpr int TM = BM / WM, TN = BN / WN;  // wave tile
@@ -135,6 +138,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
 
     // ---- epilogue: lane holds column (lane%32) and rows mfma32_row(v, lane) of each tile ----
     const int col_in_tile = lane & 31;
+    bf16_t* C = static_cast<bf16_t*>(Cv);
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
         const int row_base = m0 + wm * TM + i * 32;
@@ -165,9 +169,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
                         const int row = row_base + mfma32_row(v, lane);
                         if (row < M) {
                             float val = acc[i][j][v];
-                            if (EPI == EPI_RESIDUAL)
-                                val += bf16_to_f32(R[(size_t)row * ldr + col]);
-                            C[(size_t)row * ldc + col] = f32_to_bf16(val);
+                            if (EPI == EPI_RES_BF16_TO_F32) {
+                                val += bf16_to_f32(
+                                    static_cast<const bf16_t*>(Rv)[(size_t)row * ldr + col]);
+                                static_cast<float*>(Cv)[(size_t)row * ldc + col] = val;
+                            } else {
+                                if (EPI == EPI_RES_F32_TO_BF16)
+                                    val += static_cast<const float*>(Rv)[(size_t)row * ldr + col];
+                                C[(size_t)row * ldc + col] = f32_to_bf16(val);
+                            }
                         }
                     }
                 }
@@ -177,8 +187,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
 }
 
 template <int BM, int BN, int WM, int WN>
-static int launch_cfg(const bf16_t* A, int lda, const bf16_t* W, int M, int N, int K, bf16_t* C,
-                      int ldc, const bf16_t* R, int ldr, int epi, hipStream_t st) {
+static int launch_cfg(const bf16_t* A, int lda, const bf16_t* W, int M, int N, int K, void* C,
+                      int ldc, const void* R, int ldr, int epi, hipStream_t st) {
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     const int total = tiles_m * tiles_n;
     const int grid = ((total + 7) / 8) * 8;
@@ -196,15 +206,16 @@ static int launch_cfg(const bf16_t* A, int lda, const bf16_t* W, int M, int N, i
                            ldr, tiles_m, tiles_n);                                            \
     } while (0)
     if (epi == EPI_STORE) MVLA_GEMM_LAUNCH(EPI_STORE);
-    else if (epi == EPI_RESIDUAL) MVLA_GEMM_LAUNCH(EPI_RESIDUAL);
+    else if (epi == EPI_RES_BF16_TO_F32) MVLA_GEMM_LAUNCH(EPI_RES_BF16_TO_F32);
+    else if (epi == EPI_RES_F32_TO_BF16) MVLA_GEMM_LAUNCH(EPI_RES_F32_TO_BF16);
     else MVLA_GEMM_LAUNCH(EPI_SILU_MUL);
 #undef MVLA_GEMM_LAUNCH
     MVLA_HIP_CHECK(hipGetLastError());
     return MVLA_OK;
 }
 
-int launch_gemm(const bf16_t* A, int lda, const bf16_t* W, int M, int N, int K, bf16_t* C, int ldc,
-                const bf16_t* R, int ldr, int epilogue, hipStream_t st) {
+int launch_gemm(const bf16_t* A, int lda, const bf16_t* W, int M, int N, int K, void* C, int ldc,
+                const void* R, int ldr, int epilogue, hipStream_t st) {
     if (M <= 0 || N <= 0) return MVLA_OK;
     if (K % BK != 0 || lda % 8 != 0) return MVLA_EUNSUPPORTED;
     if (epilogue == EPI_SILU_MUL && N % 64 != 0) return MVLA_EUNSUPPORTED;

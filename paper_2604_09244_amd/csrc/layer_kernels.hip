@@ -59,6 +59,50 @@ int launch_rmsnorm(const bf16_t* x, const bf16_t* gain, int M, int D, float eps,
     return MVLA_OK;
 }
 
+// Same, reading the fp32 residual stream (eight floats per 16-byte output chunk).
+__global__ __launch_bounds__(NORM_THREADS) void rmsnorm_f32_kernel(const float4* __restrict__ x,
+                                                                   const uint4* __restrict__ gain,
+                                                                   int M, int row_vec, float inv_d,
+                                                                   float eps,
+                                                                   uint4* __restrict__ out) {
+    const int row = blockIdx.x * (NORM_THREADS / 64) + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (row >= M) return;
+    const float4* xr = x + (size_t)row * row_vec * 2;
+    float ss = 0.f;
+    for (int c = lane; c < row_vec * 2; c += 64) {
+        const float4 v = xr[c];
+        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    }
+    for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+    const float scale = 1.0f / sqrtf(ss * inv_d + eps);
+    uint4* orow = out + (size_t)row * row_vec;
+    for (int c = lane; c < row_vec; c += 64) {
+        const float4 a = xr[2 * c], b = xr[2 * c + 1];
+        const uint4 g = gain[c];
+        const float xs[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+        const uint32_t gw[4] = {g.x, g.y, g.z, g.w};
+        uint32_t r[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            r[i] = pack_bf16x2(xs[2 * i] * scale * __uint_as_float(gw[i] << 16),
+                               xs[2 * i + 1] * scale * __uint_as_float(gw[i] & 0xFFFF0000u));
+        orow[c] = make_uint4(r[0], r[1], r[2], r[3]);
+    }
+}
+
+int launch_rmsnorm_f32(const float* x, const bf16_t* gain, int M, int D, float eps, bf16_t* out,
+                       hipStream_t st) {
+    if (M <= 0) return MVLA_OK;
+    const int rows_per_block = NORM_THREADS / 64;
+    hipLaunchKernelGGL(rmsnorm_f32_kernel, dim3((M + rows_per_block - 1) / rows_per_block),
+                       dim3(NORM_THREADS), 0, st, reinterpret_cast<const float4*>(x),
+                       reinterpret_cast<const uint4*>(gain), M, D / 8, 1.0f / (float)D, eps,
+                       reinterpret_cast<uint4*>(out));
+    MVLA_HIP_CHECK(hipGetLastError());
+    return MVLA_OK;
+}
+
 // ---------------------------------------------------------------------------
 // Rotary table in fp64: angle = pos * base^(-2i/dh).
 // ---------------------------------------------------------------------------

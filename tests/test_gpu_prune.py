@@ -124,7 +124,7 @@ def test_select_edge_cases(ctx):
     flat = np.ones((2, n2 + n3), np.float32)
     _select_check(ctx, flat, np.array([[5, 60], [37, 28]]), n2, n3, nt)
     _select_check(ctx, flat, np.array([[0, 0], [0, 0]]), n2, n3, nt)
-    _select_check(ctx, flat, np.array([[37, 91]]), n2, n3, 0)
+    _select_check(ctx, flat[:1], np.array([[37, 91]]), n2, n3, 0)
     s = r.normal(size=(3, n2 + n3)).astype(np.float32)
     s[:, ::5] = 0.0
     s[:, 1::7] = -0.0
@@ -145,7 +145,7 @@ def test_select_edge_cases(ctx):
 def test_select_unsupported_segment_is_an_error(ctx):
     sal = torch.zeros(1, 16385 + 8, device="cuda")
     with pytest.raises(mv.MvlaError) as e:
-        ctx.select_topk(sal, torch.zeros(1, 2, dtype=torch.int32, device="cuda"), 16385, 8, 0, 0)
+        ctx.select_topk(sal, torch.zeros(1, 2, dtype=torch.int32, device="cuda"), 16385, 8, 1, 0)
     assert e.value.code == -4
 
 
