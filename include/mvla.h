@@ -187,6 +187,29 @@ int mvla_score_only(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_w
                     const void* x, const int32_t* pos, int B, int S, int n_query_tail,
                     const float* key_bias, float* probs_out);
 
+/* ------------------------------------------------------------------------ */
+/* Measurement (the paper's overhead study, Table 4, reports the pruning    */
+/* method's own cost apart from the step latency; these calls give the same */
+/* split per kernel)                                                        */
+/* ------------------------------------------------------------------------ */
+
+/* Bracket every launch whose kernel id bit is set in kernel_mask with a pair
+ * of HIP events on the context's stream (ids: see mvla_kernel_name).  Creates
+ * up to max_records event pairs on first use (host objects; no device
+ * memory); further launches beyond max_records are not timed.  Mask 0 turns
+ * timing off.  Discards records not yet read. */
+int mvla_profile_enable(mvla_ctx* ctx, uint32_t kernel_mask, int max_records);
+/* Wait for the recorded launches and copy out up to `capacity` records:
+ * kernel id, tag (the launch's row count M, or batch for the pruning
+ * kernels) and elapsed milliseconds; *n_out = records written.  HOST arrays.
+ * Clears the record list. */
+int mvla_profile_read(mvla_ctx* ctx, int capacity, int32_t* ids, int32_t* tags, float* ms,
+                      int32_t* n_out);
+/* Name of kernel id 0..14 ("rmsnorm", "gemm_qkv", "rope_split", "score_probs",
+ * "attention", "gemm_o", "rmsnorm_mlp", "gemm_gateup", "gemm_down", "salience",
+ * "budget", "select", "compact", "rope_table", "prune_fused"), "?" otherwise. */
+const char* mvla_kernel_name(int id);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,6 +22,7 @@ EXPORTS = [
     "mvla_version", "mvla_strerror", "mvla_workspace_bytes", "mvla_create", "mvla_set_stream",
     "mvla_destroy", "mvla_salience", "mvla_modality_budget", "mvla_select_topk", "mvla_compact",
     "mvla_prune_step", "mvla_rope_table", "mvla_prefill_layer", "mvla_score_only",
+    "mvla_profile_enable", "mvla_profile_read", "mvla_kernel_name",
 ]
 
 
@@ -73,6 +74,10 @@ def load() -> C.CDLL:
                                        i, i, vp, i, vp, vp]
     lib.mvla_score_only.argtypes = [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeightsC), vp, vp,
                                     i, i, i, vp, vp]
+    lib.mvla_profile_enable.argtypes = [vp, C.c_uint32, i]
+    lib.mvla_profile_read.argtypes = [vp, i, vp, vp, vp, vp]
+    lib.mvla_kernel_name.restype = C.c_char_p
+    lib.mvla_kernel_name.argtypes = [i]
     _lib = lib
     return lib
 
@@ -139,6 +144,25 @@ class Context:
 
     def set_stream(self, stream: torch.cuda.Stream):
         _check(load().mvla_set_stream(self._h, stream.cuda_stream), "mvla_set_stream")
+
+    # ---- timing ----------------------------------------------------------
+    def profile_enable(self, kernel_ids: Optional[Sequence[int]], max_records: int = 4096):
+        """kernel_ids None = all kernels, [] = off."""
+        mask = 0xFFFFFFFF if kernel_ids is None else sum(1 << k for k in kernel_ids)
+        _check(load().mvla_profile_enable(self._h, mask, max_records), "mvla_profile_enable")
+        self._prof_cap = max_records
+
+    def profile_read(self):
+        """-> list of (kernel name, tag, milliseconds) in launch order."""
+        cap = getattr(self, "_prof_cap", 0)
+        ids = (C.c_int32 * max(cap, 1))()
+        tags = (C.c_int32 * max(cap, 1))()
+        ms = (C.c_float * max(cap, 1))()
+        n = C.c_int32(0)
+        _check(load().mvla_profile_read(self._h, cap, ids, tags, ms, C.byref(n)),
+               "mvla_profile_read")
+        lib = load()
+        return [(lib.mvla_kernel_name(ids[j]).decode(), tags[j], ms[j]) for j in range(n.value)]
 
     # ---- pruning step --------------------------------------------------
     def salience(self, attn: torch.Tensor, n_vis: int, out: Optional[torch.Tensor] = None):

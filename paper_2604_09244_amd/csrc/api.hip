@@ -62,9 +62,78 @@ int check_layer_args(const mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_
     return MVLA_OK;
 }
 
+// Brackets one launch with a pair of pre-created events when its kernel id is selected.
+struct Timed {
+    mvla_ctx* c;
+    ProfRecord* r = nullptr;
+    Timed(mvla_ctx* ctx, int id, int tag) : c(ctx) {
+        if ((ctx->prof_mask >> id) & 1u) {
+            if (ctx->prof_used < ctx->prof_pool.size()) {
+                r = &ctx->prof_pool[ctx->prof_used++];
+                r->id = id;
+                r->tag = tag;
+                (void)hipEventRecord(r->start, ctx->stream);
+            }
+        }
+    }
+    ~Timed() {
+        if (r) (void)hipEventRecord(r->stop, c->stream);
+    }
+};
+#define TIMED(ctx, id, tag, call)   \
+    do {                            \
+        Timed t_(ctx, id, tag);     \
+        rc = (call);                \
+    } while (0);                    \
+    if (rc) return rc
+
+const char* const kKernelNames[KID_COUNT] = {
+    "rmsnorm", "gemm_qkv", "rope_split", "score_probs", "attention", "gemm_o", "rmsnorm_mlp",
+    "gemm_gateup", "gemm_down", "salience", "budget", "select", "compact", "rope_table",
+    "prune_fused"};
+
 }  // namespace
 
 extern "C" {
+
+int mvla_profile_enable(mvla_ctx* ctx, uint32_t kernel_mask, int max_records) {
+    if (!ctx || max_records < 0) return MVLA_EINVAL;
+    while ((int)ctx->prof_pool.size() < max_records) {
+        ProfRecord r{};
+        if (hipEventCreate(&r.start) != hipSuccess) return MVLA_EHIP;
+        if (hipEventCreate(&r.stop) != hipSuccess) {
+            (void)hipEventDestroy(r.start);
+            return MVLA_EHIP;
+        }
+        ctx->prof_pool.push_back(r);
+    }
+    ctx->prof_mask = kernel_mask;
+    ctx->prof_used = 0;
+    return MVLA_OK;
+}
+
+int mvla_profile_read(mvla_ctx* ctx, int capacity, int32_t* ids, int32_t* tags, float* ms,
+                      int32_t* n_out) {
+    if (!ctx || !n_out || capacity < 0 || (capacity > 0 && (!ids || !tags || !ms)))
+        return MVLA_EINVAL;
+    const size_t n = ctx->prof_used < (size_t)capacity ? ctx->prof_used : (size_t)capacity;
+    for (size_t i = 0; i < n; ++i) {
+        ProfRecord& r = ctx->prof_pool[i];
+        MVLA_HIP_CHECK(hipEventSynchronize(r.stop));
+        float t = 0.f;
+        MVLA_HIP_CHECK(hipEventElapsedTime(&t, r.start, r.stop));
+        ids[i] = r.id;
+        tags[i] = r.tag;
+        ms[i] = t;
+    }
+    *n_out = (int32_t)n;
+    ctx->prof_used = 0;
+    return MVLA_OK;
+}
+
+const char* mvla_kernel_name(int id) {
+    return (id >= 0 && id < KID_COUNT) ? kKernelNames[id] : "?";
+}
 
 const char* mvla_version(void) { return "0.1.0"; }
 
@@ -114,7 +183,14 @@ int mvla_set_stream(mvla_ctx* ctx, void* hip_stream) {
     return MVLA_OK;
 }
 
-void mvla_destroy(mvla_ctx* ctx) { delete ctx; }
+void mvla_destroy(mvla_ctx* ctx) {
+    if (!ctx) return;
+    for (ProfRecord& r : ctx->prof_pool) {
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+    }
+    delete ctx;
+}
 
 // ---------------------------------------------------------------------------
 int mvla_salience(mvla_ctx* ctx, const float* attn, int B, int H, int Nq, int S, int n_vis,
@@ -123,8 +199,11 @@ int mvla_salience(mvla_ctx* ctx, const float* attn, int B, int H, int Nq, int S,
     if (B <= 0 || H <= 0 || Nq <= 0 || S <= 0 || n_vis <= 0 || n_vis > S) return MVLA_EINVAL;
     if (!aligned(attn, 4) || !aligned(sal, 4)) return MVLA_EINVAL;
     if (salience_scratch_bytes(B, H, Nq, n_vis) > ctx->scratch_bytes) return MVLA_ENOMEM;
-    return launch_salience(attn, B, H, Nq, S, n_vis, sal, reinterpret_cast<float*>(ctx->scratch),
-                           ctx->counters, ctx->stream);
+    int rc;
+    TIMED(ctx, KID_SALIENCE, B, launch_salience(attn, B, H, Nq, S, n_vis, sal,
+                                                reinterpret_cast<float*>(ctx->scratch),
+                                                ctx->counters, ctx->stream));
+    return MVLA_OK;
 }
 
 int mvla_modality_budget(mvla_ctx* ctx, const float* sal, int B, int n2, int n3, int k_total,
@@ -134,7 +213,10 @@ int mvla_modality_budget(mvla_ctx* ctx, const float* sal, int B, int n2, int n3,
     if (k_total < 0 || k_total > n2 + n3) return MVLA_EINVAL;
     if (min2 < 0 || min3 < 0 || min2 > n2 || min3 > n3 || min2 + min3 > k_total)
         return MVLA_EINVAL;
-    return launch_budget(sal, B, n2, n3, k_total, min2, min3, k2k3, mass, ctx->stream);
+    int rc;
+    TIMED(ctx, KID_BUDGET, B, launch_budget(sal, B, n2, n3, k_total, min2, min3, k2k3, mass,
+                                            ctx->stream));
+    return MVLA_OK;
 }
 
 int mvla_select_topk(mvla_ctx* ctx, const float* sal, const int32_t* k2k3, int B, int n2, int n3,
@@ -142,7 +224,10 @@ int mvla_select_topk(mvla_ctx* ctx, const float* sal, const int32_t* k2k3, int B
     if (!ctx || !sal || !k2k3 || !kept_idx) return MVLA_EINVAL;
     if (B <= 0 || n2 < 0 || n3 < 0 || n2 + n3 <= 0 || n_text < 0) return MVLA_EINVAL;
     if (k_total < 0 || k_total > n2 + n3) return MVLA_EINVAL;
-    return launch_select(sal, k2k3, B, n2, n3, n_text, k_total, kept_idx, ctx->stream);
+    int rc;
+    TIMED(ctx, KID_SELECT, B, launch_select(sal, k2k3, B, n2, n3, n_text, k_total, kept_idx,
+                                            ctx->stream));
+    return MVLA_OK;
 }
 
 int mvla_compact(mvla_ctx* ctx, const void* h, const int32_t* pos, const int32_t* kept_idx, int B,
@@ -156,8 +241,11 @@ int mvla_compact(mvla_ctx* ctx, const void* h, const int32_t* pos, const int32_t
         const size_t na = (size_t)B * S * D * 2, nb = (size_t)B * S_out * D * 2;
         if (a < b + nb && b < a + na) return MVLA_EINVAL;
     }
-    return launch_compact(static_cast<const bf16_t*>(h), pos, kept_idx, B, S, S_out, D,
-                          static_cast<bf16_t*>(h_out), pos_out, ctx->stream);
+    int rc;
+    TIMED(ctx, KID_COMPACT, B * S_out,
+          launch_compact(static_cast<const bf16_t*>(h), pos, kept_idx, B, S, S_out, D,
+                         static_cast<bf16_t*>(h_out), pos_out, ctx->stream));
+    return MVLA_OK;
 }
 
 int mvla_prune_step(mvla_ctx* ctx, const float* attn, int H, int Nq, const void* h,
@@ -189,7 +277,10 @@ int mvla_rope_table(mvla_ctx* ctx, double base, int rope_len, int dh, float* cos
                     float* sin_out) {
     if (!ctx || !cos_out || !sin_out) return MVLA_EINVAL;
     if (rope_len <= 0 || dh <= 0 || dh % 2 != 0 || !(base > 0.0)) return MVLA_EINVAL;
-    return launch_rope_table(base, rope_len, dh, cos_out, sin_out, ctx->stream);
+    int rc;
+    TIMED(ctx, KID_ROPE_TABLE, rope_len,
+          launch_rope_table(base, rope_len, dh, cos_out, sin_out, ctx->stream));
+    return MVLA_OK;
 }
 
 int mvla_prefill_layer(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weights* w,
@@ -207,31 +298,33 @@ int mvla_prefill_layer(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_laye
     const bf16_t* xin = static_cast<const bf16_t*>(x);
     const bf16_t* wqkv = static_cast<const bf16_t*>(w->wqkv);
 
-    rc = launch_rmsnorm(xin, static_cast<const bf16_t*>(w->g_attn), M, D, cfg->rms_eps, lb.u, st);
-    if (rc) return rc;
-    rc = launch_gemm(lb.u, D, wqkv, M, 3 * D, D, lb.qkv, 3 * D, nullptr, 0, EPI_STORE, st);
-    if (rc) return rc;
-    rc = launch_rope_split(lb.qkv, pos, w->rope_cos, w->rope_sin, w->rope_len, B, S, H, dh,
-                           lb.S_pad, lb.vt, st);
-    if (rc) return rc;
+    TIMED(ctx, KID_RMSNORM, M,
+          launch_rmsnorm(xin, static_cast<const bf16_t*>(w->g_attn), M, D, cfg->rms_eps, lb.u, st));
+    TIMED(ctx, KID_GEMM_QKV, M,
+          launch_gemm(lb.u, D, wqkv, M, 3 * D, D, lb.qkv, 3 * D, nullptr, 0, EPI_STORE, st));
+    TIMED(ctx, KID_ROPE_SPLIT, M,
+          launch_rope_split(lb.qkv, pos, w->rope_cos, w->rope_sin, w->rope_len, B, S, H, dh,
+                            lb.S_pad, lb.vt, st));
     if (n_query_tail > 0) {
-        rc = launch_score_probs(lb.qkv, 3 * D, lb.qkv + D, 3 * D, key_bias, B, S, H, dh,
-                                n_query_tail, probs_out, st);
-        if (rc) return rc;
+        TIMED(ctx, KID_SCORE_PROBS, M,
+              launch_score_probs(lb.qkv, 3 * D, lb.qkv + D, 3 * D, key_bias, B, S, H, dh,
+                                 n_query_tail, probs_out, st));
     }
-    rc = launch_attention(lb.qkv, lb.qkv + D, 3 * D, lb.vt, lb.S_pad, B, S, H, dh, lb.attn, D, st);
-    if (rc) return rc;
-    rc = launch_gemm(lb.attn, D, static_cast<const bf16_t*>(w->wo), M, D, D, lb.x1, D, xin, D,
-                     EPI_RES_BF16_TO_F32, st);
-    if (rc) return rc;
-    rc = launch_rmsnorm_f32(lb.x1, static_cast<const bf16_t*>(w->g_mlp), M, D, cfg->rms_eps, lb.u,
-                            st);
-    if (rc) return rc;
-    rc = launch_gemm(lb.u, D, static_cast<const bf16_t*>(w->w_gateup), M, 2 * F, D, lb.act, F,
-                     nullptr, 0, EPI_SILU_MUL, st);
-    if (rc) return rc;
-    return launch_gemm(lb.act, F, static_cast<const bf16_t*>(w->w_down), M, D, F,
-                       y, D, lb.x1, D, EPI_RES_F32_TO_BF16, st);
+    TIMED(ctx, KID_ATTENTION, M,
+          launch_attention(lb.qkv, lb.qkv + D, 3 * D, lb.vt, lb.S_pad, B, S, H, dh, lb.attn, D, st));
+    TIMED(ctx, KID_GEMM_O, M,
+          launch_gemm(lb.attn, D, static_cast<const bf16_t*>(w->wo), M, D, D, lb.x1, D, xin, D,
+                      EPI_RES_BF16_TO_F32, st));
+    TIMED(ctx, KID_RMSNORM_MLP, M,
+          launch_rmsnorm_f32(lb.x1, static_cast<const bf16_t*>(w->g_mlp), M, D, cfg->rms_eps, lb.u,
+                             st));
+    TIMED(ctx, KID_GEMM_GATEUP, M,
+          launch_gemm(lb.u, D, static_cast<const bf16_t*>(w->w_gateup), M, 2 * F, D, lb.act, F,
+                      nullptr, 0, EPI_SILU_MUL, st));
+    TIMED(ctx, KID_GEMM_DOWN, M,
+          launch_gemm(lb.act, F, static_cast<const bf16_t*>(w->w_down), M, D, F, y, D, lb.x1, D,
+                      EPI_RES_F32_TO_BF16, st));
+    return MVLA_OK;
 }
 
 int mvla_score_only(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weights* w,
@@ -246,18 +339,20 @@ int mvla_score_only(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_w
     if (lb.bytes > ctx->scratch_bytes) return MVLA_ENOMEM;
     const int M = B * S;
     hipStream_t st = ctx->stream;
-    rc = launch_rmsnorm(static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(w->g_attn), M, D,
-                        cfg->rms_eps, lb.u, st);
-    if (rc) return rc;
+    TIMED(ctx, KID_RMSNORM, M,
+          launch_rmsnorm(static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(w->g_attn), M, D,
+                         cfg->rms_eps, lb.u, st));
     // query and key projections only (first 2D rows of wqkv), stored with row stride 2D
-    rc = launch_gemm(lb.u, D, static_cast<const bf16_t*>(w->wqkv), M, 2 * D, D, lb.qkv, 2 * D,
-                     nullptr, 0, EPI_STORE, st);
-    if (rc) return rc;
-    rc = launch_rope_split(lb.qkv, pos, w->rope_cos, w->rope_sin, w->rope_len, B, S, H, dh,
-                           lb.S_pad, nullptr, st);
-    if (rc) return rc;
-    return launch_score_probs(lb.qkv, 2 * D, lb.qkv + D, 2 * D, key_bias, B, S, H, dh,
-                              n_query_tail, probs_out, st);
+    TIMED(ctx, KID_GEMM_QKV, M,
+          launch_gemm(lb.u, D, static_cast<const bf16_t*>(w->wqkv), M, 2 * D, D, lb.qkv, 2 * D,
+                      nullptr, 0, EPI_STORE, st));
+    TIMED(ctx, KID_ROPE_SPLIT, M,
+          launch_rope_split(lb.qkv, pos, w->rope_cos, w->rope_sin, w->rope_len, B, S, H, dh,
+                            lb.S_pad, nullptr, st));
+    TIMED(ctx, KID_SCORE_PROBS, M,
+          launch_score_probs(lb.qkv, 2 * D, lb.qkv + D, 2 * D, key_bias, B, S, H, dh,
+                             n_query_tail, probs_out, st));
+    return MVLA_OK;
 }
 
 }  // extern "C"

@@ -73,24 +73,22 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(
         v_dst[i] = lds_slot(row, ch);
     }
     uint4 k_reg[K_CH], v_reg[V_CH];
-    auto fetch = [&](int kt) {
-#pragma unroll
-        for (int i = 0; i < K_CH; ++i) {
-            const int key = min(kt * ATT_KT + k_row[i], S - 1);
-            k_reg[i] = *reinterpret_cast<const uint4*>(k_src[i] + (size_t)key * ld);
-        }
-#pragma unroll
-        for (int i = 0; i < V_CH; ++i)
-            v_reg[i] = *reinterpret_cast<const uint4*>(v_src[i] + kt * ATT_KT);
-    };
-    auto stash = [&](int stage) {
-        uint4* Kd = Ks + stage * ATT_KT * CPR;
-        uint4* Vd = Vs + stage * DH * 8;
-#pragma unroll
-        for (int i = 0; i < K_CH; ++i) Kd[k_dst[i]] = k_reg[i];
-#pragma unroll
-        for (int i = 0; i < V_CH; ++i) Vd[v_dst[i]] = v_reg[i];
-    };
+#define ATT_FETCH(KT)                                                                      \
+    {                                                                                      \
+        _Pragma("unroll") for (int i = 0; i < K_CH; ++i) {                                 \
+            const int key = min((KT) * ATT_KT + k_row[i], S - 1);                          \
+            k_reg[i] = *reinterpret_cast<const uint4*>(k_src[i] + (size_t)key * ld);       \
+        }                                                                                  \
+        _Pragma("unroll") for (int i = 0; i < V_CH; ++i) v_reg[i] =                        \
+            *reinterpret_cast<const uint4*>(v_src[i] + (KT) * ATT_KT);                     \
+    }
+#define ATT_STASH(STAGE)                                                                   \
+    {                                                                                      \
+        uint4* Kd = Ks + (STAGE) * ATT_KT * CPR;                                           \
+        uint4* Vd = Vs + (STAGE) * DH * 8;                                                 \
+        _Pragma("unroll") for (int i = 0; i < K_CH; ++i) Kd[k_dst[i]] = k_reg[i];          \
+        _Pragma("unroll") for (int i = 0; i < V_CH; ++i) Vd[v_dst[i]] = v_reg[i];          \
+    }
 
     f32x16_t o_acc[DB];
 #pragma unroll
@@ -99,14 +97,14 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(
         for (int v = 0; v < 16; ++v) o_acc[d][v] = 0.f;
     float run_m = -INFINITY, run_l = 0.f;   // run_l: this lane's share of the row sum
 
-    fetch(0);
-    stash(0);
+    ATT_FETCH(0)
+    ATT_STASH(0)
     __syncthreads();
 
     for (int kt = 0; kt < n_kt; ++kt) {
         const int cur = kt & 1;
-        const bool more = kt + 1 < n_kt;
-        if (more) fetch(kt + 1);
+        const int nkt = min(kt + 1, n_kt - 1);  // unconditional: the last tile re-fetches itself
+        ATT_FETCH(nkt)
         const int key0 = kt * ATT_KT;
         // a wave whose queries all precede this tile has nothing to add
         if (key0 <= qw0 + 31 && qw0 < S) {
@@ -173,10 +171,12 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(
                 }
             }
         }
-        if (more) stash(cur ^ 1);
+        ATT_STASH(cur ^ 1)
         __syncthreads();
     }
 
+#undef ATT_FETCH
+#undef ATT_STASH
     // ---- normalise and store: lane holds query my_q, rows = head-dim
     const float tot = run_l + __shfl_xor(run_l, 32);
     if (my_q < S) {

@@ -8,7 +8,25 @@
 
 typedef uint16_t bf16_t;  // raw bf16 storage
 
+#include <vector>
+
+// per-kernel timing records (HIP events on the context's stream)
+enum KernelId {
+    KID_RMSNORM = 0, KID_GEMM_QKV, KID_ROPE_SPLIT, KID_SCORE_PROBS, KID_ATTENTION, KID_GEMM_O,
+    KID_RMSNORM_MLP, KID_GEMM_GATEUP, KID_GEMM_DOWN, KID_SALIENCE, KID_BUDGET, KID_SELECT,
+    KID_COMPACT, KID_ROPE_TABLE, KID_PRUNE_FUSED, KID_COUNT
+};
+
+struct ProfRecord {
+    int id, tag;
+    hipEvent_t start, stop;
+};
+
 struct mvla_ctx {
+    // timing (off unless mvla_profile_enable was called)
+    uint32_t prof_mask = 0;
+    std::vector<ProfRecord> prof_pool;  // pre-created events
+    size_t prof_used = 0;
     int device;
     hipStream_t stream;
     char* ws;          // caller-owned device workspace

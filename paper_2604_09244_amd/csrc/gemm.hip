@@ -102,13 +102,13 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     const int frag_row = lane & 31, frag_g = lane >> 5;
     for (int kt = 0; kt < k_tiles; ++kt) {
         const int cur = kt & 1;
-        const bool more = kt + 1 < k_tiles;
-        if (more) {
+        // next K-slab goes into flight before the matrix cores start on this one (the last
+        // iteration re-fetches its own slab: harmless, keeps the loop free of branches)
+        const int nk = min(kt + 1, k_tiles - 1) * 8;
 #pragma unroll
-            for (int i = 0; i < A_CH; ++i) a_reg[i] = a_src[i][(kt + 1) * 8];
+        for (int i = 0; i < A_CH; ++i) a_reg[i] = a_src[i][nk];
 #pragma unroll
-            for (int i = 0; i < B_CH; ++i) b_reg[i] = b_src[i][(kt + 1) * 8];
-        }
+        for (int i = 0; i < B_CH; ++i) b_reg[i] = b_src[i][nk];
         const uint4* Ac = As + cur * BM * 8;
         const uint4* Bc = Bs + cur * BN * 8;
 #pragma unroll
@@ -125,14 +125,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
 #pragma unroll
                 for (int j = 0; j < FN; ++j) acc[i][j] = mfma32(af[i], bfr[j], acc[i][j]);
         }
-        if (more) {
-            uint4* An = As + (cur ^ 1) * BM * 8;
-            uint4* Bn = Bs + (cur ^ 1) * BN * 8;
+        uint4* An = As + (cur ^ 1) * BM * 8;
+        uint4* Bn = Bs + (cur ^ 1) * BN * 8;
 #pragma unroll
-            for (int i = 0; i < A_CH; ++i) An[a_dst[i]] = a_reg[i];
+        for (int i = 0; i < A_CH; ++i) An[a_dst[i]] = a_reg[i];
 #pragma unroll
-            for (int i = 0; i < B_CH; ++i) Bn[b_dst[i]] = b_reg[i];
-        }
+        for (int i = 0; i < B_CH; ++i) Bn[b_dst[i]] = b_reg[i];
         __syncthreads();
     }
 
