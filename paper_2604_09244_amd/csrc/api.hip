@@ -62,6 +62,8 @@ int check_layer_args(const mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_
     return MVLA_OK;
 }
 
+#define GEMM_WS(ctx) (ctx)->gemm_partial, (ctx)->gemm_partial_bytes, (ctx)->counters + kCounterWords / 2, kCounterWords / 2
+
 // Brackets one launch with a pair of pre-created events when its kernel id is selected.
 struct Timed {
     mvla_ctx* c;
@@ -152,13 +154,14 @@ size_t mvla_workspace_bytes(int B, int S, int D, int H, int F, int n_query_tail)
     if (B <= 0 || S <= 0 || D <= 0 || H <= 0 || F <= 0 || n_query_tail < 0) return 0;
     const size_t sal = salience_scratch_bytes(B, H, n_query_tail > 0 ? n_query_tail : 1, S);
     const LayerBuffers lb = layer_buffers(nullptr, B, S, D, F);
-    return kCounterBytes + (sal > lb.bytes ? sal : lb.bytes) + 256;
+    return kCounterBytes + gemm_partial_bytes() + (sal > lb.bytes ? sal : lb.bytes) + 256;
 }
 
 int mvla_create(mvla_ctx** out, int device, void* hip_stream, void* workspace,
                 size_t workspace_bytes) {
     if (!out || !workspace || device < 0) return MVLA_EINVAL;
-    if (!aligned(workspace, 256) || workspace_bytes < kCounterBytes + 256) return MVLA_EINVAL;
+    const size_t fixed = kCounterBytes + gemm_partial_bytes();
+    if (!aligned(workspace, 256) || workspace_bytes < fixed + 256) return MVLA_EINVAL;
     MVLA_HIP_CHECK(hipSetDevice(device));
     mvla_ctx* c = new (std::nothrow) mvla_ctx;
     if (!c) return MVLA_ENOMEM;
@@ -167,8 +170,10 @@ int mvla_create(mvla_ctx** out, int device, void* hip_stream, void* workspace,
     c->ws = static_cast<char*>(workspace);
     c->ws_bytes = workspace_bytes;
     c->counters = reinterpret_cast<uint32_t*>(c->ws);
-    c->scratch = c->ws + kCounterBytes;
-    c->scratch_bytes = workspace_bytes - kCounterBytes;
+    c->gemm_partial = reinterpret_cast<float*>(c->ws + kCounterBytes);
+    c->gemm_partial_bytes = gemm_partial_bytes();
+    c->scratch = c->ws + fixed;
+    c->scratch_bytes = workspace_bytes - fixed;
     if (hipMemsetAsync(c->counters, 0, kCounterBytes, c->stream) != hipSuccess) {
         delete c;
         return MVLA_EHIP;
@@ -301,7 +306,7 @@ int mvla_prefill_layer(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_laye
     TIMED(ctx, KID_RMSNORM, M,
           launch_rmsnorm(xin, static_cast<const bf16_t*>(w->g_attn), M, D, cfg->rms_eps, lb.u, st));
     TIMED(ctx, KID_GEMM_QKV, M,
-          launch_gemm(lb.u, D, wqkv, M, 3 * D, D, lb.qkv, 3 * D, nullptr, 0, EPI_STORE, st));
+          launch_gemm(lb.u, D, wqkv, M, 3 * D, D, lb.qkv, 3 * D, nullptr, 0, EPI_STORE, GEMM_WS(ctx), st));
     TIMED(ctx, KID_ROPE_SPLIT, M,
           launch_rope_split(lb.qkv, pos, w->rope_cos, w->rope_sin, w->rope_len, B, S, H, dh,
                             lb.S_pad, lb.vt, st));
@@ -314,16 +319,16 @@ int mvla_prefill_layer(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_laye
           launch_attention(lb.qkv, lb.qkv + D, 3 * D, lb.vt, lb.S_pad, B, S, H, dh, lb.attn, D, st));
     TIMED(ctx, KID_GEMM_O, M,
           launch_gemm(lb.attn, D, static_cast<const bf16_t*>(w->wo), M, D, D, lb.x1, D, xin, D,
-                      EPI_RES_BF16_TO_F32, st));
+                      EPI_RES_BF16_TO_F32, GEMM_WS(ctx), st));
     TIMED(ctx, KID_RMSNORM_MLP, M,
           launch_rmsnorm_f32(lb.x1, static_cast<const bf16_t*>(w->g_mlp), M, D, cfg->rms_eps, lb.u,
                              st));
     TIMED(ctx, KID_GEMM_GATEUP, M,
           launch_gemm(lb.u, D, static_cast<const bf16_t*>(w->w_gateup), M, 2 * F, D, lb.act, F,
-                      nullptr, 0, EPI_SILU_MUL, st));
+                      nullptr, 0, EPI_SILU_MUL, GEMM_WS(ctx), st));
     TIMED(ctx, KID_GEMM_DOWN, M,
           launch_gemm(lb.act, F, static_cast<const bf16_t*>(w->w_down), M, D, F, y, D, lb.x1, D,
-                      EPI_RES_F32_TO_BF16, st));
+                      EPI_RES_F32_TO_BF16, GEMM_WS(ctx), st));
     return MVLA_OK;
 }
 
@@ -345,7 +350,7 @@ int mvla_score_only(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_w
     // query and key projections only (first 2D rows of wqkv), stored with row stride 2D
     TIMED(ctx, KID_GEMM_QKV, M,
           launch_gemm(lb.u, D, static_cast<const bf16_t*>(w->wqkv), M, 2 * D, D, lb.qkv, 2 * D,
-                      nullptr, 0, EPI_STORE, st));
+                      nullptr, 0, EPI_STORE, GEMM_WS(ctx), st));
     TIMED(ctx, KID_ROPE_SPLIT, M,
           launch_rope_split(lb.qkv, pos, w->rope_cos, w->rope_sin, w->rope_len, B, S, H, dh,
                             lb.S_pad, nullptr, st));

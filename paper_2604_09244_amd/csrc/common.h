@@ -32,8 +32,11 @@ struct mvla_ctx {
     char* ws;          // caller-owned device workspace
     size_t ws_bytes;
     // fixed areas at the head of the workspace
-    uint32_t* counters;  // kCounterWords block-arrival counters (kept at zero between calls)
-    char* scratch;       // everything after the counter area
+    uint32_t* counters;  // kCounterWords block-arrival counters (kept at zero between calls):
+                         // the first half serves the salience kernel, the second the GEMMs
+    float* gemm_partial; // fp32 partial tiles of K-split GEMM workgroups
+    size_t gemm_partial_bytes;
+    char* scratch;       // everything after the fixed areas
     size_t scratch_bytes;
 };
 
@@ -82,8 +85,12 @@ int launch_score_probs(const bf16_t* q, int q_row_stride, const bf16_t* k, int k
 // C bf16 = acc + R(fp32).  EPI_SILU_MUL: C bf16 [M, N/2] = SiLU(gate) * up.
 enum GemmEpilogue { EPI_STORE = 0, EPI_RES_BF16_TO_F32 = 1, EPI_RES_F32_TO_BF16 = 2,
                     EPI_SILU_MUL = 3 };
+// partial: fp32 scratch of gemm_partial_bytes() for K-split tiles; counters: n_counters zeroed
+// arrival counters (left at zero again when the kernel ends).
+size_t gemm_partial_bytes();
 int launch_gemm(const bf16_t* A, int lda, const bf16_t* W, int M, int N, int K, void* C, int ldc,
-                const void* R, int ldr, int epilogue, hipStream_t st);
+                const void* R, int ldr, int epilogue, float* partial, size_t partial_bytes,
+                uint32_t* counters, int n_counters, hipStream_t st);
 
 // attention.hip: causal flash attention; q,k rows inside qkv (row stride ldqkv), vt [B,H,dh,S_pad]
 int launch_attention(const bf16_t* q, const bf16_t* k, int ldqkv, const bf16_t* vt, int S_pad,

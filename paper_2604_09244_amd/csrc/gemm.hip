@@ -1,11 +1,25 @@
 // bf16 GEMM on the gfx950 matrix cores:  C[M,N] = A[M,K] * W[N,K]^T, fp32
-// accumulation.  Both operands are contiguous along K, so global loads, LDS
-// tiles and MFMA fragments all move 16-byte chunks of 8 K-elements.
+// accumulation.  Both operands are contiguous along K, so HBM reads, LDS tiles
+// and MFMA fragments all move 16-byte chunks of 8 K-elements.
 //
-// A workgroup owns a BM x BN tile of C and walks K in steps of 64 with two LDS
-// stages: while the matrix cores consume stage s, the next K-slab is already
-// in flight from HBM into registers and is written to stage s^1 afterwards.
-// Wave (wm, wn) owns a (BM/WM) x (BN/WN) sub-tile made of 32x32 MFMA tiles.
+// Data path.  K-slabs of the A and W tiles go from global memory straight into
+// LDS (global_load_lds, 16 bytes per lane, no register staging) into a ring of
+// NS stages, so the next slab(s) are in flight while the matrix cores work on
+// the current one.  The LDS image is XOR-swizzled; because a direct load
+// always lands its 64 lanes on 1 KiB of consecutive LDS, the swizzle is applied
+// on the global side: lane l fetches the chunk that belongs at its slot.
+// MFMA fragments are double-buffered in registers: the ds_reads of k-step s+1
+// (and, across the stage barrier, of the next slab) are issued before the MFMAs
+// of step s.
+//
+// Work split.  A workgroup owns a BM x BN tile; its waves own (BM/WM) x (BN/WN)
+// sub-tiles of 32x32 MFMA blocks.  Tiles that fill whole rounds of the chip
+// are computed start to finish by one workgroup.  The tiles of the last,
+// partial round are cut along K into equal ranges of k-iterations handed out
+// contiguously to the otherwise idle CUs; the pieces of a tile meet in an fp32
+// partial buffer and whichever piece arrives last (integer arrival counter)
+// adds them up in fixed piece order and runs the epilogue, so results do not
+// depend on timing.
 //
 // Epilogues: plain bf16 store; residual add (bf16 residual in, fp32 out -- or
 // fp32 residual in, bf16 out: the residual stream between the two halves of a
@@ -17,166 +31,341 @@
 
 namespace mvla {
 
-constexpr int BK = 64;
-
-// Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.
-// Every XCD gets one contiguous range of the tile sequence, and the sequence
-// itself runs through groups of GROUP_M row-tiles column by column, so the ~32
-// tiles an XCD has in flight form a GROUP_M x (32/GROUP_M) patch that re-uses
-// both its activation rows and its weight panel out of that L2.
-constexpr int GROUP_M = 8;
-__device__ __forceinline__ bool tile_coords(int tiles_m, int tiles_n, int* tm, int* tn) {
-    const int total = tiles_m * tiles_n;
-    const int per_xcd = (total + 7) >> 3;
-    const int lin = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (lin >= total) return false;
-    const int group_tiles = GROUP_M * tiles_n;
-    const int g = lin / group_tiles, r = lin % group_tiles;
-    const int gm = min(GROUP_M, tiles_m - g * GROUP_M);  // rows in this (maybe last) group
-    *tm = g * GROUP_M + r % gm;
-    *tn = r / gm;
-    return true;
+// direct global -> LDS copy of 16 bytes per lane: the wave's 64 lanes land on 1 KiB starting
+// at the wave-uniform LDS byte address lds_addr.  Not tracked by the compiler's wait-count
+// insertion; every consumer is ordered behind wait_vm<>() and a workgroup barrier.
+__device__ __forceinline__ void dma16(const void* g, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr),
+                 "v"(g)
+                 : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int BM, int BN, int WM, int WN, int EPI>
+// Partial sums cross between CUs (and XCDs, each with its own L2) through agent-coherent
+// accesses, which go to the shared level of the memory system one access at a time; nothing
+// here needs a whole-cache write-back or invalidate.
+typedef float f32q_t __attribute__((ext_vector_type(4)));
+// The wait states after the store keep the next VALU write away from the data registers
+// (a store of more than 64 bits reads them late; the compiler cannot see that inside asm).
+__device__ __forceinline__ void st16_coherent(float* p, f32q_t v) {
+    asm volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 2" ::"v"(p), "v"(v) : "memory");
+}
+// Issues the load; the value may be used only after settle() has been applied to it.
+__device__ __forceinline__ f32q_t ld16_coherent(const float* p) {
+    f32q_t v;
+    asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(p) : "memory");
+    return v;
+}
+__device__ __forceinline__ void settle(f32q_t& a, f32q_t& b, f32q_t& c, f32q_t& d) {
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d)::"memory");
+}
+
+constexpr int GROUP_M = 8;
+constexpr int SK_MIN_ITERS = 8;    // smallest K-range worth its own workgroup (in slabs)
+constexpr int SK_MAX_PIECES = 64;  // most pieces one tile is ever cut into
+
+// An LDS row holds one K-slab of a tile row: CPR = BK/8 chunks of 16 bytes.  Chunk c of row r
+// lives at slot r*CPR + (c ^ swz(r)) with swz(r) = (r >> 1) & 7 for 128-byte rows and
+// (r >> 2) & 3 for 64-byte rows: both conflict-free for the 32-row x 16-byte fragment reads
+// (measured: SQ_LDS_BANK_CONFLICT = 0).
+template <int CPR>
+__device__ __forceinline__ int swz(int row) {
+    return CPR == 8 ? (row >> 1) & 7 : (row >> 2) & 3;
+}
+
+struct GemmPlan {
+    int tiles_m, tiles_n, k_tiles;
+    int dp_tiles;     // tiles computed whole by one workgroup
+    int dp_grid;      // dp_tiles rounded up to a multiple of 8 (workgroup ids 0 .. dp_grid-1)
+    int sk_tiles;     // tiles of the last partial round, split along K
+    int sk_blocks;    // workgroups sharing the sk_tiles * k_tiles iterations
+};
+
+// Workgroup ids are dealt round-robin to the 8 XCDs (each has its own L2).  Give every XCD a
+// contiguous range of the sequence, and run the sequence through groups of GROUP_M row-tiles
+// column by column, so the tiles an XCD has in flight share activation rows and weight panels.
+__device__ __forceinline__ int xcd_chunked(int id, int total) {
+    return (id & 7) * ((total + 7) >> 3) + (id >> 3);  // may be >= total for padded ids
+}
+__device__ __forceinline__ void tile_of(int lin, int tiles_m, int tiles_n, int* tm, int* tn) {
+    const int group_tiles = GROUP_M * tiles_n;
+    const int g = lin / group_tiles, r = lin % group_tiles;
+    const int gm = min(GROUP_M, tiles_m - g * GROUP_M);
+    *tm = g * GROUP_M + r % gm;
+    *tn = r / gm;
+}
+
+// One output element through the epilogue.  For EPI_SILU_MUL, `val` is the gate and `up`
+// its partner; `col` is then the output column in the [M, N/2] result.
+template <int EPI>
+__device__ __forceinline__ void store_elem(void* Cv, int ldc, const void* Rv, int ldr, int row,
+                                           int col, float val, float up) {
+    if (EPI == EPI_SILU_MUL) {
+        const float s = val / (1.f + __expf(-val));
+        static_cast<bf16_t*>(Cv)[(size_t)row * ldc + col] = f32_to_bf16(s * up);
+    } else if (EPI == EPI_RES_BF16_TO_F32) {
+        static_cast<float*>(Cv)[(size_t)row * ldc + col] =
+            val + bf16_to_f32(static_cast<const bf16_t*>(Rv)[(size_t)row * ldr + col]);
+    } else if (EPI == EPI_RES_F32_TO_BF16) {
+        static_cast<bf16_t*>(Cv)[(size_t)row * ldc + col] =
+            f32_to_bf16(val + static_cast<const float*>(Rv)[(size_t)row * ldr + col]);
+    } else {
+        static_cast<bf16_t*>(Cv)[(size_t)row * ldc + col] = f32_to_bf16(val);
+    }
+}
+
+template <int BM, int BN, int BK, int WM, int WN, int NS, int EPI>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ W, int M, int N, int K,
-    void* __restrict__ Cv, int ldc, const void* __restrict__ Rv, int ldr, int tiles_m,
-    int tiles_n) {
+    void* __restrict__ Cv, int ldc, const void* __restrict__ Rv, int ldr, GemmPlan plan,
+    float* __restrict__ partial, uint32_t* __restrict__ counters) {
     constexpr int NT = WM * WN * 64;
-    constexpr int TM = BM / WM, TN = BN / WN;  // wave tile
-    constexpr int FM = TM / 32, FN = TN / 32;  // MFMA tiles per wave
-    constexpr int A_CH = BM * 8 / NT, B_CH = BN * 8 / NT;
-    static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile/thread mismatch");
+    constexpr int CPR = BK / 8;             // 16-byte chunks per LDS row
+    constexpr int KS = BK / 16;             // MFMA k-steps per slab
+    constexpr int TM = BM / WM, TN = BN / WN, FM = TM / 32, FN = TN / 32;
+    constexpr int STAGE = (BM + BN) * CPR;  // 16-byte slots per stage
+    constexpr int A_LD = BM * CPR / NT, B_LD = BN * CPR / NT;
+    constexpr int P = A_LD + B_LD;          // direct loads per thread per slab
+    static_assert(BM * CPR % NT == 0 && BN * CPR % NT == 0, "tile/thread mismatch");
+    static_assert(KS % 2 == 0 && NS >= 2, "");
     static_assert(EPI != EPI_SILU_MUL || FN % 2 == 0, "gate/up pairs must share a wave");
 
     extern __shared__ uint4 lds[];
-    uint4* As = lds;                 // [2][BM*8]
-    uint4* Bs = lds + 2 * BM * 8;    // [2][BN*8]
-
-    int tile_m, tile_n;
-    if (!tile_coords(tiles_m, tiles_n, &tile_m, &tile_n)) return;
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    __shared__ int sh_last;
+    __shared__ int sh_slot[SK_MAX_PIECES];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
+    const int fr = lane & 31, fg = lane >> 5;
+    const int k_tiles = plan.k_tiles;
 
-    // global source of every 16-byte chunk this thread stages
-    const uint4* a_src[A_CH];
-    const uint4* b_src[B_CH];
-    int a_dst[A_CH], b_dst[B_CH];
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) {
-        const int cid = tid + i * NT, row = cid >> 3, ch = cid & 7;
-        const int gr = min(m0 + row, M - 1);
-        a_src[i] = reinterpret_cast<const uint4*>(A + (size_t)gr * lda) + ch;
-        a_dst[i] = lds_slot(row, ch);
-    }
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) {
-        const int cid = tid + i * NT, row = cid >> 3, ch = cid & 7;
-        const int gr = min(n0 + row, N - 1);
-        b_src[i] = reinterpret_cast<const uint4*>(W + (size_t)gr * K) + ch;
-        b_dst[i] = lds_slot(row, ch);
+    // ---- which part of which tile is ours --------------------------------------------------
+    int n_seg_work;   // 1 for a whole tile, up to 2 for a K-range that straddles two tiles
+    int it_begin = 0, it_end = 0, sk_id = 0;
+    const bool is_dp = (int)blockIdx.x < plan.dp_grid;
+    if (is_dp) {
+        n_seg_work = xcd_chunked(blockIdx.x, plan.dp_tiles) < plan.dp_tiles ? 1 : 0;
+    } else {
+        sk_id = blockIdx.x - plan.dp_grid;
+        const long total = (long)plan.sk_tiles * k_tiles;
+        it_begin = (int)(total * sk_id / plan.sk_blocks);
+        it_end = (int)(total * (sk_id + 1) / plan.sk_blocks);
+        n_seg_work = (it_begin / k_tiles == (it_end - 1) / k_tiles) ? 1 : 2;
     }
 
-    f32x16_t acc[FM][FN];
-#pragma unroll
-    for (int i = 0; i < FM; ++i)
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    for (int seg = 0; seg < n_seg_work; ++seg) {
+        int lin, k0, k1, sk_tile = -1, first_blk = 0, last_blk = 0;
+        if (is_dp) {
+            lin = xcd_chunked(blockIdx.x, plan.dp_tiles);
+            k0 = 0;
+            k1 = k_tiles;
+        } else {
+            const int it0 = seg == 0 ? it_begin : (it_begin / k_tiles + 1) * k_tiles;
+            sk_tile = it0 / k_tiles;
+            const int it1 = min(it_end, (sk_tile + 1) * k_tiles);
+            k0 = it0 - sk_tile * k_tiles;
+            k1 = it1 - sk_tile * k_tiles;
+            lin = plan.dp_tiles + sk_tile;
+            // workgroups whose ranges touch this tile: the one holding its first and its last slab
+            const long total = (long)plan.sk_tiles * k_tiles;
+            first_blk = (int)((((long)sk_tile * k_tiles + 1) * plan.sk_blocks - 1) / total);
+            last_blk = (int)((((long)(sk_tile + 1) * k_tiles) * plan.sk_blocks - 1) / total);
+        }
+        int tile_m, tile_n;
+        tile_of(lin, plan.tiles_m, plan.tiles_n, &tile_m, &tile_n);
+        const int m0 = tile_m * BM, n0 = tile_n * BN;
 
-    uint4 a_reg[A_CH], b_reg[B_CH];
-    const int k_tiles = K / BK;
+        // ---- direct-load mapping: op i covers slot i*NT + tid of the A (or W) tile ----------
+        const bf16_t* a_src[A_LD];
+        const bf16_t* b_src[B_LD];
+        uint32_t a_lds[A_LD], b_lds[B_LD];
+        const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
 #pragma unroll
-    for (int i = 0; i < A_CH; ++i) a_reg[i] = a_src[i][0];
+        for (int i = 0; i < A_LD; ++i) {
+            const int sl = i * NT + tid, row = sl / CPR, ch = (sl % CPR) ^ swz<CPR>(row);
+            a_src[i] = A + (size_t)min(m0 + row, M - 1) * lda + ch * 8;
+            a_lds[i] = __builtin_amdgcn_readfirstlane(lds_base + (uint32_t)(i * NT + wave * 64) * 16u);
+        }
 #pragma unroll
-    for (int i = 0; i < B_CH; ++i) b_reg[i] = b_src[i][0];
+        for (int i = 0; i < B_LD; ++i) {
+            const int sl = i * NT + tid, row = sl / CPR, ch = (sl % CPR) ^ swz<CPR>(row);
+            b_src[i] = W + (size_t)min(n0 + row, N - 1) * K + ch * 8;
+            b_lds[i] = __builtin_amdgcn_readfirstlane(
+                lds_base + (uint32_t)(BM * CPR + i * NT + wave * 64) * 16u);
+        }
+        int a_row[FM], b_row[FN];
 #pragma unroll
-    for (int i = 0; i < A_CH; ++i) As[a_dst[i]] = a_reg[i];
+        for (int i = 0; i < FM; ++i) a_row[i] = wm * TM + i * 32 + fr;
 #pragma unroll
-    for (int i = 0; i < B_CH; ++i) Bs[b_dst[i]] = b_reg[i];
-    __syncthreads();
+        for (int j = 0; j < FN; ++j) b_row[j] = wn * TN + j * 32 + fr;
 
-    const int frag_row = lane & 31, frag_g = lane >> 5;
-    for (int kt = 0; kt < k_tiles; ++kt) {
-        const int cur = kt & 1;
-        // next K-slab goes into flight before the matrix cores start on this one (the last
-        // iteration re-fetches its own slab: harmless, keeps the loop free of branches)
-        const int nk = min(kt + 1, k_tiles - 1) * 8;
+        f32x16_t acc[FM][FN];
 #pragma unroll
-        for (int i = 0; i < A_CH; ++i) a_reg[i] = a_src[i][nk];
-#pragma unroll
-        for (int i = 0; i < B_CH; ++i) b_reg[i] = b_src[i][nk];
-        const uint4* Ac = As + cur * BM * 8;
-        const uint4* Bc = Bs + cur * BN * 8;
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            uint4 af[FM], bfr[FN];
-#pragma unroll
-            for (int i = 0; i < FM; ++i)
-                af[i] = Ac[lds_slot(wm * TM + i * 32 + frag_row, ks * 2 + frag_g)];
+        for (int i = 0; i < FM; ++i)
 #pragma unroll
             for (int j = 0; j < FN; ++j)
-                bfr[j] = Bc[lds_slot(wn * TN + j * 32 + frag_row, ks * 2 + frag_g)];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+#define MVLA_ISSUE(KT, STG)                                                                    \
+    {                                                                                          \
+        const int koff = min((KT), k1 - 1) * BK;                                               \
+        const uint32_t soff = (uint32_t)(STG) * STAGE * 16u;                                   \
+        _Pragma("unroll") for (int i = 0; i < A_LD; ++i) dma16(a_src[i] + koff, a_lds[i] + soff); \
+        _Pragma("unroll") for (int i = 0; i < B_LD; ++i) dma16(b_src[i] + koff, b_lds[i] + soff); \
+    }
+#define MVLA_READ_FRAGS(AF, BF, STG, S)                                                        \
+    {                                                                                          \
+        const uint4* As_ = lds + (STG) * STAGE;                                                \
+        const uint4* Bs_ = As_ + BM * CPR;                                                     \
+        _Pragma("unroll") for (int i = 0; i < FM; ++i) AF[i] =                                 \
+            As_[a_row[i] * CPR + (((S) * 2 + fg) ^ swz<CPR>(a_row[i]))];                            \
+        _Pragma("unroll") for (int j = 0; j < FN; ++j) BF[j] =                                 \
+            Bs_[b_row[j] * CPR + (((S) * 2 + fg) ^ swz<CPR>(b_row[j]))];                            \
+    }
+#define MVLA_MFMA(AF, BF)                                                                      \
+    {                                                                                          \
+        _Pragma("unroll") for (int i = 0; i < FM; ++i) _Pragma("unroll") for (int j = 0; j < FN; ++j) \
+            acc[i][j] = mfma32(AF[i], BF[j], acc[i][j]);                                       \
+    }
+
+        // every thread of the workgroup has left the previous segment's LDS reads behind
+        __syncthreads();
+        // ---- prologue: NS-1 slabs in flight, then one more behind the first barrier ---------
+#pragma unroll
+        for (int s = 0; s < NS - 1; ++s) MVLA_ISSUE(k0 + s, s)
+        uint4 af0[FM], bf0[FN], af1[FM], bf1[FN];
+        wait_vm<(NS - 2) * P>();
+        __syncthreads();
+        MVLA_ISSUE(k0 + NS - 1, NS - 1)
+        MVLA_READ_FRAGS(af0, bf0, 0, 0)
+        int stage = 0;
+        for (int kt = k0; kt < k1; ++kt) {
+            const int nstage = stage + 1 == NS ? 0 : stage + 1;
+#pragma unroll
+            for (int s = 0; s < KS - 2; s += 2) {
+                MVLA_READ_FRAGS(af1, bf1, stage, s + 1)
+                __builtin_amdgcn_sched_barrier(0);
+                MVLA_MFMA(af0, bf0)
+                __builtin_amdgcn_sched_barrier(0);
+                MVLA_READ_FRAGS(af0, bf0, stage, s + 2)
+                __builtin_amdgcn_sched_barrier(0);
+                MVLA_MFMA(af1, bf1)
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            MVLA_READ_FRAGS(af1, bf1, stage, KS - 1)
+            __builtin_amdgcn_sched_barrier(0);
+            MVLA_MFMA(af0, bf0)
+            __builtin_amdgcn_sched_barrier(0);
+            // slab kt+1 has landed for every wave; slab kt's stage is free for slab kt+NS
+            wait_vm<(NS - 2) * P>();
+            __syncthreads();
+            MVLA_ISSUE(kt + NS, stage)
+            MVLA_READ_FRAGS(af0, bf0, nstage, 0)
+            __builtin_amdgcn_sched_barrier(0);
+            MVLA_MFMA(af1, bf1)
+            __builtin_amdgcn_sched_barrier(0);
+            stage = nstage;
+        }
+        wait_vm<0>();
+#undef MVLA_ISSUE
+#undef MVLA_READ_FRAGS
+#undef MVLA_MFMA
+
+        // ---- K-split tiles: park the partial sums; the last piece to arrive finishes --------
+        const int n_pieces = is_dp ? 1 : last_blk - first_blk + 1;
+        if (n_pieces > 1) {
+            // slot 0 of a workgroup holds the piece of the tile its range starts in, slot 1 the next
+            const int my_slot = 2 * sk_id + (seg == 0 ? 0 : 1);
+            float* mine = partial + (size_t)my_slot * (BM * BN);
+            // 16 bytes per lane: register quad c of block (i,j) goes to float offset
+            // (((i*FN + j)*4 + c)*NT + tid)*4 of the slot
 #pragma unroll
             for (int i = 0; i < FM; ++i)
 #pragma unroll
-                for (int j = 0; j < FN; ++j) acc[i][j] = mfma32(af[i], bfr[j], acc[i][j]);
-        }
-        uint4* An = As + (cur ^ 1) * BM * 8;
-        uint4* Bn = Bs + (cur ^ 1) * BN * 8;
+                for (int j = 0; j < FN; ++j)
 #pragma unroll
-        for (int i = 0; i < A_CH; ++i) An[a_dst[i]] = a_reg[i];
+                    for (int c = 0; c < 4; ++c) {
+                        f32q_t q = {acc[i][j][4 * c], acc[i][j][4 * c + 1], acc[i][j][4 * c + 2],
+                                    acc[i][j][4 * c + 3]};
+                        st16_coherent(&mine[(((i * FN + j) * 4 + c) * NT + tid) * 4], q);
+                    }
+            wait_vm<0>();     // this thread's partial sums have reached the coherent level
+            __syncthreads();  // ... and so have everyone else's in the workgroup
+            if (tid == 0) {
+                const uint32_t prev = __hip_atomic_fetch_add(&counters[sk_tile], 1u, __ATOMIC_RELAXED,
+                                                             __HIP_MEMORY_SCOPE_AGENT);
+                sh_last = (prev == (uint32_t)(n_pieces - 1));
+                if (sh_last)
+                    __hip_atomic_store(&counters[sk_tile], 0u, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+            }
+            if (tid < n_pieces) {
+                // piece of workgroup b: its slot 0 if b's range starts inside this tile, else 1
+                const long total = (long)plan.sk_tiles * k_tiles;
+                const int b = first_blk + tid;
+                const int b_start_tile = (int)(total * b / plan.sk_blocks) / k_tiles;
+                sh_slot[tid] = 2 * b + (b_start_tile == sk_tile ? 0 : 1);
+            }
+            __syncthreads();
+            if (!sh_last) continue;
+            // Sum the pieces in piece order, one 32x32 block (gate and up blocks together) at a
+            // time, and send each element through the epilogue.
+            constexpr int JS2 = EPI == EPI_SILU_MUL ? 2 : 1;
+#pragma unroll 1
+            for (int ij = 0; ij < FM * FN; ij += JS2) {
+                const int i = ij / FN, j = ij % FN;
+                f32q_t sum[JS2][4];
 #pragma unroll
-        for (int i = 0; i < B_CH; ++i) Bn[b_dst[i]] = b_reg[i];
-        __syncthreads();
-    }
-
-    // ---- epilogue: lane holds column (lane%32) and rows mfma32_row(v, lane) of each tile ----
-    const int col_in_tile = lane & 31;
-    bf16_t* C = static_cast<bf16_t*>(Cv);
+                for (int h = 0; h < JS2; ++h)
 #pragma unroll
-    for (int i = 0; i < FM; ++i) {
-        const int row_base = m0 + wm * TM + i * 32;
-        if (EPI == EPI_SILU_MUL) {
+                    for (int c = 0; c < 4; ++c) sum[h][c] = f32q_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+                for (int pc = 0; pc < n_pieces; ++pc) {
+                    const float* src = partial + (size_t)sh_slot[pc] * (BM * BN) + tid * 4;
 #pragma unroll
-            for (int j = 0; j < FN; j += 2) {
-                const int ncol = n0 + wn * TN + j * 32;  // gate block start (multiple of 64)
-                const int ocol = (ncol >> 1) + col_in_tile;
-                if (ncol + 32 + col_in_tile < N) {
+                    for (int h = 0; h < JS2; ++h) {
+                        f32q_t t0 = ld16_coherent(&src[((ij + h) * 4 + 0) * NT * 4]);
+                        f32q_t t1 = ld16_coherent(&src[((ij + h) * 4 + 1) * NT * 4]);
+                        f32q_t t2 = ld16_coherent(&src[((ij + h) * 4 + 2) * NT * 4]);
+                        f32q_t t3 = ld16_coherent(&src[((ij + h) * 4 + 3) * NT * 4]);
+                        settle(t0, t1, t2, t3);
+                        sum[h][0] += t0; sum[h][1] += t1; sum[h][2] += t2; sum[h][3] += t3;
+                    }
+                }
+                const int ncol = n0 + wn * TN + j * 32;
+                if (ncol + (JS2 - 1) * 32 + fr < N) {
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
-                        const int row = row_base + mfma32_row(v, lane);
-                        if (row < M) {
-                            const float g = acc[i][j][v], u = acc[i][j + 1][v];
-                            const float s = g / (1.f + __expf(-g));
-                            C[(size_t)row * ldc + ocol] = f32_to_bf16(s * u);
-                        }
+                        const int row = m0 + wm * TM + i * 32 + mfma32_row(v, lane);
+                        if (row < M)
+                            store_elem<EPI>(Cv, ldc, Rv, ldr, row,
+                                            JS2 == 2 ? (ncol >> 1) + fr : ncol + fr,
+                                            sum[0][v >> 2][v & 3], sum[JS2 - 1][v >> 2][v & 3]);
                     }
                 }
             }
-        } else {
+            continue;
+        }
+
+        // ---- epilogue: lane holds column (lane%32), rows mfma32_row(v, lane) of each block ----
+        constexpr int JS = EPI == EPI_SILU_MUL ? 2 : 1;
 #pragma unroll
-            for (int j = 0; j < FN; ++j) {
-                const int col = n0 + wn * TN + j * 32 + col_in_tile;
-                if (col < N) {
+        for (int i = 0; i < FM; ++i) {
+            const int row_base = m0 + wm * TM + i * 32;
+#pragma unroll
+            for (int j = 0; j < FN; j += JS) {
+                const int ncol = n0 + wn * TN + j * 32;
+                if (ncol + (JS - 1) * 32 + fr < N) {
+                    const int ocol = JS == 2 ? (ncol >> 1) + fr : ncol + fr;
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const int row = row_base + mfma32_row(v, lane);
-                        if (row < M) {
-                            float val = acc[i][j][v];
-                            if (EPI == EPI_RES_BF16_TO_F32) {
-                                val += bf16_to_f32(
-                                    static_cast<const bf16_t*>(Rv)[(size_t)row * ldr + col]);
-                                static_cast<float*>(Cv)[(size_t)row * ldc + col] = val;
-                            } else {
-                                if (EPI == EPI_RES_F32_TO_BF16)
-                                    val += static_cast<const float*>(Rv)[(size_t)row * ldr + col];
-                                C[(size_t)row * ldc + col] = f32_to_bf16(val);
-                            }
-                        }
+                        if (row < M)
+                            store_elem<EPI>(Cv, ldc, Rv, ldr, row, ocol, acc[i][j][v],
+                                            acc[i][JS == 2 ? j + 1 : j][v]);
                     }
                 }
             }
@@ -184,24 +373,63 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     }
 }
 
-template <int BM, int BN, int WM, int WN>
+// ---- host side ------------------------------------------------------------------------------
+constexpr int kNumCUs = 256;
+
+// Split of the tile set into whole-tile workgroups and K-split workgroups for `slots`
+// concurrently resident workgroups.
+static GemmPlan make_plan(int M, int N, int K, int BM, int BN, int BK, int slots, int sk_pct) {
+    GemmPlan p;
+    p.tiles_m = (M + BM - 1) / BM;
+    p.tiles_n = (N + BN - 1) / BN;
+    p.k_tiles = K / BK;
+    const int tiles = p.tiles_m * p.tiles_n;
+    const int rem = tiles % slots;
+    // a last round that is at least sk_pct % full is not worth cutting up
+    if (rem == 0 || rem * 100 >= slots * sk_pct) {
+        p.dp_tiles = tiles;
+        p.dp_grid = (tiles + 7) / 8 * 8;
+        p.sk_tiles = 0;
+        p.sk_blocks = 0;
+        return p;
+    }
+    p.dp_tiles = tiles - rem;
+    p.dp_grid = (p.dp_tiles + 7) / 8 * 8;
+    p.sk_tiles = rem;
+    const long iters = (long)rem * p.k_tiles;
+    long blocks = slots;
+    if (iters / blocks < SK_MIN_ITERS) blocks = iters / SK_MIN_ITERS;
+    if (blocks > (long)rem * (SK_MAX_PIECES / 2 - 1)) blocks = (long)rem * (SK_MAX_PIECES / 2 - 1);
+    if (blocks < rem) blocks = rem;  // a workgroup never spans more than two tiles
+    p.sk_blocks = (int)blocks;
+    return p;
+}
+
+template <int BM, int BN, int BK, int WM, int WN, int NS>
 static int launch_cfg(const bf16_t* A, int lda, const bf16_t* W, int M, int N, int K, void* C,
-                      int ldc, const void* R, int ldr, int epi, hipStream_t st) {
-    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
-    const int total = tiles_m * tiles_n;
-    const int grid = ((total + 7) / 8) * 8;
-    const size_t lds = (size_t)2 * (BM + BN) * 8 * sizeof(uint4);
+                      int ldc, const void* R, int ldr, int epi, int slots_per_cu, int sk_pct,
+                      float* partial,
+                      size_t partial_bytes, uint32_t* counters, int n_counters, hipStream_t st) {
+    GemmPlan plan = make_plan(M, N, K, BM, BN, BK, kNumCUs * slots_per_cu, sk_pct);
+    if (plan.sk_blocks > 0) {
+        const size_t need = (size_t)2 * plan.sk_blocks * BM * BN * sizeof(float);
+        if (need > partial_bytes || plan.sk_tiles > n_counters) {  // no room: whole tiles only
+            plan.dp_tiles += plan.sk_tiles;
+            plan.dp_grid = (plan.dp_tiles + 7) / 8 * 8;
+            plan.sk_tiles = plan.sk_blocks = 0;
+        }
+    }
+    const int grid = plan.dp_grid + plan.sk_blocks;
+    const size_t lds = (size_t)NS * (BM + BN) * (BK / 8) * sizeof(uint4);
     dim3 block(WM * WN * 64);
 #define MVLA_GEMM_LAUNCH(E)                                                                   \
     do {                                                                                      \
-        auto kern = gemm_kernel<BM, BN, WM, WN, E>;                                           \
-        if (lds > 64 * 1024) {                                                                \
-            MVLA_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),           \
-                                               hipFuncAttributeMaxDynamicSharedMemorySize,    \
-                                               (int)lds));                                    \
-        }                                                                                     \
+        auto kern = gemm_kernel<BM, BN, BK, WM, WN, NS, E>;                                       \
+        MVLA_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),               \
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,        \
+                                           (int)lds));                                        \
         hipLaunchKernelGGL(kern, dim3(grid), block, lds, st, A, lda, W, M, N, K, C, ldc, R,   \
-                           ldr, tiles_m, tiles_n);                                            \
+                           ldr, plan, partial, counters);                                     \
     } while (0)
     if (epi == EPI_STORE) MVLA_GEMM_LAUNCH(EPI_STORE);
     else if (epi == EPI_RES_BF16_TO_F32) MVLA_GEMM_LAUNCH(EPI_RES_BF16_TO_F32);
@@ -212,15 +440,62 @@ static int launch_cfg(const bf16_t* A, int lda, const bf16_t* W, int M, int N, i
     return MVLA_OK;
 }
 
+size_t gemm_partial_bytes() {
+    // two partial tiles per K-split workgroup; 256x256 tiles on 256 slots == 128x128 on 512
+    return (size_t)2 * kNumCUs * 256 * 256 * sizeof(float);
+}
+
+// Tile configurations and the time one round of them takes at K = 4096 on this chip (measured
+// once, microseconds; only their ratios matter for the choice below).
+struct TileCfg {
+    int BM, BN, slots_per_cu;
+    float round_us;
+};
+constexpr int kNumCfgs = 4;
+static const TileCfg kCfgs[kNumCfgs] = {
+    {256, 256, 1, 110.f},  // K-slab 64, eight waves of 128x64, two stages
+    {256, 128, 1, 62.f},   // K-slab 64, eight waves of 64x64, three stages
+    {128, 128, 2, 67.f},   // K-slab 64, four waves of 64x64, two stages, two workgroups per CU
+    {128, 128, 1, 37.f},   // K-slab 64, four waves of 64x64, three stages
+};
+constexpr int kSplitPct = 50;        // cut the last round along K only when it is under half full
+constexpr float kSplitOverhead = 0.3f;  // cost of the partial-sum exchange, in rounds
+
+// Estimated rounds of work for a tile configuration: whole rounds, plus the last partial
+// round either as a full round or, when K-split, as its fill fraction plus the exchange cost.
+static float estimate_us(const TileCfg& c, int M, int N, int K) {
+    const long tiles = (long)((M + c.BM - 1) / c.BM) * ((N + c.BN - 1) / c.BN);
+    const int slots = kNumCUs * c.slots_per_cu;
+    const long full = tiles / slots, rem = tiles % slots;
+    float rounds = (float)full;
+    if (rem) rounds += (rem * 100 < (long)slots * kSplitPct) ? (float)rem / slots + kSplitOverhead : 1.f;
+    return rounds * c.round_us * (float)K / 4096.f;
+}
+
 int launch_gemm(const bf16_t* A, int lda, const bf16_t* W, int M, int N, int K, void* C, int ldc,
-                const void* R, int ldr, int epilogue, hipStream_t st) {
+                const void* R, int ldr, int epilogue, float* partial, size_t partial_bytes,
+                uint32_t* counters, int n_counters, hipStream_t st) {
     if (M <= 0 || N <= 0) return MVLA_OK;
-    if (K % BK != 0 || lda % 8 != 0) return MVLA_EUNSUPPORTED;
+    if (K < 64 || K % 64 != 0 || lda % 8 != 0) return MVLA_EUNSUPPORTED;
     if (epilogue == EPI_SILU_MUL && N % 64 != 0) return MVLA_EUNSUPPORTED;
-    // Large problems: 256x128 tiles (4 waves of 128x64).  Small M: 128x128 tiles.
-    if (M >= 1024)
-        return launch_cfg<256, 128, 2, 2>(A, lda, W, M, N, K, C, ldc, R, ldr, epilogue, st);
-    return launch_cfg<128, 128, 2, 2>(A, lda, W, M, N, K, C, ldc, R, ldr, epilogue, st);
+    int best = 0;
+    float best_us = estimate_us(kCfgs[0], M, N, K);
+    for (int i = 1; i < kNumCfgs; ++i) {
+        const float t = estimate_us(kCfgs[i], M, N, K);
+        if (t < best_us) {
+            best_us = t;
+            best = i;
+        }
+    }
+#define MVLA_ARGS A, lda, W, M, N, K, C, ldc, R, ldr, epilogue, kCfgs[best].slots_per_cu, kSplitPct, \
+                  partial, partial_bytes, counters, n_counters, st
+    switch (best) {
+        case 0: return launch_cfg<256, 256, 64, 2, 4, 2>(MVLA_ARGS);
+        case 1: return launch_cfg<256, 128, 64, 4, 2, 3>(MVLA_ARGS);
+        case 2: return launch_cfg<128, 128, 64, 2, 2, 2>(MVLA_ARGS);
+        default: return launch_cfg<128, 128, 64, 2, 2, 3>(MVLA_ARGS);
+    }
+#undef MVLA_ARGS
 }
 
 }  // namespace mvla

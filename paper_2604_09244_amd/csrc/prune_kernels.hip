@@ -94,21 +94,24 @@ __global__ __launch_bounds__(SAL_THREADS) void salience_kernel(
     }
     // several blocks share this column chunk: publish, last arrival finishes
     float* pslot = partial + ((size_t)(b * gridDim.x + chunk) * n_split) * CW;
-    if (tid < CW) pslot[(size_t)split * CW + tid] = tot;
-    __threadfence();
+    // partial sums cross CUs/XCDs through agent-coherent accesses (no cache-wide flushes)
+    if (tid < CW)
+        __hip_atomic_store(&pslot[(size_t)split * CW + tid], tot, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (tid == 0) {
         uint32_t* ctr = counters + (b * gridDim.x + chunk);
         const uint32_t prev =
-            __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         is_last = (prev == (uint32_t)(n_split - 1));
         if (is_last) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
     if (!is_last) return;
-    __threadfence();
     if (tid < CW && c < n_vis) {
         float s = 0.f;
+#pragma unroll 8
         for (int i = 0; i < n_split; ++i)
             s += __hip_atomic_load(&pslot[(size_t)i * CW + tid], __ATOMIC_RELAXED,
                                    __HIP_MEMORY_SCOPE_AGENT);
@@ -142,7 +145,7 @@ int launch_salience(const float* attn, int B, int H, int Nq, int S, int n_vis, f
     const bool vec4 = (S % 4 == 0) && ((reinterpret_cast<uintptr_t>(attn) & 15) == 0);
     int chunks, n_split, rps;
     salience_shape(B, R, n_vis, vec4 ? 4 : 1, &chunks, &n_split, &rps);
-    if ((long)B * chunks > kCounterWords) return MVLA_EUNSUPPORTED;
+    if ((long)B * chunks > kCounterWords / 2) return MVLA_EUNSUPPORTED;  // first half is ours
     dim3 grid(chunks, n_split, B);
     const float inv_rows = 1.0f / (float)R;
     if (vec4)
