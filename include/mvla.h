@@ -128,7 +128,7 @@ int mvla_prune_step(mvla_ctx* ctx, const float* attn, int H, int Nq, const void*
 /* ------------------------------------------------------------------------ */
 
 typedef struct {
-    int D;         /* hidden size, multiple of 64                              */
+    int D;         /* hidden size, multiple of 64, at most 8192                */
     int H;         /* attention heads                                          */
     int dh;        /* head dim: 64 or 128; H*dh == D                           */
     int F;         /* MLP width, multiple of 64                                */

@@ -46,7 +46,7 @@ int check_layer_args(const mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_
     if (cfg->D <= 0 || cfg->H <= 0 || cfg->dh <= 0 || cfg->F <= 0) return MVLA_EINVAL;
     if (cfg->H * cfg->dh != cfg->D) return MVLA_EINVAL;
     if (cfg->dh != 64 && cfg->dh != 128) return MVLA_EUNSUPPORTED;
-    if (cfg->D % 64 != 0 || cfg->F % 64 != 0) return MVLA_EUNSUPPORTED;
+    if (cfg->D % 64 != 0 || cfg->F % 64 != 0 || cfg->D > 8192) return MVLA_EUNSUPPORTED;
     if (!(cfg->rms_eps >= 0.f)) return MVLA_EINVAL;
     if (!w->wqkv || !w->g_attn || !w->rope_cos || !w->rope_sin || w->rope_len <= 0)
         return MVLA_EINVAL;

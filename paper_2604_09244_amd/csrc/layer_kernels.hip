@@ -7,100 +7,97 @@
 namespace mvla {
 
 // ---------------------------------------------------------------------------
-// RMSNorm: out = x * gain / sqrt(mean(x^2) + eps), one wave per row, fp32 maths.
+// RMSNorm: out = x * gain / sqrt(mean(x^2) + eps), fp32 maths, bf16 out.  One
+// workgroup per row; a thread keeps its 16-byte chunks in registers between the
+// sum of squares and the scaling, so the row is read once.
 // ---------------------------------------------------------------------------
 constexpr int NORM_THREADS = 256;
+constexpr int NORM_MAX_CHUNKS = 4;  // per thread: D <= 256 * 4 * 8 = 8192
 
-__global__ __launch_bounds__(NORM_THREADS) void rmsnorm_kernel(const uint4* __restrict__ x,
-                                                               const uint4* __restrict__ gain,
-                                                               int M, int row_vec, float inv_d,
-                                                               float eps, uint4* __restrict__ out) {
-    const int row = blockIdx.x * (NORM_THREADS / 64) + (threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63;
-    if (row >= M) return;
-    const uint4* xr = x + (size_t)row * row_vec;
-    float ss = 0.f;
-    for (int c = lane; c < row_vec; c += 64) {
-        const uint4 v = xr[c];
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+__device__ __forceinline__ float block_sum(float v, float* sh) {
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float t = 0.f;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float lo = __uint_as_float(w[i] << 16), hi = __uint_as_float(w[i] & 0xFFFF0000u);
-            ss += lo * lo + hi * hi;
+    for (int w = 0; w < NORM_THREADS / 64; ++w) t += sh[w];
+    return t;
+}
+
+// IN_F32: the row is fp32 (the mid-layer residual stream), else bf16.
+template <bool IN_F32>
+__global__ __launch_bounds__(NORM_THREADS) void rmsnorm_kernel(const void* __restrict__ xv,
+                                                               const uint4* __restrict__ gain,
+                                                               int row_vec /* D/8 */, float inv_d,
+                                                               float eps, uint4* __restrict__ out) {
+    __shared__ float sh[NORM_THREADS / 64];
+    const int row = blockIdx.x, tid = threadIdx.x;
+    float vals[NORM_MAX_CHUNKS][8];
+    float ss = 0.f;
+#pragma unroll
+    for (int k = 0; k < NORM_MAX_CHUNKS; ++k) {
+        const int c = tid + k * NORM_THREADS;
+        if (c < row_vec) {
+            if (IN_F32) {
+                const float4* xr = static_cast<const float4*>(xv) + (size_t)row * row_vec * 2;
+                const float4 a = xr[2 * c], b = xr[2 * c + 1];
+                vals[k][0] = a.x; vals[k][1] = a.y; vals[k][2] = a.z; vals[k][3] = a.w;
+                vals[k][4] = b.x; vals[k][5] = b.y; vals[k][6] = b.z; vals[k][7] = b.w;
+            } else {
+                const uint4 v = (static_cast<const uint4*>(xv) + (size_t)row * row_vec)[c];
+                const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    vals[k][2 * i] = __uint_as_float(w[i] << 16);
+                    vals[k][2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) ss += vals[k][i] * vals[k][i];
         }
     }
-    for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+    ss = block_sum(ss, sh);
     const float scale = 1.0f / sqrtf(ss * inv_d + eps);
     uint4* orow = out + (size_t)row * row_vec;
-    for (int c = lane; c < row_vec; c += 64) {
-        const uint4 v = xr[c], g = gain[c];
-        const uint32_t w[4] = {v.x, v.y, v.z, v.w}, gw[4] = {g.x, g.y, g.z, g.w};
-        uint32_t r[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float lo = __uint_as_float(w[i] << 16) * scale * __uint_as_float(gw[i] << 16);
-            const float hi = __uint_as_float(w[i] & 0xFFFF0000u) * scale *
-                             __uint_as_float(gw[i] & 0xFFFF0000u);
-            r[i] = pack_bf16x2(lo, hi);
+    for (int k = 0; k < NORM_MAX_CHUNKS; ++k) {
+        const int c = tid + k * NORM_THREADS;
+        if (c < row_vec) {
+            const uint4 g = gain[c];
+            const uint32_t gw[4] = {g.x, g.y, g.z, g.w};
+            uint32_t r[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                r[i] = pack_bf16x2(vals[k][2 * i] * scale * __uint_as_float(gw[i] << 16),
+                                   vals[k][2 * i + 1] * scale * __uint_as_float(gw[i] & 0xFFFF0000u));
+            orow[c] = make_uint4(r[0], r[1], r[2], r[3]);
         }
-        orow[c] = make_uint4(r[0], r[1], r[2], r[3]);
     }
+}
+
+static int launch_rmsnorm_any(const void* x, bool f32, const bf16_t* gain, int M, int D, float eps,
+                              bf16_t* out, hipStream_t st) {
+    if (M <= 0) return MVLA_OK;
+    if (D % 8 != 0 || D / 8 > NORM_THREADS * NORM_MAX_CHUNKS) return MVLA_EUNSUPPORTED;
+    if (f32)
+        hipLaunchKernelGGL(rmsnorm_kernel<true>, dim3(M), dim3(NORM_THREADS), 0, st, x,
+                           reinterpret_cast<const uint4*>(gain), D / 8, 1.0f / (float)D, eps,
+                           reinterpret_cast<uint4*>(out));
+    else
+        hipLaunchKernelGGL(rmsnorm_kernel<false>, dim3(M), dim3(NORM_THREADS), 0, st, x,
+                           reinterpret_cast<const uint4*>(gain), D / 8, 1.0f / (float)D, eps,
+                           reinterpret_cast<uint4*>(out));
+    MVLA_HIP_CHECK(hipGetLastError());
+    return MVLA_OK;
 }
 
 int launch_rmsnorm(const bf16_t* x, const bf16_t* gain, int M, int D, float eps, bf16_t* out,
                    hipStream_t st) {
-    if (M <= 0) return MVLA_OK;
-    const int rows_per_block = NORM_THREADS / 64;
-    hipLaunchKernelGGL(rmsnorm_kernel, dim3((M + rows_per_block - 1) / rows_per_block),
-                       dim3(NORM_THREADS), 0, st, reinterpret_cast<const uint4*>(x),
-                       reinterpret_cast<const uint4*>(gain), M, D / 8, 1.0f / (float)D, eps,
-                       reinterpret_cast<uint4*>(out));
-    MVLA_HIP_CHECK(hipGetLastError());
-    return MVLA_OK;
+    return launch_rmsnorm_any(x, false, gain, M, D, eps, out, st);
 }
-
-// Same, reading the fp32 residual stream (eight floats per 16-byte output chunk).
-__global__ __launch_bounds__(NORM_THREADS) void rmsnorm_f32_kernel(const float4* __restrict__ x,
-                                                                   const uint4* __restrict__ gain,
-                                                                   int M, int row_vec, float inv_d,
-                                                                   float eps,
-                                                                   uint4* __restrict__ out) {
-    const int row = blockIdx.x * (NORM_THREADS / 64) + (threadIdx.x >> 6);
-    const int lane = threadIdx.x & 63;
-    if (row >= M) return;
-    const float4* xr = x + (size_t)row * row_vec * 2;
-    float ss = 0.f;
-    for (int c = lane; c < row_vec * 2; c += 64) {
-        const float4 v = xr[c];
-        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
-    }
-    for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
-    const float scale = 1.0f / sqrtf(ss * inv_d + eps);
-    uint4* orow = out + (size_t)row * row_vec;
-    for (int c = lane; c < row_vec; c += 64) {
-        const float4 a = xr[2 * c], b = xr[2 * c + 1];
-        const uint4 g = gain[c];
-        const float xs[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-        const uint32_t gw[4] = {g.x, g.y, g.z, g.w};
-        uint32_t r[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            r[i] = pack_bf16x2(xs[2 * i] * scale * __uint_as_float(gw[i] << 16),
-                               xs[2 * i + 1] * scale * __uint_as_float(gw[i] & 0xFFFF0000u));
-        orow[c] = make_uint4(r[0], r[1], r[2], r[3]);
-    }
-}
-
 int launch_rmsnorm_f32(const float* x, const bf16_t* gain, int M, int D, float eps, bf16_t* out,
                        hipStream_t st) {
-    if (M <= 0) return MVLA_OK;
-    const int rows_per_block = NORM_THREADS / 64;
-    hipLaunchKernelGGL(rmsnorm_f32_kernel, dim3((M + rows_per_block - 1) / rows_per_block),
-                       dim3(NORM_THREADS), 0, st, reinterpret_cast<const float4*>(x),
-                       reinterpret_cast<const uint4*>(gain), M, D / 8, 1.0f / (float)D, eps,
-                       reinterpret_cast<uint4*>(out));
-    MVLA_HIP_CHECK(hipGetLastError());
-    return MVLA_OK;
+    return launch_rmsnorm_any(x, true, gain, M, D, eps, out, st);
 }
 
 // ---------------------------------------------------------------------------
@@ -333,12 +330,151 @@ __global__ __launch_bounds__(SC_THREADS) void score_probs_kernel(
     }
 }
 
+// Single-pass variant for S <= 8 waves * KBW key blocks * 32 keys: every wave keeps the logits
+// of its KBW key blocks in registers, so Q*K^T is computed once.
+constexpr int SCR_THREADS = 512;
+constexpr int SCR_WAVES = SCR_THREADS / 64;
+
+template <int DH, int KBW>
+__global__ __launch_bounds__(SCR_THREADS) void score_probs_reg_kernel(
+    const bf16_t* __restrict__ q, int ldq, const bf16_t* __restrict__ k, int ldk,
+    const float* __restrict__ key_bias, int S, int H, int nq, float scale,
+    float* __restrict__ probs) {
+    constexpr int STEPS = DH / 16;
+    const int qt = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int fr = lane & 31, fg = lane >> 5;
+    const int row0 = S - nq, qi0 = qt * 32;
+    uint4 qf[STEPS];
+    {
+        const int qi = min(qi0 + fr, nq - 1);
+        const bf16_t* src = q + ((size_t)b * S + row0 + qi) * ldq + h * DH + fg * 8;
+#pragma unroll
+        for (int st = 0; st < STEPS; ++st) qf[st] = *reinterpret_cast<const uint4*>(src + st * 16);
+    }
+    const int n_kb = (S + 31) / 32;
+    const bf16_t* kbase = k + (size_t)b * S * ldk + h * DH + fg * 8;
+    const float* bias = key_bias ? key_bias + (size_t)b * S : nullptr;
+
+    f32x16_t lg[KBW];
+    float run_m[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) run_m[v] = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < KBW; ++i) {
+        const int kb = wave + SCR_WAVES * i;
+        const int key = kb * 32 + fr;
+        const int kr = min(key, S - 1);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) lg[i][v] = 0.f;
+        if (kb < n_kb) {   // wave-uniform
+            const bf16_t* ksrc = kbase + (size_t)kr * ldk;
+#pragma unroll
+            for (int st = 0; st < STEPS; ++st) {
+                const uint4 kf = *reinterpret_cast<const uint4*>(ksrc + st * 16);
+                lg[i] = mfma32(qf[st], kf, lg[i]);
+            }
+        }
+        const float kbias = (bias && key < S) ? bias[key] : 0.f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int qi = qi0 + mfma32_row(v, lane);
+            const bool valid = kb < n_kb && key < S && key <= row0 + qi;
+            lg[i][v] = valid ? lg[i][v] * scale + kbias : -INFINITY;
+            run_m[v] = fmaxf(run_m[v], lg[i][v]);
+        }
+    }
+    __shared__ float sh_m[SCR_WAVES][32], sh_l[SCR_WAVES][32];
+    // row maxima: over the 32 lanes of a half-wave, then over the waves
+#pragma unroll
+    for (int v = 0; v < 16; ++v)
+        for (int o = 16; o > 0; o >>= 1) run_m[v] = fmaxf(run_m[v], __shfl_xor(run_m[v], o));
+    if (fr == 0) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sh_m[wave][mfma32_row(v, lane)] = run_m[v];
+    }
+    __syncthreads();
+    float run_l[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int r = mfma32_row(v, lane);
+        float gm = sh_m[0][r];
+#pragma unroll
+        for (int w = 1; w < SCR_WAVES; ++w) gm = fmaxf(gm, sh_m[w][r]);
+        run_m[v] = gm;     // finite: key 0 is visible to every query
+        run_l[v] = 0.f;
+    }
+#pragma unroll
+    for (int i = 0; i < KBW; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            lg[i][v] = __expf(lg[i][v] - run_m[v]);   // exp(-inf) = 0 for masked entries
+            run_l[v] += lg[i][v];
+        }
+#pragma unroll
+    for (int v = 0; v < 16; ++v)
+        for (int o = 16; o > 0; o >>= 1) run_l[v] += __shfl_xor(run_l[v], o);
+    if (fr == 0) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sh_l[wave][mfma32_row(v, lane)] = run_l[v];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int r = mfma32_row(v, lane);
+        float gl = 0.f;
+#pragma unroll
+        for (int w = 0; w < SCR_WAVES; ++w) gl += sh_l[w][r];
+        run_l[v] = 1.0f / gl;
+    }
+#pragma unroll
+    for (int i = 0; i < KBW; ++i) {
+        const int kb = wave + SCR_WAVES * i;
+        const int key = kb * 32 + fr;
+        if (kb < n_kb && key < S) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int qi = qi0 + mfma32_row(v, lane);
+                if (qi < nq) probs[(((size_t)b * H + h) * nq + qi) * S + key] = lg[i][v] * run_l[v];
+            }
+        }
+    }
+}
+
+template <int DH>
+static bool launch_score_reg(const bf16_t* q, int ldq, const bf16_t* k, int ldk,
+                             const float* key_bias, int B, int S, int H, int nq, float scale,
+                             float* probs, hipStream_t st) {
+    dim3 grid((nq + 31) / 32, H, B);
+    const int need = ((S + 31) / 32 + SCR_WAVES - 1) / SCR_WAVES;  // key blocks per wave
+#define MVLA_SCR(KBW)                                                                          \
+    hipLaunchKernelGGL((score_probs_reg_kernel<DH, KBW>), grid, dim3(SCR_THREADS), 0, st, q, ldq, \
+                       k, ldk, key_bias, S, H, nq, scale, probs)
+    if (need <= 3) MVLA_SCR(3);
+    else if (need <= 6) MVLA_SCR(6);
+    else if (need <= 8) MVLA_SCR(8);
+    else return false;
+#undef MVLA_SCR
+    return true;
+}
+
 int launch_score_probs(const bf16_t* q, int q_row_stride, const bf16_t* k, int k_row_stride,
                        const float* key_bias, int B, int S, int H, int dh, int nq, float* probs,
                        hipStream_t st) {
     if (B <= 0 || nq <= 0) return MVLA_OK;
     dim3 grid((nq + 31) / 32, H, B);
     const float scale = 1.0f / sqrtf((float)dh);
+    // register-resident single pass when the row fits, else two passes
+    if (dh == 128 && launch_score_reg<128>(q, q_row_stride, k, k_row_stride, key_bias, B, S, H, nq,
+                                           scale, probs, st)) {
+        MVLA_HIP_CHECK(hipGetLastError());
+        return MVLA_OK;
+    }
+    if (dh == 64 && launch_score_reg<64>(q, q_row_stride, k, k_row_stride, key_bias, B, S, H, nq,
+                                         scale, probs, st)) {
+        MVLA_HIP_CHECK(hipGetLastError());
+        return MVLA_OK;
+    }
     if (dh == 128)
         hipLaunchKernelGGL(score_probs_kernel<128>, grid, dim3(SC_THREADS), 0, st, q, q_row_stride,
                            k, k_row_stride, key_bias, S, H, nq, scale, probs);

