@@ -25,6 +25,13 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+# HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a
+# plain copy of known size (see profiles/single_view_gemm_gateup_hbm_traffic.txt).  Valid only
+# for the GEMM source the counters were taken with: keyed by kernel shape and a hash of gemm.hip.
+MEASURED_TRAFFIC = {
+    ("gemm_gateup", 544, 22016, 4096): (275.6e6, "ceab005022a7efb6"),
+}
+
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
@@ -58,6 +65,9 @@ def main():
     ap.add_argument("--keep", type=int, default=None, help="keep ratio in permille")
     ap.add_argument("--layers", type=int, default=None, help="override layer count (not the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 128 MiB row copy (compact kernel, identity indices) so "
+                         "that hardware byte counters can be scaled against a known size")
     ap.add_argument("--separate-prune-calls", action="store_true",
                     help="issue the four pruning calls one by one instead of mvla_prune_step")
     args = ap.parse_args()
@@ -95,6 +105,15 @@ def main():
                           rope_base=wl.rope_base)
     fused = not args.separate_prune_calls
     torch.cuda.synchronize()
+    if args.calibrate_copy:
+        rows = 16384
+        src = torch.zeros(1, rows, 4096, dtype=torch.bfloat16, device=dev)
+        cal_ctx = mv.Context(1, rows, 4096, 32, 64, 0)
+        ident = torch.arange(rows, dtype=torch.int32, device=dev).view(1, rows)
+        cal_ctx.compact(src, ident, ident)          # reads 128 MiB, writes 128 MiB (+ 192 KiB ids)
+        torch.cuda.synchronize()
+        cal_ctx.close()
+        del src
 
     def timed(fn, steps):
         torch.cuda.synchronize()
@@ -125,6 +144,11 @@ def main():
     dom_ms = sum(by_tag[dom_tag]) / len(by_tag[dom_tag])
     roofline = gemm_roofline(dom_tag, 2 * wl.F, wl.D, wl.F, dom_ms * 1e-3)
     roofline["kernel"] = f"gemm_gateup M={dom_tag} N={2 * wl.F} K={wl.D}"
+    import hashlib
+    src = os.path.join(ROOT, "paper_2604_09244_amd", "csrc", "gemm.hip")
+    src_hash = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
+    meas = MEASURED_TRAFFIC.get(("gemm_gateup", dom_tag, 2 * wl.F, wl.D))
+    roofline["traffic"] = meas[0] if meas and meas[1] == src_hash else None
     roofline["avg_us"] = dom_ms * 1e3
     roofline["launches"] = len(by_tag[dom_tag])
 
