@@ -8,10 +8,13 @@
 // keys of a step which the V^T fragments follow, so probabilities go from one
 // product to the next without leaving registers.  Softmax statistics are
 // per-lane scalars; the two lanes that share a query exchange one value per
-// tile.  K tiles [64 keys x dh] and V^T tiles [dh x 64 keys] are staged in LDS
-// (two stages, next tile in flight while the current one is consumed); V^T is
-// produced by the rotary kernel, so both tiles are contiguous along the
-// contraction axis of their product.
+// tile.  K tiles [64 keys x dh] and V^T tiles [dh x 64 keys] travel from global
+// memory straight into a ring of LDS stages (global_load_lds, 16 bytes per
+// lane; the XOR swizzle is applied on the global side because a direct load
+// always lands a wave on 1 KiB of consecutive LDS), so the next tiles are in
+// flight while the current one is consumed.  V^T is produced by the rotary
+// kernel, which makes both tiles contiguous along the contraction axis of
+// their product.
 #include "common.h"
 #include "mfma.h"
 
@@ -21,19 +24,35 @@ constexpr int ATT_THREADS = 256;
 constexpr int ATT_QT = 128;  // queries per workgroup (32 per wave)
 constexpr int ATT_KT = 64;   // keys per tile
 
-template <int DH>
-__global__ __launch_bounds__(ATT_THREADS) void attention_kernel(
+// untracked direct global -> LDS copy (see gemm.hip): order consumers behind att_wait_vm + barrier
+__device__ __forceinline__ void att_dma16(const void* g, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr),
+                 "v"(g)
+                 : "memory");
+}
+template <int N>
+__device__ __forceinline__ void att_wait_vm() {
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// K rows are dh/8 chunks long (16 or 8), V^T rows 8 chunks; conflict-free XOR patterns
+template <int CPR>
+__device__ __forceinline__ int att_swz(int row) {
+    return CPR == 16 ? (row & 15) : ((row >> 1) & 7);
+}
+
+template <int DH, int NS>
+__global__ __launch_bounds__(ATT_THREADS, 2) void attention_kernel(
     const bf16_t* __restrict__ q, const bf16_t* __restrict__ k, int ld, const bf16_t* __restrict__ vt,
     int S_pad, int S, int H, float scale_log2e, bf16_t* __restrict__ out, int ldo) {
     constexpr int CPR = DH / 8;           // 16-byte chunks per K row
     constexpr int STEPS = DH / 16;        // MFMA k-steps over the head dim
     constexpr int DB = DH / 32;           // 32-row blocks of O^T
-    constexpr int K_CH = ATT_KT * CPR / ATT_THREADS;  // chunks per thread per K tile
-    constexpr int V_CH = DH * 8 / ATT_THREADS;        // chunks per thread per V^T tile
+    constexpr int K_SLOTS = ATT_KT * CPR, V_SLOTS = DH * 8, STAGE = K_SLOTS + V_SLOTS;
+    constexpr int K_LD = K_SLOTS / ATT_THREADS, V_LD = V_SLOTS / ATT_THREADS;
+    constexpr int P = K_LD + V_LD;        // direct loads per thread per tile
 
     extern __shared__ uint4 lds[];
-    uint4* Ks = lds;                          // [2][64 * CPR]
-    uint4* Vs = lds + 2 * ATT_KT * CPR;       // [2][DH * 8]
 
     // heavier (later) query tiles first
     const int qtile = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
@@ -54,40 +73,37 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(
     const int last_row = min(q0 + ATT_QT, S) - 1;
     const int n_kt = last_row / ATT_KT + 1;   // key tiles this workgroup needs (causal)
 
-    // staging sources
-    const bf16_t* k_src[K_CH];
-    int k_dst[K_CH], k_row[K_CH];
+    // direct-load mapping: op i of this thread covers slot i*256 + tid of the K (or V^T) tile
+    const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
+    const bf16_t* k_src[K_LD];
+    int k_row[K_LD];
+    uint32_t k_lds[K_LD];
 #pragma unroll
-    for (int i = 0; i < K_CH; ++i) {
-        const int cid = tid + i * ATT_THREADS, row = cid / CPR, ch = cid % CPR;
+    for (int i = 0; i < K_LD; ++i) {
+        const int sl = i * ATT_THREADS + tid, row = sl / CPR, ch = (sl % CPR) ^ att_swz<CPR>(row);
         k_row[i] = row;
         k_src[i] = k + (size_t)b * S * ld + h * DH + ch * 8;
-        k_dst[i] = row * CPR + (ch ^ (row & 7));
+        k_lds[i] = __builtin_amdgcn_readfirstlane(lds_base + (uint32_t)(i * ATT_THREADS + wave * 64) * 16u);
     }
-    const bf16_t* v_src[V_CH];
-    int v_dst[V_CH];
+    const bf16_t* v_src[V_LD];
+    uint32_t v_lds[V_LD];
 #pragma unroll
-    for (int i = 0; i < V_CH; ++i) {
-        const int cid = tid + i * ATT_THREADS, row = cid >> 3, ch = cid & 7;
+    for (int i = 0; i < V_LD; ++i) {
+        const int sl = i * ATT_THREADS + tid, row = sl >> 3, ch = (sl & 7) ^ att_swz<8>(row);
         v_src[i] = vt + ((size_t)(b * H + h) * DH + row) * S_pad + ch * 8;
-        v_dst[i] = lds_slot(row, ch);
+        v_lds[i] = __builtin_amdgcn_readfirstlane(
+            lds_base + (uint32_t)(K_SLOTS + i * ATT_THREADS + wave * 64) * 16u);
     }
-    uint4 k_reg[K_CH], v_reg[V_CH];
-#define ATT_FETCH(KT)                                                                      \
-    {                                                                                      \
-        _Pragma("unroll") for (int i = 0; i < K_CH; ++i) {                                 \
-            const int key = min((KT) * ATT_KT + k_row[i], S - 1);                          \
-            k_reg[i] = *reinterpret_cast<const uint4*>(k_src[i] + (size_t)key * ld);       \
-        }                                                                                  \
-        _Pragma("unroll") for (int i = 0; i < V_CH; ++i) v_reg[i] =                        \
-            *reinterpret_cast<const uint4*>(v_src[i] + (KT) * ATT_KT);                     \
-    }
-#define ATT_STASH(STAGE)                                                                   \
-    {                                                                                      \
-        uint4* Kd = Ks + (STAGE) * ATT_KT * CPR;                                           \
-        uint4* Vd = Vs + (STAGE) * DH * 8;                                                 \
-        _Pragma("unroll") for (int i = 0; i < K_CH; ++i) Kd[k_dst[i]] = k_reg[i];          \
-        _Pragma("unroll") for (int i = 0; i < V_CH; ++i) Vd[v_dst[i]] = v_reg[i];          \
+#define ATT_ISSUE(KT, STG)                                                                  \
+    {                                                                                       \
+        const int kt_ = min((KT), n_kt - 1);                                                \
+        const uint32_t soff = (uint32_t)(STG) * STAGE * 16u;                                \
+        _Pragma("unroll") for (int i = 0; i < K_LD; ++i) {                                  \
+            const int key = min(kt_ * ATT_KT + k_row[i], S - 1);                            \
+            att_dma16(k_src[i] + (size_t)key * ld, k_lds[i] + soff);                        \
+        }                                                                                   \
+        _Pragma("unroll") for (int i = 0; i < V_LD; ++i)                                    \
+            att_dma16(v_src[i] + kt_ * ATT_KT, v_lds[i] + soff);                            \
     }
 
     f32x16_t o_acc[DB];
@@ -97,19 +113,24 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(
         for (int v = 0; v < 16; ++v) o_acc[d][v] = 0.f;
     float run_m = -INFINITY, run_l = 0.f;   // run_l: this lane's share of the row sum
 
-    ATT_FETCH(0)
-    ATT_STASH(0)
-    __syncthreads();
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s) ATT_ISSUE(s, s)
 
+    int stage = 0;
     for (int kt = 0; kt < n_kt; ++kt) {
-        const int cur = kt & 1;
-        const int nkt = min(kt + 1, n_kt - 1);  // unconditional: the last tile re-fetches itself
-        ATT_FETCH(nkt)
+        // tile kt has landed for every wave; the stage of tile kt-1 is free for tile kt+NS-1
+        att_wait_vm<(NS - 2) * P>();
+        __syncthreads();
+        {
+            int nstage = stage + NS - 1;
+            if (nstage >= NS) nstage -= NS;
+            ATT_ISSUE(kt + NS - 1, nstage)
+        }
         const int key0 = kt * ATT_KT;
         // a wave whose queries all precede this tile has nothing to add
         if (key0 <= qw0 + 31 && qw0 < S) {
-            const uint4* Kc = Ks + cur * ATT_KT * CPR;
-            const uint2* Vc = reinterpret_cast<const uint2*>(Vs + cur * DH * 8);
+            const uint4* Kc = lds + stage * STAGE;
+            const uint2* Vc = reinterpret_cast<const uint2*>(Kc + K_SLOTS);
             // ---- S^T for the two 32-key halves of the tile
             f32x16_t s_acc[2];
 #pragma unroll
@@ -119,21 +140,33 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(
                 const int row = t * 32 + fr;
 #pragma unroll
                 for (int st = 0; st < STEPS; ++st) {
-                    const uint4 kf = Kc[row * CPR + ((st * 2 + fg) ^ (row & 7))];
+                    const uint4 kf = Kc[row * CPR + ((st * 2 + fg) ^ att_swz<CPR>(row))];
                     s_acc[t] = mfma32(kf, qf[st], s_acc[t]);
                 }
             }
-            // ---- scale, mask, row max
+            // ---- scale, (mask,) row max; only tiles that reach the diagonal or the end of the
+            // sequence need the mask (wave-uniform test)
             float tile_m = -INFINITY;
+            if (key0 + ATT_KT - 1 <= qw0 && key0 + ATT_KT <= S) {
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
+                for (int t = 0; t < 2; ++t)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int key = key0 + t * 32 + mfma32_row(v, lane);
-                    const float x = (key <= my_q && key < S) ? s_acc[t][v] * scale_log2e : -INFINITY;
-                    s_acc[t][v] = x;
-                    tile_m = fmaxf(tile_m, x);
-                }
+                    for (int v = 0; v < 16; ++v) {
+                        s_acc[t][v] *= scale_log2e;
+                        tile_m = fmaxf(tile_m, s_acc[t][v]);
+                    }
+            } else {
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int key = key0 + t * 32 + mfma32_row(v, lane);
+                        const float x =
+                            (key <= my_q && key < S) ? s_acc[t][v] * scale_log2e : -INFINITY;
+                        s_acc[t][v] = x;
+                        tile_m = fmaxf(tile_m, x);
+                    }
+            }
             tile_m = fmaxf(tile_m, __shfl_xor(tile_m, 32));
             const float new_m = fmaxf(run_m, tile_m);   // finite from the first tile on (key 0)
             const float corr = __builtin_amdgcn_exp2f(run_m - new_m);
@@ -163,20 +196,20 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(
 #pragma unroll
             for (int d = 0; d < DB; ++d) {
                 const int row = d * 32 + fr;
+                const int sw = att_swz<8>(row);
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks) {
-                    const uint2 lo = Vc[lds_slot(row, ks * 2) * 2 + fg];
-                    const uint2 hi = Vc[lds_slot(row, ks * 2 + 1) * 2 + fg];
+                    const uint2 lo = Vc[(row * 8 + ((ks * 2) ^ sw)) * 2 + fg];
+                    const uint2 hi = Vc[(row * 8 + ((ks * 2 + 1) ^ sw)) * 2 + fg];
                     o_acc[d] = mfma32(make_uint4(lo.x, lo.y, hi.x, hi.y), pf[ks], o_acc[d]);
                 }
             }
         }
-        ATT_STASH(cur ^ 1)
-        __syncthreads();
+        stage = stage + 1 == NS ? 0 : stage + 1;
     }
+    att_wait_vm<0>();
+#undef ATT_ISSUE
 
-#undef ATT_FETCH
-#undef ATT_STASH
     // ---- normalise and store: lane holds query my_q, rows = head-dim
     const float tot = run_l + __shfl_xor(run_l, 32);
     if (my_q < S) {
@@ -195,27 +228,29 @@ __global__ __launch_bounds__(ATT_THREADS) void attention_kernel(
     }
 }
 
+template <int DH, int NS>
+static int launch_att(const bf16_t* q, const bf16_t* k, int ldqkv, const bf16_t* vt, int S_pad,
+                      int B, int S, int H, bf16_t* out, int ldo, hipStream_t st) {
+    dim3 grid((S + ATT_QT - 1) / ATT_QT, H, B);
+    const float scale_log2e = 1.4426950408889634f / sqrtf((float)DH);
+    const size_t lds = (size_t)NS * (ATT_KT * (DH / 8) + DH * 8) * sizeof(uint4);
+    auto kern = attention_kernel<DH, NS>;
+    MVLA_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(kern, grid, dim3(ATT_THREADS), lds, st, q, k, ldqkv, vt, S_pad, S, H,
+                       scale_log2e, out, ldo);
+    MVLA_HIP_CHECK(hipGetLastError());
+    return MVLA_OK;
+}
+
 int launch_attention(const bf16_t* q, const bf16_t* k, int ldqkv, const bf16_t* vt, int S_pad,
                      int B, int S, int H, int dh, bf16_t* out, int ldo, hipStream_t st) {
     if (B <= 0 || S <= 0) return MVLA_OK;
     if (S_pad % ATT_KT != 0 || S_pad < S) return MVLA_EINVAL;
-    dim3 grid((S + ATT_QT - 1) / ATT_QT, H, B);
-    const float scale_log2e = 1.4426950408889634f / sqrtf((float)dh);
-    if (dh == 128) {
-        const size_t lds = (size_t)2 * (ATT_KT * 16 + 128 * 8) * sizeof(uint4);
-        MVLA_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(attention_kernel<128>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        hipLaunchKernelGGL(attention_kernel<128>, grid, dim3(ATT_THREADS), lds, st, q, k, ldqkv, vt,
-                           S_pad, S, H, scale_log2e, out, ldo);
-    } else if (dh == 64) {
-        const size_t lds = (size_t)2 * (ATT_KT * 8 + 64 * 8) * sizeof(uint4);
-        hipLaunchKernelGGL(attention_kernel<64>, grid, dim3(ATT_THREADS), lds, st, q, k, ldqkv, vt,
-                           S_pad, S, H, scale_log2e, out, ldo);
-    } else {
-        return MVLA_EUNSUPPORTED;
-    }
-    MVLA_HIP_CHECK(hipGetLastError());
-    return MVLA_OK;
+    // two stages of 32 KiB each: two workgroups per CU, whose waves overlap softmax and MFMA
+    if (dh == 128) return launch_att<128, 2>(q, k, ldqkv, vt, S_pad, B, S, H, out, ldo, st);
+    if (dh == 64) return launch_att<64, 2>(q, k, ldqkv, vt, S_pad, B, S, H, out, ldo, st);
+    return MVLA_EUNSUPPORTED;
 }
 
 }  // namespace mvla
