@@ -268,12 +268,17 @@ int mvla_prune_step(mvla_ctx* ctx, const float* attn, int H, int Nq, const void*
     if (!aligned(h, 16) || !aligned(h_out, 16)) return MVLA_EINVAL;
     if (n2 > 16384 || n3 > 16384) return MVLA_EUNSUPPORTED;
     if (salience_scratch_bytes(B, H, Nq, n2 + n3) > ctx->scratch_bytes) return MVLA_ENOMEM;
-    int rc = mvla_salience(ctx, attn, B, H, Nq, S, n2 + n3, sal);
-    if (rc) return rc;
-    rc = mvla_modality_budget(ctx, sal, B, n2, n3, k_total, min2, min3, k2k3, nullptr);
-    if (rc) return rc;
-    rc = mvla_select_topk(ctx, sal, k2k3, B, n2, n3, n_text, k_total, kept_idx);
-    if (rc) return rc;
+    {   // overlap check of the two hidden-state buffers, before anything is launched
+        const char* a = static_cast<const char*>(h);
+        const char* bb = static_cast<const char*>(h_out);
+        const size_t na = (size_t)B * S * D * 2, nb = (size_t)B * (k_total + n_text) * D * 2;
+        if (a < bb + nb && bb < a + na) return MVLA_EINVAL;
+    }
+    int rc;
+    TIMED(ctx, KID_PRUNE_FUSED, B,
+          launch_prune_fused(attn, B, H, Nq, S, n2, n3, n_text, k_total, min2, min3, sal, k2k3,
+                             kept_idx, reinterpret_cast<float*>(ctx->scratch), ctx->counters,
+                             ctx->stream));
     return mvla_compact(ctx, h, pos, kept_idx, B, S, k_total + n_text, D, h_out, pos_out);
 }
 

@@ -58,6 +58,10 @@ namespace mvla {
 size_t salience_scratch_bytes(int B, int H, int Nq, int n_vis);
 int launch_salience(const float* attn, int B, int H, int Nq, int S, int n_vis, float* sal,
                     float* partial, uint32_t* counters, hipStream_t st);
+// salience + budget + selection in one launch (same results as the three separate launches)
+int launch_prune_fused(const float* attn, int B, int H, int Nq, int S, int n2, int n3, int n_text,
+                       int k_total, int min2, int min3, float* sal, int32_t* k2k3,
+                       int32_t* kept_idx, float* partial, uint32_t* counters, hipStream_t st);
 int launch_budget(const float* sal, int B, int n2, int n3, int k_total, int min2, int min3,
                   int32_t* k2k3, float* mass, hipStream_t st);
 int launch_select(const float* sal, const int32_t* k2k3, int B, int n2, int n3, int n_text,

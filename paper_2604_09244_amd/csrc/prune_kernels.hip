@@ -17,15 +17,28 @@ namespace mvla {
 // share a column chunk through a partial buffer summed in fixed order by
 // whichever of them arrives last (integer arrival counter, no float atomics).
 // ---------------------------------------------------------------------------
+// forward declarations of the per-sample steps that the fused kernel runs after the salience
+struct FusedPrune {
+    int n2, n3, n_text, k_total, min2, min3;
+    int32_t* k2k3;
+    int32_t* kept_idx;
+    uint32_t* sample_counters;  // one arrival counter per sample (kept at zero between calls)
+};
+template <bool COHERENT>
+__device__ void finish_sample(const float* sal_b, const FusedPrune& f, int b, uint32_t* keys);
+
 constexpr int SAL_THREADS = 256;
 constexpr int SAL_LPR = 16;                        // lanes per row-group
 constexpr int SAL_GROUPS = SAL_THREADS / SAL_LPR;  // 16 row-groups per block
 
-template <int VEC>
+// FUSED: the workgroup that completes the last column chunk of a sample goes on to split the
+// budget and select that sample's tokens (same arithmetic as budget_kernel / select_kernel).
+template <int VEC, bool FUSED>
 __global__ __launch_bounds__(SAL_THREADS) void salience_kernel(
     const float* __restrict__ attn, int R, int S, int n_vis, int rows_per_split, int n_split,
     float inv_rows, float* __restrict__ sal, float* __restrict__ partial,
-    uint32_t* __restrict__ counters) {
+    uint32_t* __restrict__ counters, FusedPrune fused) {
+    extern __shared__ uint32_t dyn_lds[];  // selection keys (fused variant only)
     constexpr int CW = SAL_LPR * VEC;  // columns per chunk
     const int chunk = blockIdx.x, split = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x;
@@ -88,35 +101,60 @@ __global__ __launch_bounds__(SAL_THREADS) void salience_kernel(
 #pragma unroll
         for (int w = 0; w < SAL_THREADS / 64; ++w) tot += red[w][tid];
     }
+    // store of a finished salience value: plain, or agent-coherent when another workgroup
+    // (maybe on another XCD) will read it in this same launch
+    auto put = [&](float v) {
+        if (FUSED)
+            __hip_atomic_store(&sal[(size_t)b * n_vis + c], v, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        else
+            sal[(size_t)b * n_vis + c] = v;
+    };
     if (n_split == 1) {
-        if (tid < CW && c < n_vis) sal[(size_t)b * n_vis + c] = tot * inv_rows;
-        return;
+        if (tid < CW && c < n_vis) put(tot * inv_rows);
+        if (!FUSED) return;
+    } else {
+        // several blocks share this column chunk: publish, last arrival finishes
+        float* pslot = partial + ((size_t)(b * gridDim.x + chunk) * n_split) * CW;
+        // partial sums cross CUs/XCDs through agent-coherent accesses (no cache-wide flushes)
+        if (tid < CW)
+            __hip_atomic_store(&pslot[(size_t)split * CW + tid], tot, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (tid == 0) {
+            uint32_t* ctr = counters + (b * gridDim.x + chunk);
+            const uint32_t prev =
+                __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            is_last = (prev == (uint32_t)(n_split - 1));
+            if (is_last) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+        if (!is_last) return;
+        if (tid < CW && c < n_vis) {
+            float s = 0.f;
+#pragma unroll 8
+            for (int i = 0; i < n_split; ++i)
+                s += __hip_atomic_load(&pslot[(size_t)i * CW + tid], __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+            put(s * inv_rows);
+        }
+        if (!FUSED) return;
     }
-    // several blocks share this column chunk: publish, last arrival finishes
-    float* pslot = partial + ((size_t)(b * gridDim.x + chunk) * n_split) * CW;
-    // partial sums cross CUs/XCDs through agent-coherent accesses (no cache-wide flushes)
-    if (tid < CW)
-        __hip_atomic_store(&pslot[(size_t)split * CW + tid], tot, __ATOMIC_RELAXED,
-                           __HIP_MEMORY_SCOPE_AGENT);
+    // ---- fused tail: this chunk of sample b is complete; the last chunk's workgroup finishes b
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (tid == 0) {
-        uint32_t* ctr = counters + (b * gridDim.x + chunk);
-        const uint32_t prev =
-            __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        is_last = (prev == (uint32_t)(n_split - 1));
-        if (is_last) __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint32_t prev = __hip_atomic_fetch_add(&fused.sample_counters[b], 1u, __ATOMIC_RELAXED,
+                                                     __HIP_MEMORY_SCOPE_AGENT);
+        is_last = (prev == gridDim.x - 1);
+        if (is_last)
+            __hip_atomic_store(&fused.sample_counters[b], 0u, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
     if (!is_last) return;
-    if (tid < CW && c < n_vis) {
-        float s = 0.f;
-#pragma unroll 8
-        for (int i = 0; i < n_split; ++i)
-            s += __hip_atomic_load(&pslot[(size_t)i * CW + tid], __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
-        sal[(size_t)b * n_vis + c] = s * inv_rows;
-    }
+    finish_sample<true>(sal + (size_t)b * n_vis, fused, b, dyn_lds);
 }
 
 static void salience_shape(int B, int R, int n_vis, int vec, int* chunks, int* n_split,
@@ -139,23 +177,47 @@ size_t salience_scratch_bytes(int B, int H, int Nq, int n_vis) {
     return align_up((size_t)B * (size_t)(n_vis + 64) * (R / (2 * SAL_GROUPS) + 2) * 4, 256);
 }
 
-int launch_salience(const float* attn, int B, int H, int Nq, int S, int n_vis, float* sal,
-                    float* partial, uint32_t* counters, hipStream_t st) {
+static int launch_salience_any(const float* attn, int B, int H, int Nq, int S, int n_vis,
+                               float* sal, float* partial, uint32_t* counters,
+                               const FusedPrune* fused, hipStream_t st) {
     const int R = H * Nq;
     const bool vec4 = (S % 4 == 0) && ((reinterpret_cast<uintptr_t>(attn) & 15) == 0);
     int chunks, n_split, rps;
     salience_shape(B, R, n_vis, vec4 ? 4 : 1, &chunks, &n_split, &rps);
-    if ((long)B * chunks > kCounterWords / 2) return MVLA_EUNSUPPORTED;  // first half is ours
+    // counters: [0, B*chunks) chunk arrivals, then B sample arrivals (first half of the area)
+    if ((long)B * chunks + B > kCounterWords / 2) return MVLA_EUNSUPPORTED;
     dim3 grid(chunks, n_split, B);
     const float inv_rows = 1.0f / (float)R;
-    if (vec4)
-        hipLaunchKernelGGL(salience_kernel<4>, grid, dim3(SAL_THREADS), 0, st, attn, R, S, n_vis,
-                           rps, n_split, inv_rows, sal, partial, counters);
-    else
-        hipLaunchKernelGGL(salience_kernel<1>, grid, dim3(SAL_THREADS), 0, st, attn, R, S, n_vis,
-                           rps, n_split, inv_rows, sal, partial, counters);
+    FusedPrune f{};
+    size_t lds = 0;
+    if (fused) {
+        f = *fused;
+        f.sample_counters = counters + (size_t)B * chunks;
+        lds = (size_t)max(max(f.n2, f.n3), 1) * 4;
+    }
+#define MVLA_SAL(V, F)                                                                          \
+    hipLaunchKernelGGL((salience_kernel<V, F>), grid, dim3(SAL_THREADS), lds, st, attn, R, S, n_vis, \
+                       rps, n_split, inv_rows, sal, partial, counters, f)
+    if (vec4) {
+        if (fused) MVLA_SAL(4, true); else MVLA_SAL(4, false);
+    } else {
+        if (fused) MVLA_SAL(1, true); else MVLA_SAL(1, false);
+    }
+#undef MVLA_SAL
     MVLA_HIP_CHECK(hipGetLastError());
     return MVLA_OK;
+}
+
+int launch_salience(const float* attn, int B, int H, int Nq, int S, int n_vis, float* sal,
+                    float* partial, uint32_t* counters, hipStream_t st) {
+    return launch_salience_any(attn, B, H, Nq, S, n_vis, sal, partial, counters, nullptr, st);
+}
+
+int launch_prune_fused(const float* attn, int B, int H, int Nq, int S, int n2, int n3, int n_text,
+                       int k_total, int min2, int min3, float* sal, int32_t* k2k3,
+                       int32_t* kept_idx, float* partial, uint32_t* counters, hipStream_t st) {
+    FusedPrune f{n2, n3, n_text, k_total, min2, min3, k2k3, kept_idx, nullptr};
+    return launch_salience_any(attn, B, H, Nq, S, n2 + n3, sal, partial, counters, &f, st);
 }
 
 // ---------------------------------------------------------------------------
@@ -251,12 +313,16 @@ __device__ inline uint32_t block_scan_incl(uint32_t v, uint32_t* wsum) {
     return v + add;
 }
 
+template <bool COHERENT>
 __device__ void select_segment(const float* __restrict__ seg, int n, int k, int idx_offset,
                                int32_t* __restrict__ out, uint32_t* keys /*LDS [n]*/,
                                uint32_t* hist /*LDS [256]*/, uint32_t* wsum /*LDS [4]*/,
                                uint32_t* bcast /*LDS [4]*/) {
     const int tid = threadIdx.x;
-    for (int i = tid; i < n; i += SEL_THREADS) keys[i] = sal_key(seg[i]);
+    for (int i = tid; i < n; i += SEL_THREADS)
+        keys[i] = sal_key(COHERENT ? __hip_atomic_load(&seg[i], __ATOMIC_RELAXED,
+                                                       __HIP_MEMORY_SCOPE_AGENT)
+                                   : seg[i]);
     if (k <= 0) return;
     if (k > n) k = n;
     uint32_t prefix = 0, prefix_mask = 0;
@@ -324,13 +390,50 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(const float* __rest
     k2 = min(max(k2, max(0, k_total - n3)), min(n2, k_total));
     const int k3 = k_total - k2;
     if (which == 0) {
-        select_segment(sal + (size_t)b * (n2 + n3), n2, k2, 0, row, keys, hist, wsum, bcast);
+        select_segment<false>(sal + (size_t)b * (n2 + n3), n2, k2, 0, row, keys, hist, wsum, bcast);
     } else if (which == 1) {
-        select_segment(sal + (size_t)b * (n2 + n3) + n2, n3, k3, n2, row + k2, keys, hist, wsum,
-                       bcast);
+        select_segment<false>(sal + (size_t)b * (n2 + n3) + n2, n3, k3, n2, row + k2, keys, hist,
+                              wsum, bcast);
     } else {
         for (int i = threadIdx.x; i < n_text; i += SEL_THREADS) row[k_total + i] = n2 + n3 + i;
     }
+}
+
+// Budget and selection of one sample by one workgroup (tail of the fused kernel).  Same
+// summation order as budget_kernel, same selection as select_kernel.
+template <bool COHERENT>
+__device__ void finish_sample(const float* sal_b, const FusedPrune& f, int b, uint32_t* keys) {
+    __shared__ double sh_d[BUD_THREADS / 64];
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t wsum[SEL_THREADS / 64];
+    __shared__ uint32_t bcast[4];
+    __shared__ int sh_k2;
+    auto ld = [&](int i) {
+        return COHERENT ? __hip_atomic_load(&sal_b[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                        : sal_b[i];
+    };
+    double a2 = 0.0, a3 = 0.0;
+    for (int i = threadIdx.x; i < f.n2; i += BUD_THREADS) a2 += (double)ld(i);
+    for (int i = threadIdx.x; i < f.n3; i += BUD_THREADS) a3 += (double)ld(f.n2 + i);
+    a2 = block_sum_f64(a2, sh_d);
+    a3 = block_sum_f64(a3, sh_d);
+    if (threadIdx.x == 0) {
+        int k2;
+        double m2;
+        budget_split(a2, a3, f.n2, f.n3, f.k_total, f.min2, f.min3, &k2, &m2);
+        f.k2k3[2 * b] = k2;
+        f.k2k3[2 * b + 1] = f.k_total - k2;
+        sh_k2 = k2;
+    }
+    __syncthreads();
+    const int k2 = sh_k2;
+    int32_t* row = f.kept_idx + (size_t)b * (f.k_total + f.n_text);
+    select_segment<COHERENT>(sal_b, f.n2, k2, 0, row, keys, hist, wsum, bcast);
+    __syncthreads();
+    select_segment<COHERENT>(sal_b + f.n2, f.n3, f.k_total - k2, f.n2, row + k2, keys, hist, wsum,
+                             bcast);
+    for (int i = threadIdx.x; i < f.n_text; i += SEL_THREADS)
+        row[f.k_total + i] = f.n2 + f.n3 + i;
 }
 
 int launch_select(const float* sal, const int32_t* k2k3, int B, int n2, int n3, int n_text,
