@@ -167,10 +167,10 @@ def main():
 
     # roofline of the bandwidth-bound pruning kernels (algorithmic bytes per launch)
     extra = {}
-    sal_key = ("salience", wl.B)
-    if sal_key in acc:
-        b = 4.0 * wl.B * wl.H * wl.nt * wl.n_vis + 4.0 * wl.B * wl.n_vis
-        extra["salience"] = hbm_roofline(b, 1e-3 * sum(acc[sal_key]) / len(acc[sal_key]))
+    for sal_key in (("salience", wl.B), ("prune_fused", wl.B)):   # fused: + budget and selection
+        if sal_key in acc:
+            b = 4.0 * wl.B * wl.H * wl.nt * wl.n_vis + 4.0 * wl.B * wl.n_vis
+            extra[sal_key[0]] = hbm_roofline(b, 1e-3 * sum(acc[sal_key]) / len(acc[sal_key]))
     cmp_key = ("compact", M_kept)
     if cmp_key in acc:
         b = 2.0 * M_kept * wl.D * 2 + 12.0 * M_kept
