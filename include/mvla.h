@@ -123,6 +123,17 @@ int mvla_prune_step(mvla_ctx* ctx, const float* attn, int H, int Nq, const void*
                     int k_total, int min2, int min3, float* sal, int32_t* k2k3,
                     int32_t* kept_idx, void* h_out, int32_t* pos_out);
 
+/* Temporal smoothing of a per-token (or per-patch) indicator across action
+ * iterations (Sec. 4.3 Eq. 7; Sec. 4.4 Eqs. 8-9; Algorithm 1 "Action Iteration
+ * Stage"), t counted from 1:
+ *     t == 1      : x_hat = x_t                    (cold start: no history)
+ *     1 < t < k   : x_hat = ((t-1)/t) x_hat + x_t/t    (running mean, Eq. 8)
+ *     t >= k      : x_hat = beta x_hat + (1-beta) x_t  (Eq. 9)
+ * x_t: device fp32 [n]; x_hat: device fp32 [n], read (t > 1) and overwritten.
+ * Paper defaults: k = 7, beta = 0.85.  Requires 0 < beta < 1, t >= 1, k >= 1. */
+int mvla_temporal_smooth(mvla_ctx* ctx, const float* x_t, float* x_hat, size_t n, int t, int k,
+                         double beta);
+
 /* ------------------------------------------------------------------------ */
 /* Backbone layer                                                           */
 /* ------------------------------------------------------------------------ */
@@ -205,9 +216,9 @@ int mvla_profile_enable(mvla_ctx* ctx, uint32_t kernel_mask, int max_records);
  * Clears the record list. */
 int mvla_profile_read(mvla_ctx* ctx, int capacity, int32_t* ids, int32_t* tags, float* ms,
                       int32_t* n_out);
-/* Name of kernel id 0..14 ("rmsnorm", "gemm_qkv", "rope_split", "score_probs",
+/* Name of kernel id 0..15 ("rmsnorm", "gemm_qkv", "rope_split", "score_probs",
  * "attention", "gemm_o", "rmsnorm_mlp", "gemm_gateup", "gemm_down", "salience",
- * "budget", "select", "compact", "rope_table", "prune_fused"), "?" otherwise. */
+ * "budget", "select", "compact", "rope_table", "prune_fused", "smooth"), "?" otherwise. */
 const char* mvla_kernel_name(int id);
 
 #ifdef __cplusplus

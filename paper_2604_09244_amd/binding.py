@@ -22,7 +22,7 @@ EXPORTS = [
     "mvla_version", "mvla_strerror", "mvla_workspace_bytes", "mvla_create", "mvla_set_stream",
     "mvla_destroy", "mvla_salience", "mvla_modality_budget", "mvla_select_topk", "mvla_compact",
     "mvla_prune_step", "mvla_rope_table", "mvla_prefill_layer", "mvla_score_only",
-    "mvla_profile_enable", "mvla_profile_read", "mvla_kernel_name",
+    "mvla_profile_enable", "mvla_profile_read", "mvla_kernel_name", "mvla_temporal_smooth",
 ]
 
 
@@ -74,6 +74,7 @@ def load() -> C.CDLL:
                                        i, i, vp, i, vp, vp]
     lib.mvla_score_only.argtypes = [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeightsC), vp, vp,
                                     i, i, i, vp, vp]
+    lib.mvla_temporal_smooth.argtypes = [vp, vp, vp, sz, i, i, C.c_double]
     lib.mvla_profile_enable.argtypes = [vp, C.c_uint32, i]
     lib.mvla_profile_read.argtypes = [vp, i, vp, vp, vp, vp]
     lib.mvla_kernel_name.restype = C.c_char_p
@@ -206,6 +207,16 @@ class Context:
                                    S_out, D, h_out.data_ptr(), pos_out.data_ptr()), "mvla_compact")
         return h_out, pos_out
 
+    def temporal_smooth(self, x_t: torch.Tensor, x_hat: torch.Tensor, t: int, k: int = 7,
+                        beta: float = 0.85):
+        """In-place update of x_hat with the observation x_t at step t (1-based)."""
+        _dev(x_t, torch.float32)
+        _dev(x_hat, torch.float32)
+        assert x_t.numel() == x_hat.numel()
+        _check(load().mvla_temporal_smooth(self._h, x_t.data_ptr(), x_hat.data_ptr(), x_t.numel(),
+                                           t, k, beta), "mvla_temporal_smooth")
+        return x_hat
+
     def prune_step(self, attn, h, pos, n2, n3, n_text, k_total, min2=0, min3=0, out=None):
         B, H, Nq, S = _dev(attn, torch.float32).shape
         D = _dev(h, torch.bfloat16).shape[2]
@@ -288,6 +299,7 @@ class PrefillPlan:
         self.h_full = [torch.empty(B, self.S, cfg.D, dtype=bf, device=dev) for _ in range(2)]
         self.h_kept = [torch.empty(B, self.S_kept, cfg.D, dtype=bf, device=dev) for _ in range(2)]
         self.probs = torch.empty(B, cfg.H, nt, self.S, dtype=f32, device=dev)
+        self.sal_hat = torch.zeros(B, n2 + n3, dtype=f32, device=dev)   # smoothed salience state
         self.prune = dict(sal=torch.empty(B, n2 + n3, dtype=f32, device=dev),
                           k2k3=torch.empty(B, 2, dtype=i32, device=dev),
                           kept_idx=torch.empty(B, self.S_kept, dtype=i32, device=dev),
@@ -295,9 +307,16 @@ class PrefillPlan:
                           pos=torch.empty(B, self.S_kept, dtype=i32, device=dev))
 
     def run(self, x: torch.Tensor, pos: torch.Tensor, key_bias: Optional[torch.Tensor] = None,
-            fused_prune: bool = True):
-        """Pruned prefill: p full layers, pruning step, L-p layers on kept tokens."""
+            fused_prune: bool = True, smooth_step: int = 0, smooth_k: int = 7,
+            smooth_beta: float = 0.85):
+        """Pruned prefill: p full layers, pruning step, L-p layers on kept tokens.
+
+        smooth_step > 0 turns on the action-iteration smoothing of the salience: the call is
+        timestep ``smooth_step`` (1-based) of an episode; step 1 is the cold start and returns
+        the unpruned prefill, later steps select on the smoothed salience."""
         ctx, cfg = self.ctx, self.cfg
+        if smooth_step == 1:
+            return self._cold_start(x, pos, key_bias, smooth_k, smooth_beta)
         h = x
         for li in range(self.p):
             tail = self.nt if li == self.p - 1 else 0
@@ -307,11 +326,15 @@ class PrefillPlan:
             h = y
         if self.p == 0:
             ctx.score_only(cfg, self.structs[0], h, pos, self.nt, key_bias, self.probs)
-        if fused_prune:
+        if fused_prune and smooth_step == 0:
             ctx.prune_step(self.probs, h, pos, self.n2, self.n3, self.nt, self.k_total,
                            out=self.prune)
         else:
             ctx.salience(self.probs, self.n2 + self.n3, out=self.prune["sal"])
+            if smooth_step > 1:
+                ctx.temporal_smooth(self.prune["sal"], self.sal_hat, smooth_step, smooth_k,
+                                    smooth_beta)
+                self.prune["sal"].copy_(self.sal_hat)
             ctx.modality_budget(self.prune["sal"], self.n2, self.n3, self.k_total,
                                 out=self.prune["k2k3"])
             ctx.select_topk(self.prune["sal"], self.prune["k2k3"], self.n2, self.n3, self.nt,
@@ -322,6 +345,25 @@ class PrefillPlan:
             y = self.h_kept[(li - self.p + 1) & 1]
             ctx.prefill_layer(cfg, self.structs[li], h, pk, y)
             h = y
+        return h
+
+    def _cold_start(self, x, pos, key_bias, k, beta):
+        """Step 1 of an episode: all tokens go through every layer; the salience observed on
+        the way seeds the smoothed state."""
+        h = x
+        if self.p == 0:
+            self.ctx.score_only(self.cfg, self.structs[0], h, pos, self.nt, key_bias, self.probs)
+            self.ctx.salience(self.probs, self.n2 + self.n3, out=self.prune["sal"])
+            self.ctx.temporal_smooth(self.prune["sal"], self.sal_hat, 1, k, beta)
+        for li in range(self.L):
+            tail = self.nt if li == self.p - 1 else 0
+            y = self.h_full[li & 1]
+            self.ctx.prefill_layer(self.cfg, self.structs[li], h, pos, y, tail, key_bias,
+                                   self.probs if tail else None)
+            h = y
+            if tail:
+                self.ctx.salience(self.probs, self.n2 + self.n3, out=self.prune["sal"])
+                self.ctx.temporal_smooth(self.prune["sal"], self.sal_hat, 1, k, beta)
         return h
 
     def run_unpruned(self, x: torch.Tensor, pos: torch.Tensor):

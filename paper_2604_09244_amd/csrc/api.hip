@@ -92,7 +92,7 @@ struct Timed {
 const char* const kKernelNames[KID_COUNT] = {
     "rmsnorm", "gemm_qkv", "rope_split", "score_probs", "attention", "gemm_o", "rmsnorm_mlp",
     "gemm_gateup", "gemm_down", "salience", "budget", "select", "compact", "rope_table",
-    "prune_fused"};
+    "prune_fused", "smooth"};
 
 }  // namespace
 
@@ -280,6 +280,16 @@ int mvla_prune_step(mvla_ctx* ctx, const float* attn, int H, int Nq, const void*
                              kept_idx, reinterpret_cast<float*>(ctx->scratch), ctx->counters,
                              ctx->stream));
     return mvla_compact(ctx, h, pos, kept_idx, B, S, k_total + n_text, D, h_out, pos_out);
+}
+
+int mvla_temporal_smooth(mvla_ctx* ctx, const float* x_t, float* x_hat, size_t n, int t, int k,
+                         double beta) {
+    if (!ctx || !x_t || !x_hat) return MVLA_EINVAL;
+    if (t < 1 || k < 1 || !(beta > 0.0 && beta < 1.0)) return MVLA_EINVAL;
+    int rc;
+    TIMED(ctx, KID_SMOOTH, (int)(n > 0x7fffffff ? 0x7fffffff : n),
+          launch_smooth(x_t, x_hat, n, t, k, beta, ctx->stream));
+    return MVLA_OK;
 }
 
 // ---------------------------------------------------------------------------

@@ -482,4 +482,35 @@ int launch_compact(const bf16_t* h, const int32_t* pos, const int32_t* kept_idx,
     return MVLA_OK;
 }
 
+// ---------------------------------------------------------------------------
+// Action-iteration smoothing of an indicator (paper Sec. 4.3 Eq. 7, Sec. 4.4
+// Eqs. 8-9): observation at the cold start, running mean while the window
+// fills, exponential moving average afterwards.  w_prev and w_new are the two
+// weights of the step, computed on the host in fp64 and rounded to fp32.
+// ---------------------------------------------------------------------------
+__global__ void smooth_kernel(const float* __restrict__ x_t, float* __restrict__ x_hat, size_t n,
+                              float w_prev, float w_new, int cold) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const float x = x_t[i];
+    x_hat[i] = cold ? x : w_prev * x_hat[i] + w_new * x;
+}
+
+int launch_smooth(const float* x_t, float* x_hat, size_t n, int t, int k, double beta,
+                  hipStream_t st) {
+    if (n == 0) return MVLA_OK;
+    double wp, wn;
+    if (t < k) {
+        wp = (double)(t - 1) / (double)t;
+        wn = 1.0 / (double)t;
+    } else {
+        wp = beta;
+        wn = 1.0 - beta;
+    }
+    hipLaunchKernelGGL(smooth_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, x_t,
+                       x_hat, n, (float)wp, (float)wn, t == 1 ? 1 : 0);
+    MVLA_HIP_CHECK(hipGetLastError());
+    return MVLA_OK;
+}
+
 }  // namespace mvla
