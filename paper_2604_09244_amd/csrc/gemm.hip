@@ -350,23 +350,86 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
             continue;
         }
 
-        // ---- epilogue: lane holds column (lane%32), rows mfma32_row(v, lane) of each block ----
-        constexpr int JS = EPI == EPI_SILU_MUL ? 2 : 1;
+        // ---- epilogue through LDS: the accumulator tile (lane = column, registers = rows) is
+        // laid down as fp32 rows, then every thread takes 8 consecutive columns of a row, so the
+        // residual is read and the result written with 16-byte accesses on whole cache lines.
+        // A pass covers as many tile rows as the pipeline's LDS holds (a whole number of wave
+        // rows); only the waves owning those rows write.
+        constexpr int LDS_FLOATS = NS * STAGE * 4;
+        constexpr int PASSES = (BM * BN + LDS_FLOATS - 1) / LDS_FLOATS;
+        constexpr int RP = BM / PASSES;                  // tile rows per pass
+        static_assert(BM % PASSES == 0 && RP % TM == 0, "pass must hold whole wave rows");
+        static_assert(RP * BN <= LDS_FLOATS, "epilogue tile does not fit the stages");
+        constexpr int OUT_COLS = EPI == EPI_SILU_MUL ? BN / 2 : BN;   // output columns per tile
+        constexpr int ITEMS = RP * OUT_COLS / 8;                      // 8-column items per pass
+        float* tile = reinterpret_cast<float*>(lds);
+        const int out_n0 = EPI == EPI_SILU_MUL ? n0 / 2 : n0;
+        const int out_N = EPI == EPI_SILU_MUL ? N / 2 : N;
+#pragma unroll 1
+        for (int pass = 0; pass < PASSES; ++pass) {
+            __syncthreads();   // previous readers of the LDS (fragments or the last pass) are done
+            if (wm * TM >= pass * RP && wm * TM < (pass + 1) * RP) {
 #pragma unroll
-        for (int i = 0; i < FM; ++i) {
-            const int row_base = m0 + wm * TM + i * 32;
+                for (int i = 0; i < FM; ++i)
 #pragma unroll
-            for (int j = 0; j < FN; j += JS) {
-                const int ncol = n0 + wn * TN + j * 32;
-                if (ncol + (JS - 1) * 32 + fr < N) {
-                    const int ocol = JS == 2 ? (ncol >> 1) + fr : ncol + fr;
+                    for (int j = 0; j < FN; ++j)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int row = row_base + mfma32_row(v, lane);
-                        if (row < M)
-                            store_elem<EPI>(Cv, ldc, Rv, ldr, row, ocol, acc[i][j][v],
-                                            acc[i][JS == 2 ? j + 1 : j][v]);
+                        for (int v = 0; v < 16; ++v) {
+                            const int r = wm * TM - pass * RP + i * 32 + mfma32_row(v, lane);
+                            tile[r * BN + wn * TN + j * 32 + fr] = acc[i][j][v];
+                        }
+            }
+            __syncthreads();
+#pragma unroll 1
+            for (int it = tid; it < ITEMS; it += NT) {
+                const int r = it / (OUT_COLS / 8), c8 = it % (OUT_COLS / 8);
+                const int row = m0 + pass * RP + r;
+                const int ocol = out_n0 + c8 * 8;
+                if (row >= M || ocol >= out_N) continue;
+                float x[8];
+                if (EPI == EPI_SILU_MUL) {
+                    // gate block [64q, 64q+32) and up block [64q+32, 64q+64) of the tile
+                    const int oc = c8 * 8;                      // output column within the tile
+                    const float* g = tile + r * BN + (oc >> 5) * 64 + (oc & 31);
+                    const float4 g0 = *reinterpret_cast<const float4*>(g);
+                    const float4 g1 = *reinterpret_cast<const float4*>(g + 4);
+                    const float4 u0 = *reinterpret_cast<const float4*>(g + 32);
+                    const float4 u1 = *reinterpret_cast<const float4*>(g + 36);
+                    const float gv[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+                    const float uv[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) x[e] = gv[e] / (1.f + __expf(-gv[e])) * uv[e];
+                } else {
+                    const float* t = tile + r * BN + c8 * 8;
+                    const float4 t0 = *reinterpret_cast<const float4*>(t);
+                    const float4 t1 = *reinterpret_cast<const float4*>(t + 4);
+                    x[0] = t0.x; x[1] = t0.y; x[2] = t0.z; x[3] = t0.w;
+                    x[4] = t1.x; x[5] = t1.y; x[6] = t1.z; x[7] = t1.w;
+                }
+                if (EPI == EPI_RES_BF16_TO_F32) {
+                    const uint4 rv = *reinterpret_cast<const uint4*>(
+                        static_cast<const bf16_t*>(Rv) + (size_t)row * ldr + ocol);
+                    const uint32_t rw[4] = {rv.x, rv.y, rv.z, rv.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        x[2 * e] += __uint_as_float(rw[e] << 16);
+                        x[2 * e + 1] += __uint_as_float(rw[e] & 0xFFFF0000u);
                     }
+                    float4* dst = reinterpret_cast<float4*>(static_cast<float*>(Cv) +
+                                                            (size_t)row * ldc + ocol);
+                    dst[0] = make_float4(x[0], x[1], x[2], x[3]);
+                    dst[1] = make_float4(x[4], x[5], x[6], x[7]);
+                } else {
+                    if (EPI == EPI_RES_F32_TO_BF16) {
+                        const float4* rp = reinterpret_cast<const float4*>(
+                            static_cast<const float*>(Rv) + (size_t)row * ldr + ocol);
+                        const float4 r0 = rp[0], r1 = rp[1];
+                        x[0] += r0.x; x[1] += r0.y; x[2] += r0.z; x[3] += r0.w;
+                        x[4] += r1.x; x[5] += r1.y; x[6] += r1.z; x[7] += r1.w;
+                    }
+                    *reinterpret_cast<uint4*>(static_cast<bf16_t*>(Cv) + (size_t)row * ldc + ocol) =
+                        make_uint4(pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]),
+                                   pack_bf16x2(x[4], x[5]), pack_bf16x2(x[6], x[7]));
                 }
             }
         }
@@ -478,6 +541,7 @@ int launch_gemm(const bf16_t* A, int lda, const bf16_t* W, int M, int N, int K, 
     if (M <= 0 || N <= 0) return MVLA_OK;
     if (K < 64 || K % 64 != 0 || lda % 8 != 0) return MVLA_EUNSUPPORTED;
     if (epilogue == EPI_SILU_MUL && N % 64 != 0) return MVLA_EUNSUPPORTED;
+    if (N % 8 != 0 || ldc % 8 != 0 || (R && ldr % 8 != 0)) return MVLA_EUNSUPPORTED;
     int best = 0;
     float best_us = estimate_us(kCfgs[0], M, N, K);
     for (int i = 1; i < kNumCfgs; ++i) {
