@@ -123,6 +123,21 @@ int mvla_prune_step(mvla_ctx* ctx, const float* attn, int H, int Nq, const void*
                     int k_total, int min2, int min3, float* sal, int32_t* k2k3,
                     int32_t* kept_idx, void* h_out, int32_t* pos_out);
 
+/* Per-patch modality indicators of the semantic stage (Sec. 3.2, Eqs. 4-6).
+ * Patch p owns 2D token p and 3D token n_patch + p (needs as many 3D as 2D
+ * tokens, as in the paper's 256 + 256 setup); its attention vectors a2, a3 run
+ * over the H*Nq (head, query) rows.  a3 is split into its projection on a2 and
+ * the orthogonal rest (Eq. 4):
+ *     m2d[b,p] = |a2|_1 / (|a2|_1 + |a3|_1)                          (Eq. 5)
+ *     m3d[b,p] = |a3 - (<a3,a2>/<a2,a2>) a2|_1 / (|a2|_1 + |a3|_1)     (Eq. 6)
+ * (a2 = 0 leaves a3 whole; zero denominator -> 0).  These are the per-patch
+ * indicators M^{S2}_{2D,p}, M^{S2}_{3D,p} of Algorithm 1; their means over
+ * patches are its baselines.
+ * attn: device fp32 [B, H, Nq, S] with 2*n_patch <= S; m2d, m3d: device fp32
+ * [B, n_patch]. */
+int mvla_modality_decompose(mvla_ctx* ctx, const float* attn, int B, int H, int Nq, int S,
+                            int n_patch, float* m2d, float* m3d);
+
 /* Temporal smoothing of a per-token (or per-patch) indicator across action
  * iterations (Sec. 4.3 Eq. 7; Sec. 4.4 Eqs. 8-9; Algorithm 1 "Action Iteration
  * Stage"), t counted from 1:
@@ -216,9 +231,10 @@ int mvla_profile_enable(mvla_ctx* ctx, uint32_t kernel_mask, int max_records);
  * Clears the record list. */
 int mvla_profile_read(mvla_ctx* ctx, int capacity, int32_t* ids, int32_t* tags, float* ms,
                       int32_t* n_out);
-/* Name of kernel id 0..15 ("rmsnorm", "gemm_qkv", "rope_split", "score_probs",
+/* Name of kernel id 0..16 ("rmsnorm", "gemm_qkv", "rope_split", "score_probs",
  * "attention", "gemm_o", "rmsnorm_mlp", "gemm_gateup", "gemm_down", "salience",
- * "budget", "select", "compact", "rope_table", "prune_fused", "smooth"), "?" otherwise. */
+ * "budget", "select", "compact", "rope_table", "prune_fused", "smooth",
+ * "decompose"), "?" otherwise. */
 const char* mvla_kernel_name(int id);
 
 #ifdef __cplusplus

@@ -43,7 +43,7 @@ import numpy as np
 __all__ = [
     "rmsnorm", "rope_rotate_half", "attention_probs", "decoder_layer",
     "score_only", "salience", "modality_budget", "select_topk", "compact",
-    "keep_count", "pruned_prefill", "ema_indicator",
+    "keep_count", "pruned_prefill", "ema_indicator", "modality_decompose",
 ]
 
 F64 = np.float64
@@ -285,6 +285,38 @@ def pruned_prefill(x, pos, layers, H, n2, n3, n_text, k_total, p,
         for b in range(B):
             h[b], _ = decoder_layer(h[b], pos2[b], layers[li], H, eps, base)
     return dict(y=h, pos=pos2, kept_idx=kept, k2k3=k2k3, sal=sal, probs=probs)
+
+
+# --------------------------------------------------------------------------
+# Semantic-stage modality indicators per patch (Sec. 3.2, Eqs. 4-6)
+# --------------------------------------------------------------------------
+def modality_decompose(probs, n_patch):
+    """Per-patch 2D share and "unique 3D" share of the attention.
+
+    probs: [B, H, Nq, S]; patch p owns 2D token p and 3D token n_patch + p.
+    Its two attention vectors a2, a3 run over the H*Nq (head, query) rows.
+    a3 is split into the part parallel to a2 and the part orthogonal to it
+    (Eq. 4); with L1 norms,
+        M2D[p] = |a2|_1 / (|a2|_1 + |a3|_1)                       (Eq. 5)
+        M3D[p] = |a3 - (<a3,a2>/<a2,a2>) a2|_1 / (|a2|_1 + |a3|_1)  (Eq. 6)
+    (a2 = 0 leaves a3 whole; a zero denominator gives 0 for both).
+    Returns (m2d, m3d), float64 [B, n_patch] each.
+    """
+    p = np.asarray(probs, F64)
+    B, H, Nq, S = p.shape
+    a2 = p[:, :, :, :n_patch].reshape(B, H * Nq, n_patch)
+    a3 = p[:, :, :, n_patch:2 * n_patch].reshape(B, H * Nq, n_patch)
+    s22 = np.sum(a2 * a2, axis=1)
+    s23 = np.sum(a2 * a3, axis=1)
+    coef = np.divide(s23, s22, out=np.zeros_like(s23), where=s22 > 0)
+    ortho = a3 - coef[:, None, :] * a2
+    l2 = np.sum(np.abs(a2), axis=1)
+    l3 = np.sum(np.abs(a3), axis=1)
+    lo = np.sum(np.abs(ortho), axis=1)
+    den = l2 + l3
+    m2d = np.divide(l2, den, out=np.zeros_like(den), where=den > 0)
+    m3d = np.divide(lo, den, out=np.zeros_like(den), where=den > 0)
+    return m2d, m3d
 
 
 # --------------------------------------------------------------------------

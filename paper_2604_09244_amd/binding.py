@@ -23,6 +23,7 @@ EXPORTS = [
     "mvla_destroy", "mvla_salience", "mvla_modality_budget", "mvla_select_topk", "mvla_compact",
     "mvla_prune_step", "mvla_rope_table", "mvla_prefill_layer", "mvla_score_only",
     "mvla_profile_enable", "mvla_profile_read", "mvla_kernel_name", "mvla_temporal_smooth",
+    "mvla_modality_decompose",
 ]
 
 
@@ -74,6 +75,7 @@ def load() -> C.CDLL:
                                        i, i, vp, i, vp, vp]
     lib.mvla_score_only.argtypes = [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeightsC), vp, vp,
                                     i, i, i, vp, vp]
+    lib.mvla_modality_decompose.argtypes = [vp, vp, i, i, i, i, i, vp, vp]
     lib.mvla_temporal_smooth.argtypes = [vp, vp, vp, sz, i, i, C.c_double]
     lib.mvla_profile_enable.argtypes = [vp, C.c_uint32, i]
     lib.mvla_profile_read.argtypes = [vp, i, vp, vp, vp, vp]
@@ -206,6 +208,16 @@ class Context:
         _check(load().mvla_compact(self._h, h.data_ptr(), pos.data_ptr(), kept.data_ptr(), B, S,
                                    S_out, D, h_out.data_ptr(), pos_out.data_ptr()), "mvla_compact")
         return h_out, pos_out
+
+    def modality_decompose(self, attn: torch.Tensor, n_patch: int):
+        """Per-patch (M2D, M3D) of Eqs. 5-6 from the language-query attention rows."""
+        B, H, Nq, S = _dev(attn, torch.float32).shape
+        m2d = torch.empty(B, n_patch, dtype=torch.float32, device=attn.device)
+        m3d = torch.empty_like(m2d)
+        _check(load().mvla_modality_decompose(self._h, attn.data_ptr(), B, H, Nq, S, n_patch,
+                                              m2d.data_ptr(), m3d.data_ptr()),
+               "mvla_modality_decompose")
+        return m2d, m3d
 
     def temporal_smooth(self, x_t: torch.Tensor, x_hat: torch.Tensor, t: int, k: int = 7,
                         beta: float = 0.85):

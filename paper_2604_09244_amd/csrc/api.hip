@@ -92,7 +92,7 @@ struct Timed {
 const char* const kKernelNames[KID_COUNT] = {
     "rmsnorm", "gemm_qkv", "rope_split", "score_probs", "attention", "gemm_o", "rmsnorm_mlp",
     "gemm_gateup", "gemm_down", "salience", "budget", "select", "compact", "rope_table",
-    "prune_fused", "smooth"};
+    "prune_fused", "smooth", "decompose"};
 
 }  // namespace
 
@@ -280,6 +280,16 @@ int mvla_prune_step(mvla_ctx* ctx, const float* attn, int H, int Nq, const void*
                              kept_idx, reinterpret_cast<float*>(ctx->scratch), ctx->counters,
                              ctx->stream));
     return mvla_compact(ctx, h, pos, kept_idx, B, S, k_total + n_text, D, h_out, pos_out);
+}
+
+int mvla_modality_decompose(mvla_ctx* ctx, const float* attn, int B, int H, int Nq, int S,
+                            int n_patch, float* m2d, float* m3d) {
+    if (!ctx || !attn || !m2d || !m3d) return MVLA_EINVAL;
+    if (B <= 0 || H <= 0 || Nq <= 0 || S <= 0 || n_patch <= 0 || 2 * (long)n_patch > S)
+        return MVLA_EINVAL;
+    int rc;
+    TIMED(ctx, KID_DECOMPOSE, B, launch_decompose(attn, B, H, Nq, S, n_patch, m2d, m3d, ctx->stream));
+    return MVLA_OK;
 }
 
 int mvla_temporal_smooth(mvla_ctx* ctx, const float* x_t, float* x_hat, size_t n, int t, int k,

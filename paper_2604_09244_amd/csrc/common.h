@@ -14,7 +14,7 @@ typedef uint16_t bf16_t;  // raw bf16 storage
 enum KernelId {
     KID_RMSNORM = 0, KID_GEMM_QKV, KID_ROPE_SPLIT, KID_SCORE_PROBS, KID_ATTENTION, KID_GEMM_O,
     KID_RMSNORM_MLP, KID_GEMM_GATEUP, KID_GEMM_DOWN, KID_SALIENCE, KID_BUDGET, KID_SELECT,
-    KID_COMPACT, KID_ROPE_TABLE, KID_PRUNE_FUSED, KID_SMOOTH, KID_COUNT
+    KID_COMPACT, KID_ROPE_TABLE, KID_PRUNE_FUSED, KID_SMOOTH, KID_DECOMPOSE, KID_COUNT
 };
 
 struct ProfRecord {
@@ -69,6 +69,8 @@ int launch_select(const float* sal, const int32_t* k2k3, int B, int n2, int n3, 
 int launch_compact(const bf16_t* h, const int32_t* pos, const int32_t* kept_idx, int B, int S,
                    int S_out, int D, bf16_t* h_out, int32_t* pos_out, hipStream_t st);
 
+int launch_decompose(const float* attn, int B, int H, int Nq, int S, int n_patch, float* m2d,
+                     float* m3d, hipStream_t st);
 int launch_smooth(const float* x_t, float* x_hat, size_t n, int t, int k, double beta,
                   hipStream_t st);
 

@@ -483,6 +483,81 @@ int launch_compact(const bf16_t* h, const int32_t* pos, const int32_t* kept_idx,
 }
 
 // ---------------------------------------------------------------------------
+// Per-patch modality indicators of the semantic stage (paper Sec. 3.2,
+// Eqs. 4-6): the 3D attention vector of a patch (over the head x query rows)
+// is split into its projection on the 2D vector and the orthogonal rest; the
+// outputs are the L1 shares |a2| / (|a2|+|a3|) and |a3_ortho| / (|a2|+|a3|).
+// One workgroup handles 64 patches of one sample: 4 row-groups x 64 lanes, a
+// lane owns a patch (coalesced 256-byte row segments); pass 1 accumulates
+// <a2,a2>, <a2,a3>, |a2|, |a3|, pass 2 the L1 norm of the residual.
+// ---------------------------------------------------------------------------
+constexpr int DEC_THREADS = 256;
+
+__global__ __launch_bounds__(DEC_THREADS) void decompose_kernel(const float* __restrict__ attn,
+                                                                int R, int S, int n_patch,
+                                                                float* __restrict__ m2d,
+                                                                float* __restrict__ m3d) {
+    __shared__ float red[4][DEC_THREADS / 64][64];
+    __shared__ float coef[64];
+    const int b = blockIdx.y, p = blockIdx.x * 64 + (threadIdx.x & 63), g = threadIdx.x >> 6;
+    const bool live = p < n_patch;
+    const float* base = attn + (size_t)b * R * S;
+    float s22 = 0.f, s23 = 0.f, l2 = 0.f, l3 = 0.f;
+    if (live)
+        for (int r = g; r < R; r += DEC_THREADS / 64) {
+            const float a2 = base[(size_t)r * S + p], a3 = base[(size_t)r * S + n_patch + p];
+            s22 += a2 * a2;
+            s23 += a2 * a3;
+            l2 += fabsf(a2);
+            l3 += fabsf(a3);
+        }
+    red[0][g][threadIdx.x & 63] = s22;
+    red[1][g][threadIdx.x & 63] = s23;
+    red[2][g][threadIdx.x & 63] = l2;
+    red[3][g][threadIdx.x & 63] = l3;
+    __syncthreads();
+    float den = 0.f, n2 = 0.f;
+    if (g == 0) {
+        float t[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            t[q] = 0.f;
+#pragma unroll
+            for (int w = 0; w < DEC_THREADS / 64; ++w) t[q] += red[q][w][threadIdx.x];
+        }
+        coef[threadIdx.x] = t[0] > 0.f ? t[1] / t[0] : 0.f;
+        n2 = t[2];
+        den = t[2] + t[3];
+    }
+    __syncthreads();
+    const float c = coef[threadIdx.x & 63];
+    float lo = 0.f;
+    if (live)
+        for (int r = g; r < R; r += DEC_THREADS / 64) {
+            const float a2 = base[(size_t)r * S + p], a3 = base[(size_t)r * S + n_patch + p];
+            lo += fabsf(a3 - c * a2);
+        }
+    __syncthreads();
+    red[0][g][threadIdx.x & 63] = lo;
+    __syncthreads();
+    if (g == 0 && live) {
+        float t = 0.f;
+#pragma unroll
+        for (int w = 0; w < DEC_THREADS / 64; ++w) t += red[0][w][threadIdx.x];
+        m2d[(size_t)b * n_patch + p] = den > 0.f ? n2 / den : 0.f;
+        m3d[(size_t)b * n_patch + p] = den > 0.f ? t / den : 0.f;
+    }
+}
+
+int launch_decompose(const float* attn, int B, int H, int Nq, int S, int n_patch, float* m2d,
+                     float* m3d, hipStream_t st) {
+    hipLaunchKernelGGL(decompose_kernel, dim3((n_patch + 63) / 64, B), dim3(DEC_THREADS), 0, st, attn,
+                       H * Nq, S, n_patch, m2d, m3d);
+    MVLA_HIP_CHECK(hipGetLastError());
+    return MVLA_OK;
+}
+
+// ---------------------------------------------------------------------------
 // Action-iteration smoothing of an indicator (paper Sec. 4.3 Eq. 7, Sec. 4.4
 // Eqs. 8-9): observation at the cold start, running mean while the window
 // fills, exponential moving average afterwards.  w_prev and w_new are the two

@@ -202,3 +202,22 @@ def test_argument_errors_launch_nothing(ctx):
     assert lib.mvla_compact(ctx.handle, h.data_ptr(), pos.data_ptr(), pos.data_ptr(), 1, 4, 2, 7,
                             h.data_ptr(), pos.data_ptr()) == -1   # D % 8
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("B,H,Nq,n_patch,extra", [(1, 4, 16, 64, 16), (2, 32, 32, 256, 32),
+                                                  (3, 5, 7, 70, 3), (1, 1, 1, 1, 0)])
+def test_modality_decompose_parity(ctx, B, H, Nq, n_patch, extra):
+    """Eqs. 4-6 per patch against the oracle (fp32 sums on the GPU: 1e-5 relative on M2D, 1e-4
+    absolute on the orthogonal share, whose residual |a3 - c a2| cancels)."""
+    S = 2 * n_patch + extra
+    g = torch.Generator().manual_seed(B * 100 + n_patch)
+    p = torch.rand(B, H, Nq, S, generator=g) ** 3
+    p = (p / p.sum(-1, keepdim=True)).contiguous()
+    if n_patch > 2:
+        p[:, :, :, n_patch + 1] = 0.5 * p[:, :, :, 1]      # a parallel patch
+        p[:, :, :, 2] = 0.0                                # an empty 2D vector
+    m2, m3 = ctx.modality_decompose(p.cuda(), n_patch)
+    torch.cuda.synchronize()
+    r2, r3 = O.modality_decompose(p.numpy(), n_patch)
+    assert np.max(np.abs(to64(m2) - r2)) <= 1e-5 * max(1.0, r2.max())
+    assert np.max(np.abs(to64(m3) - r3)) <= 1e-4

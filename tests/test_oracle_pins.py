@@ -380,6 +380,34 @@ def test_overhead_definition_from_table4():
     assert round(float(cost_ms) / 1000 / float(lat_s) * 100, 1) == float(pct)
 
 
+# ---------------------------------------------------------------- Eqs. 4-6
+def test_modality_decompose_special_cases():
+    r = rng(21)
+    B, H, Nq, n = 2, 3, 4, 5
+    S = 2 * n + 2
+    p = r.random((B, H, Nq, S))
+    # patch 0: a3 = 0.25 * a2 -> nothing orthogonal; patch 1: disjoint supports -> all of a3 is
+    # orthogonal; patch 2: a2 = 0 -> a3 stays whole
+    p[:, :, :, n + 0] = 0.25 * p[:, :, :, 0]
+    p[:, :, :2, 1] = 0.0
+    p[:, :, 2:, n + 1] = 0.0
+    p[:, :, :, 2] = 0.0
+    m2, m3 = O.modality_decompose(p, n)
+    assert np.allclose(m3[:, 0], 0.0, atol=1e-15) and np.allclose(m2[:, 0], 1 / 1.25)
+    assert np.allclose(m2[:, 1] + m3[:, 1], 1.0)
+    assert np.allclose(m2[:, 2], 0.0) and np.allclose(m3[:, 2], 1.0)
+    # generic patches: the residual is orthogonal to a2, Pythagoras holds, and 0 <= M3D <= 1 - M2D
+    a2 = p[:, :, :, 3].reshape(B, -1)
+    a3 = p[:, :, :, n + 3].reshape(B, -1)
+    for b in range(B):
+        c = np.linalg.lstsq(a2[b][:, None], a3[b], rcond=None)[0][0]   # library projection
+        res = a3[b] - c * a2[b]
+        assert abs(res @ a2[b]) < 1e-12
+        assert math.isclose(m3[b, 3], np.abs(res).sum() / (a2[b].sum() + a3[b].sum()), rel_tol=1e-12)
+        assert math.isclose(res @ res + (c * a2[b]) @ (c * a2[b]), a3[b] @ a3[b], rel_tol=1e-12)
+    assert np.all(m3 >= 0) and np.all(m3 <= 1 - m2 + 1e-12)
+
+
 # ---------------------------------------------------------------- bf16 operand floor
 def test_bf16_operand_rounding_floor():
     """An fp64 layer whose only inexact steps are bf16 roundings of the eight
