@@ -131,7 +131,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     constexpr int P = A_LD + B_LD;          // direct loads per thread per slab
     static_assert(BM * CPR % NT == 0 && BN * CPR % NT == 0, "tile/thread mismatch");
     static_assert(KS % 2 == 0 && NS >= 2, "");
-    static_assert(EPI != EPI_SILU_MUL || FN % 2 == 0, "gate/up pairs must share a wave");
+    // the K-split fix-up adds gate and up registers of one lane: needs both blocks in one wave
+    constexpr bool SK_OK = !(EPI == EPI_SILU_MUL && FN % 2 != 0);
 
     extern __shared__ uint4 lds[];
     __shared__ int sh_last;
@@ -275,7 +276,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
 #undef MVLA_MFMA
 
         // ---- K-split tiles: park the partial sums; the last piece to arrive finishes --------
-        const int n_pieces = is_dp ? 1 : last_blk - first_blk + 1;
+        const int n_pieces = (is_dp || !SK_OK) ? 1 : last_blk - first_blk + 1;
         if (n_pieces > 1) {
             // slot 0 of a workgroup holds the piece of the tile its range starts in, slot 1 the next
             const int my_slot = 2 * sk_id + (seg == 0 ? 0 : 1);
@@ -313,7 +314,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
             if (!sh_last) continue;
             // Sum the pieces in piece order, one 32x32 block (gate and up blocks together) at a
             // time, and send each element through the epilogue.
-            constexpr int JS2 = EPI == EPI_SILU_MUL ? 2 : 1;
+            constexpr int JS2 = (EPI == EPI_SILU_MUL && SK_OK) ? 2 : 1;
 #pragma unroll 1
             for (int ij = 0; ij < FM * FN; ij += JS2) {
                 const int i = ij / FN, j = ij % FN;
@@ -356,7 +357,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
         // A pass covers as many tile rows as the pipeline's LDS holds (a whole number of wave
         // rows); only the waves owning those rows write.
         constexpr int LDS_FLOATS = NS * STAGE * 4;
-        constexpr int PASSES = (BM * BN + LDS_FLOATS - 1) / LDS_FLOATS;
+        constexpr int PASSES = BM * BN <= LDS_FLOATS ? 1 : WM;   // whole tile, or one wave row each
         constexpr int RP = BM / PASSES;                  // tile rows per pass
         static_assert(BM % PASSES == 0 && RP % TM == 0, "pass must hold whole wave rows");
         static_assert(RP * BN <= LDS_FLOATS, "epilogue tile does not fit the stages");
@@ -473,7 +474,9 @@ static int launch_cfg(const bf16_t* A, int lda, const bf16_t* W, int M, int N, i
                       int ldc, const void* R, int ldr, int epi, int slots_per_cu, int sk_pct,
                       float* partial,
                       size_t partial_bytes, uint32_t* counters, int n_counters, hipStream_t st) {
-    GemmPlan plan = make_plan(M, N, K, BM, BN, BK, kNumCUs * slots_per_cu, sk_pct);
+    constexpr bool sk_ok = !((BN / WN / 32) % 2 != 0);   // odd wave width: no K-split for gate/up
+    GemmPlan plan = make_plan(M, N, K, BM, BN, BK, kNumCUs * slots_per_cu,
+                              (epi == EPI_SILU_MUL && !sk_ok) ? 0 : sk_pct);
     if (plan.sk_blocks > 0) {
         const size_t need = (size_t)2 * plan.sk_blocks * BM * BN * sizeof(float);
         if (need > partial_bytes || plan.sk_tiles > n_counters) {  // no room: whole tiles only
@@ -514,12 +517,13 @@ struct TileCfg {
     int BM, BN, slots_per_cu;
     float round_us;
 };
-constexpr int kNumCfgs = 4;
+constexpr int kNumCfgs = 5;
 static const TileCfg kCfgs[kNumCfgs] = {
     {256, 256, 1, 110.f},  // K-slab 64, eight waves of 128x64, two stages
     {256, 128, 1, 62.f},   // K-slab 64, eight waves of 64x64, three stages
     {128, 128, 2, 67.f},   // K-slab 64, four waves of 64x64, two stages, two workgroups per CU
     {128, 128, 1, 37.f},   // K-slab 64, four waves of 64x64, three stages
+    {288, 192, 1, 128.f},  // K-slab 64, six waves of 96x96, two stages (row counts just over 2x256)
 };
 constexpr int kSplitPct = 50;        // cut the last round along K only when it is under half full
 constexpr float kSplitOverhead = 0.3f;  // cost of the partial-sum exchange, in rounds
@@ -557,7 +561,8 @@ int launch_gemm(const bf16_t* A, int lda, const bf16_t* W, int M, int N, int K, 
         case 0: return launch_cfg<256, 256, 64, 2, 4, 2>(MVLA_ARGS);
         case 1: return launch_cfg<256, 128, 64, 4, 2, 3>(MVLA_ARGS);
         case 2: return launch_cfg<128, 128, 64, 2, 2, 2>(MVLA_ARGS);
-        default: return launch_cfg<128, 128, 64, 2, 2, 3>(MVLA_ARGS);
+        case 3: return launch_cfg<128, 128, 64, 2, 2, 3>(MVLA_ARGS);
+        default: return launch_cfg<288, 192, 64, 3, 2, 2>(MVLA_ARGS);
     }
 #undef MVLA_ARGS
 }
