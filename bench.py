@@ -29,7 +29,7 @@ if ROOT not in sys.path:
 # plain copy of known size (see profiles/single_view_gemm_gateup_hbm_traffic.txt).  Valid only
 # for the GEMM source the counters were taken with: keyed by kernel shape and a hash of gemm.hip.
 MEASURED_TRAFFIC = {
-    ("gemm_gateup", 544, 22016, 4096): (275.6e6, "ceab005022a7efb6"),
+    ("gemm_gateup", 544, 22016, 4096): (232.8e6, "fba67ffa73d6fd87"),
 }
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
@@ -72,7 +72,7 @@ def main():
                     help="issue the four pruning calls one by one instead of mvla_prune_step")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (batch samples are "
+        print("bench.py measures one GPU: this library has no multi-GPU path (batch samples are "
               "independent and would shard with replicated weights and no exchange); "
               "run with --gpus 1", file=sys.stderr)
         sys.exit(2)

@@ -257,7 +257,7 @@ def test_action_iteration_sequence(ctx):
     layers = [mv.pack_layer({k: v.cuda() for k, v in w.items()}) for w in ws_cpu]
     plan = mv.PrefillPlan(ctx, layer_cfg(wl), layers, wl.B, wl.n2, wl.n3, wl.nt, wl.k_total, wl.p)
     x, pos = W.hidden_states(wl, device="cuda")
-    overlaps, prev_kept = [], None
+    overlaps = []
     for t in range(wl.steps):
         if t > 0:
             x = W.next_timestep(wl, x, t)
@@ -280,6 +280,4 @@ def test_action_iteration_sequence(ctx):
             assert np.array_equal(k2k3.cpu().numpy(), ora["k2k3"])
             assert np.array_equal(kept.cpu().numpy(), ora["kept_idx"])
             overlaps.append(len(set(kept_gpu[0]) & set(ora["kept_idx"][0])) / wl.S_kept)
-            # kept-token layer, teacher-forced on the oracle's compacted hidden states
-        prev_kept = kept_gpu
     assert min(overlaps) > 0.9, overlaps
