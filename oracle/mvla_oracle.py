@@ -23,6 +23,11 @@ What is modelled (paper: "2D or 3D: Who Governs Salience in VLA Models?"):
   Sec. 4.4: kept tokens go on to the later layers, the rest are discarded.
 * Temporal smoothing of an indicator (Sec. 4.3/4.4, Eqs. 7-9, Algorithm 1
   "Action Iteration Stage").
+* The mask generation of Algorithm 1 itself (dual threshold on the per-patch
+  feature share of Eq. 1, 1-D k-means into background / robot / object,
+  the semantic rules with their two baselines, intersection fusion with the
+  conflict fallback, Eq. 10), for inputs with one 3D token per 2D token.
+  The random draws of the background rule are an input.
 
 Every reduction is carried in float64.  Inputs are whatever values the caller
 hands over (for bf16 workloads: the bf16-rounded values widened to float64);
@@ -31,7 +36,10 @@ nothing is rounded in between.
 Pins (tests/test_oracle_pins.py): brute-force subset enumeration and
 torch.topk for selection; closed forms for salience, budget, RMSNorm, RoPE,
 EMA; a loop-written O(n^2) attention and torch's scaled_dot_product_attention;
-an independently written torch-CPU decoder layer; keep-100% == unpruned.
+an independently written torch-CPU decoder layer; keep-100% == unpruned;
+scikit-learn's Lloyd iteration from the same start, well-separated clusters
+and the fixed-point property for the k-means; hand-derived rule tables for the
+candidate sets and their fusion.
 End-to-end selection *quality* against the paper's success rates and measured
 per-modality pruning rates is parity unpinned (needs the simulator and the
 model checkpoint).
@@ -44,6 +52,8 @@ __all__ = [
     "rmsnorm", "rope_rotate_half", "attention_probs", "decoder_layer",
     "score_only", "salience", "modality_budget", "select_topk", "compact",
     "keep_count", "pruned_prefill", "ema_indicator", "modality_decompose",
+    "feature_share", "kmeans_1d", "candidate_masks", "mask_indices", "patch_score",
+    "masked_prefill", "SEM_BG", "SEM_ROB", "SEM_OBJ",
 ]
 
 F64 = np.float64
@@ -336,3 +346,215 @@ def ema_indicator(x_hat_prev, x_t, t, k=7, beta=0.85):
     if t < k:
         return prev * (F64(t - 1) / F64(t)) + x_t / F64(t)
     return beta * prev + (1.0 - beta) * x_t
+
+
+# --------------------------------------------------------------------------
+# Mask generation of the tri-stage framework (Sec. 4.1-4.4, Algorithm 1)
+# --------------------------------------------------------------------------
+def feature_share(feat, n_patch):
+    """Data-preprocessing indicators per patch (Sec. 3.1, Eq. 1).
+
+    feat: [B, S, D] token features; patch p owns rows p (2D) and n_patch + p
+    (3D).  With l2 = |f_2D|_1 and l3 = |f_3D|_1 of the patch,
+        M2D[p] = l2 / (l2 + l3),   M3D[p] = l3 / (l2 + l3)
+    (both 0 when l2 + l3 == 0).  Returns (m2d, m3d), float64 [B, n_patch].
+    """
+    f = np.asarray(feat, F64)
+    l2 = np.sum(np.abs(f[:, :n_patch, :]), axis=-1)
+    l3 = np.sum(np.abs(f[:, n_patch:2 * n_patch, :]), axis=-1)
+    den = l2 + l3
+    m2d = np.divide(l2, den, out=np.zeros_like(den), where=den > 0)
+    m3d = np.divide(l3, den, out=np.zeros_like(den), where=den > 0)
+    return m2d, m3d
+
+
+def kmeans_1d(v, max_iter=32):
+    """Lloyd's k-means with 3 centres on the scalars v (Sec. 4.2: 1-D K-Means,
+    K = 3, on the patches' attention scores).
+
+    The paper fixes neither the start nor the stopping rule; taken here:
+    centres start at (min, (min+max)/2, max); a point goes to the nearest
+    centre, the lower-numbered one on equal distance; a centre becomes the
+    mean of its points (a centre without points stays); stop when an
+    assignment repeats the previous one or after max_iter assignments.
+    Returns (labels int [n] in {0,1,2}, centres float64 [3], margin) where
+    margin is the smallest gap, over all assignments made, between a point's
+    nearest and second-nearest distance relative to the data range (tests
+    use it to set aside inputs that sit on a rounding knife-edge).
+    """
+    x = np.asarray(v, F64).ravel()
+    lo, hi = x.min(), x.max()
+    c = np.array([lo, 0.5 * (lo + hi), hi], F64)
+    span = hi - lo if hi > lo else 1.0
+    labels, margin = None, np.inf
+    for _ in range(max_iter):
+        d = np.abs(x[:, None] - c[None, :])            # [n, 3]
+        new = np.argmin(d, axis=1)                     # first minimum: lower centre on ties
+        for a in range(3):                             # knife-edge measure, distinct centres only
+            for b2 in range(a + 1, 3):
+                if c[a] != c[b2]:
+                    near = np.minimum(d[:, a], d[:, b2]) <= d.min(axis=1)
+                    if near.any():
+                        gap = np.abs(d[near, a] - d[near, b2]).min()
+                        margin = min(margin, gap / span)
+        if labels is not None and np.array_equal(new, labels):
+            break
+        labels = new
+        for j in range(3):
+            members = x[labels == j]
+            if members.size:
+                c[j] = members.sum() / members.size
+    return labels.astype(np.int64), c, margin
+
+
+SEM_BG, SEM_ROB, SEM_OBJ = 0, 1, 2
+
+
+def candidate_masks(x_hat, score, u, tau_2d=0.08, tau_3d=0.20, bg_drop=0.9,
+                    obj_2d_min=0.9, obj_3d_max=0.01, max_iter=32):
+    """Candidate sets and retention masks of Algorithm 1 for t > 1
+    (Sec. 4.1 dual threshold, Sec. 4.2 semantic rules, Sec. 4.4 fusion, Eq. 10).
+
+    x_hat: float32 [4, B, P], the smoothed per-patch indicators in the order
+           (M2D^S1, M3D^S1, M2D^S2, M3D^S2).
+    score: float32 [B, P], the patch's attention score that is clustered.
+    u    : float32 [B, P], uniform draws in [0, 1) for the background drop.
+    Decisions compare float32 values with float32 thresholds; the two
+    baselines are float64 means over the sample's patches.
+    Readings where the text gives no number: clusters are named by the order
+    of their centres (lowest = background, middle = robot, highest = object);
+    "2D far above 0 and 3D near 0" for an object patch is
+    M2D^S2 > obj_2d_min and M3D^S2 < obj_3d_max.
+    Returns dict(mask2d, mask3d uint8 [B, P]; sem uint8 [B, P];
+    mu float64 [B, 2]; kmeans_margin, mu_margin float64 [B]).
+    """
+    xh = np.asarray(x_hat)
+    assert xh.dtype == np.float32 and xh.shape[0] == 4
+    sc = np.asarray(score)
+    uu = np.asarray(u)
+    assert sc.dtype == np.float32 and uu.dtype == np.float32
+    _, B, P = xh.shape
+    f32 = np.float32
+    mask2d = np.zeros((B, P), np.uint8)
+    mask3d = np.zeros((B, P), np.uint8)
+    sem = np.zeros((B, P), np.uint8)
+    mu = np.zeros((B, 2), F64)
+    km_margin = np.zeros(B, F64)
+    mu_margin = np.zeros(B, F64)
+    for b in range(B):
+        labels, _, km_margin[b] = kmeans_1d(sc[b], max_iter)
+        m2 = xh[2, b].astype(F64)
+        m3 = xh[3, b].astype(F64)
+        mu2 = m2.sum() / P
+        mu3 = m3.sum() / P
+        mu[b] = (mu2, mu3)
+        mu_margin[b] = min(np.min(np.abs(m2 - mu2)), np.min(np.abs(m3 - mu3)))
+        for p in range(P):
+            # data-preprocessing stage: dual threshold on the smoothed 3D share
+            m3_s1 = xh[1, b, p]
+            if m3_s1 < f32(tau_2d):
+                c1 = {"2D"}
+            elif m3_s1 > f32(tau_3d):
+                c1 = {"3D"}
+            else:
+                c1 = {"2D", "3D"}
+            # semantic stage
+            s = int(labels[p])
+            sem[b, p] = s
+            if s == SEM_BG:
+                c2 = set() if uu[b, p] < f32(bg_drop) else {"2D", "3D"}
+            elif s == SEM_ROB:
+                if m3[p] > mu3:
+                    c2 = {"2D", "3D"}
+                elif m2[p] > mu2:
+                    c2 = {"2D"}
+                else:
+                    c2 = set()
+            else:
+                if xh[2, b, p] > f32(obj_2d_min) and xh[3, b, p] < f32(obj_3d_max):
+                    c2 = {"2D"}
+                else:
+                    c2 = {"2D", "3D"}
+            # fusion: patches without a semantic candidate are dropped
+            if c2:
+                cf = c2 & c1
+                if not cf:
+                    cf = c2
+                mask2d[b, p] = 1 if "2D" in cf else 0
+                mask3d[b, p] = 1 if "3D" in cf else 0
+    return dict(mask2d=mask2d, mask3d=mask3d, sem=sem, mu=mu,
+                kmeans_margin=km_margin, mu_margin=mu_margin)
+
+
+def mask_indices(mask2d, mask3d, n_text):
+    """Kept token indices per sample from the two masks (Eq. 10): 2D tokens
+    with mask 1, then 3D tokens with mask 1 (offset by the patch count), then
+    every language token.  Returns a list of B int32 arrays (ragged)."""
+    m2 = np.asarray(mask2d)
+    m3 = np.asarray(mask3d)
+    B, P = m2.shape
+    out = []
+    for b in range(B):
+        keep2 = [p for p in range(P) if m2[b, p]]
+        keep3 = [P + p for p in range(P) if m3[b, p]]
+        text = list(range(2 * P, 2 * P + n_text))
+        out.append(np.array(keep2 + keep3 + text, np.int32))
+    return out
+
+
+def patch_score(sal, n_patch):
+    """Attention score of a patch: its 2D token's salience plus its 3D token's
+    (the summand of Eq. 3), added in float32 as the kernel does."""
+    s = np.asarray(sal, np.float32)
+    return s[:, :n_patch] + s[:, n_patch:2 * n_patch]
+
+
+def masked_prefill(x, pos, layers, H, n_patch, n_text, p, t, x_hat_prev, u,
+                   eps=1e-5, base=10000.0, key_bias=None, k=7, beta=0.85,
+                   **rule_kw):
+    """One action-iteration step of the whole path with Algorithm 1's masks.
+
+    p >= 1 layers run on all tokens; the p-th yields the language-query
+    probabilities, and its output rows serve as the token features of Eq. 1
+    (the paper hooks the last layer, where pruned tokens no longer exist;
+    taken here: the last layer that still sees every token).  The four
+    indicators are smoothed over steps (Eqs. 8-9); at t == 1 nothing is
+    pruned; later the masks select the tokens and the remaining layers run
+    per sample on its own kept tokens (ragged).
+    Returns dict(y: list of [S'_b, D], kept: list of int32, x_hat float64
+    [4,B,P], x_t, masks: dict or None, probs, sal, feat).
+    """
+    x = np.asarray(x, F64)
+    B, S, D = x.shape
+    assert p >= 1 and S == 2 * n_patch + n_text
+    h = x.copy()
+    probs = [None] * B
+    for li in range(p):
+        tail = n_text if li == p - 1 else 0
+        for b in range(B):
+            kb = None if key_bias is None else key_bias[b]
+            h[b], pr = decoder_layer(h[b], pos[b], layers[li], H, eps, base, tail, kb)
+            if tail:
+                probs[b] = pr
+    probs = np.stack(probs)
+    m2_s1, m3_s1 = feature_share(h, n_patch)
+    m2_s2, m3_s2 = modality_decompose(probs, n_patch)
+    x_t = np.stack([m2_s1, m3_s1, m2_s2, m3_s2])
+    x_hat = ema_indicator(x_hat_prev, x_t, t, k, beta)
+    sal = salience(probs, 2 * n_patch).astype(np.float32)
+    if t == 1:
+        masks = None
+        kept = [np.arange(S, dtype=np.int32) for _ in range(B)]
+    else:
+        masks = candidate_masks(x_hat.astype(np.float32), patch_score(sal, n_patch),
+                                np.asarray(u, np.float32), **rule_kw)
+        kept = mask_indices(masks["mask2d"], masks["mask3d"], n_text)
+    ys = []
+    for b in range(B):
+        hb = h[b][kept[b]].copy()
+        pb = np.asarray(pos)[b][kept[b]]
+        for li in range(p, len(layers)):
+            hb, _ = decoder_layer(hb, pb, layers[li], H, eps, base)
+        ys.append(hb)
+    return dict(y=ys, kept=kept, x_hat=x_hat, x_t=x_t, masks=masks, probs=probs,
+                sal=sal, feat=h)
