@@ -149,6 +149,68 @@ int mvla_modality_decompose(mvla_ctx* ctx, const float* attn, int B, int H, int 
 int mvla_temporal_smooth(mvla_ctx* ctx, const float* x_t, float* x_hat, size_t n, int t, int k,
                          double beta);
 
+/* Data-preprocessing indicators per patch (Sec. 3.1, Eq. 1): with l2, l3 the
+ * L1 norms of the patch's 2D and 3D token features,
+ *     m2d[b,p] = l2 / (l2 + l3),   m3d[b,p] = l3 / (l2 + l3)   (0 if l2+l3 == 0).
+ * Patch p owns token rows p and n_patch + p.
+ * feat: device bf16 [B, S, D], D % 8 == 0, 2*n_patch <= S (which layer's
+ * output serves as "features" is the caller's choice); m2d, m3d: device fp32
+ * [B, n_patch].  fp32 accumulation. */
+int mvla_feature_share(mvla_ctx* ctx, const void* feat, int B, int S, int D, int n_patch,
+                       float* m2d, float* m3d);
+
+/* Constants of the mask rules of Algorithm 1.  tau_2d, tau_3d: the dual
+ * threshold on the smoothed 3D feature share (Sec. 4.1; paper: 0.08, 0.20).
+ * bg_drop: probability with which a background patch is discarded (Sec. 4.2:
+ * 0.9).  obj_2d_min, obj_3d_max: an object patch keeps only its 2D token
+ * when M2D^S2 > obj_2d_min and M3D^S2 < obj_3d_max (the paper says "far above
+ * 0" and "near 0" without numbers).  kmeans_max_iter: cap on the Lloyd
+ * assignments. */
+typedef struct mvla_mask_rules {
+    float tau_2d, tau_3d, bg_drop, obj_2d_min, obj_3d_max;
+    int32_t kmeans_max_iter;
+} mvla_mask_rules;
+/* Fills *r (host) with 0.08, 0.20, 0.9, 0.9, 0.01, 32. */
+void mvla_mask_rules_default(mvla_mask_rules* r);
+
+/* Candidate sets, their fusion and the retention masks of Algorithm 1 for a
+ * step t > 1 (Sec. 4.1, 4.2, 4.4; Eq. 10), one sample at a time:
+ *  - patch score = sal[b,p] + sal[b,n_patch+p] (fp32); Lloyd's 1-D k-means
+ *    with 3 centres started at (min, mid-range, max), nearest centre with the
+ *    lower-numbered one on equal distance, centres as fp64 means, a centre
+ *    without points unchanged, stopping when an assignment repeats or after
+ *    kmeans_max_iter assignments; lowest centre = background (sem 0), middle =
+ *    robot (1), highest = object (2);
+ *  - baselines mu2, mu3: fp64 means over the sample's patches of M2D^S2, M3D^S2;
+ *  - C1 = {2D} if M3D^S1 < tau_2d, {3D} if > tau_3d, else {2D,3D};
+ *  - C2: background: {} if u < bg_drop else {2D,3D}; robot: {2D,3D} if
+ *    M3D^S2 > mu3, else {2D} if M2D^S2 > mu2, else {}; object: {2D} under
+ *    the exception above, else {2D,3D};
+ *  - C2 = {} drops the patch; otherwise C = C1 & C2, or C2 when that is empty.
+ * x_hat : device fp32 [4, B, n_patch], smoothed indicators in the order
+ *         M2D^S1, M3D^S1, M2D^S2, M3D^S2 (row 0 is not read).
+ * sal   : device fp32 [B, 2*n_patch] (as mvla_salience writes for n_vis = 2*n_patch).
+ * u     : device fp32 [B, n_patch], caller-drawn uniforms in [0, 1).
+ * rules : host.
+ * mask2d, mask3d: device uint8 [B, n_patch], 1 = keep; sem: device uint8
+ *         [B, n_patch] or NULL; kept_len: device int32 [B] = kept visual
+ *         tokens + n_text.
+ * n_patch <= 16384, else MVLA_EUNSUPPORTED.  NaN/Inf are invalid input. */
+int mvla_candidate_masks(mvla_ctx* ctx, const float* x_hat, const float* sal, const float* u, int B,
+                         int n_patch, int n_text, const mvla_mask_rules* rules, uint8_t* mask2d,
+                         uint8_t* mask3d, uint8_t* sem, int32_t* kept_len);
+
+/* Masks to token indices (Eq. 10: tokens with mask 1 go on): per sample the
+ * kept 2D token indices ascending, then the kept 3D ones (n_patch + p), then
+ * the n_text language tokens 2*n_patch ..; entries from kept_len[b] up to
+ * S_pad repeat the last token's index so that every row has S_pad entries
+ * (padding rows sit after all real rows, where causal attention never looks
+ * back at them).  A row with more than S_pad kept tokens is cut at S_pad:
+ * pass S_pad >= max_b kept_len[b].
+ * kept_idx: device int32 [B, S_pad], usable by mvla_compact with S_out = S_pad. */
+int mvla_mask_indices(mvla_ctx* ctx, const uint8_t* mask2d, const uint8_t* mask3d, int B,
+                      int n_patch, int n_text, int S_pad, int32_t* kept_idx);
+
 /* ------------------------------------------------------------------------ */
 /* Backbone layer                                                           */
 /* ------------------------------------------------------------------------ */
@@ -231,10 +293,11 @@ int mvla_profile_enable(mvla_ctx* ctx, uint32_t kernel_mask, int max_records);
  * Clears the record list. */
 int mvla_profile_read(mvla_ctx* ctx, int capacity, int32_t* ids, int32_t* tags, float* ms,
                       int32_t* n_out);
-/* Name of kernel id 0..16 ("rmsnorm", "gemm_qkv", "rope_split", "score_probs",
+/* Name of kernel id 0..19 ("rmsnorm", "gemm_qkv", "rope_split", "score_probs",
  * "attention", "gemm_o", "rmsnorm_mlp", "gemm_gateup", "gemm_down", "salience",
  * "budget", "select", "compact", "rope_table", "prune_fused", "smooth",
- * "decompose"), "?" otherwise. */
+ * "decompose", "feature_share", "candidate_masks", "mask_indices"), "?"
+ * otherwise. */
 const char* mvla_kernel_name(int id);
 
 #ifdef __cplusplus

@@ -23,7 +23,8 @@ EXPORTS = [
     "mvla_destroy", "mvla_salience", "mvla_modality_budget", "mvla_select_topk", "mvla_compact",
     "mvla_prune_step", "mvla_rope_table", "mvla_prefill_layer", "mvla_score_only",
     "mvla_profile_enable", "mvla_profile_read", "mvla_kernel_name", "mvla_temporal_smooth",
-    "mvla_modality_decompose",
+    "mvla_modality_decompose", "mvla_feature_share", "mvla_mask_rules_default",
+    "mvla_candidate_masks", "mvla_mask_indices",
 ]
 
 
@@ -43,6 +44,22 @@ class LayerWeightsC(C.Structure):
     _fields_ = [("wqkv", C.c_void_p), ("wo", C.c_void_p), ("w_gateup", C.c_void_p),
                 ("w_down", C.c_void_p), ("g_attn", C.c_void_p), ("g_mlp", C.c_void_p),
                 ("rope_cos", C.c_void_p), ("rope_sin", C.c_void_p), ("rope_len", C.c_int)]
+
+
+class MaskRules(C.Structure):
+    """Constants of Algorithm 1's mask rules (mvla_mask_rules)."""
+    _fields_ = [("tau_2d", C.c_float), ("tau_3d", C.c_float), ("bg_drop", C.c_float),
+                ("obj_2d_min", C.c_float), ("obj_3d_max", C.c_float),
+                ("kmeans_max_iter", C.c_int32)]
+
+    @classmethod
+    def default(cls, **over) -> "MaskRules":
+        r = cls()
+        load().mvla_mask_rules_default(C.byref(r))
+        for k, v in over.items():
+            assert hasattr(r, k), k
+            setattr(r, k, v)
+        return r
 
 
 def load() -> C.CDLL:
@@ -77,6 +94,12 @@ def load() -> C.CDLL:
                                     i, i, i, vp, vp]
     lib.mvla_modality_decompose.argtypes = [vp, vp, i, i, i, i, i, vp, vp]
     lib.mvla_temporal_smooth.argtypes = [vp, vp, vp, sz, i, i, C.c_double]
+    lib.mvla_feature_share.argtypes = [vp, vp, i, i, i, i, vp, vp]
+    lib.mvla_mask_rules_default.argtypes = [C.POINTER(MaskRules)]
+    lib.mvla_mask_rules_default.restype = None
+    lib.mvla_candidate_masks.argtypes = [vp, vp, vp, vp, i, i, i, C.POINTER(MaskRules), vp, vp, vp,
+                                         vp]
+    lib.mvla_mask_indices.argtypes = [vp, vp, vp, i, i, i, i, vp]
     lib.mvla_profile_enable.argtypes = [vp, C.c_uint32, i]
     lib.mvla_profile_read.argtypes = [vp, i, vp, vp, vp, vp]
     lib.mvla_kernel_name.restype = C.c_char_p
@@ -209,11 +232,14 @@ class Context:
                                    S_out, D, h_out.data_ptr(), pos_out.data_ptr()), "mvla_compact")
         return h_out, pos_out
 
-    def modality_decompose(self, attn: torch.Tensor, n_patch: int):
+    def modality_decompose(self, attn: torch.Tensor, n_patch: int, out=None):
         """Per-patch (M2D, M3D) of Eqs. 5-6 from the language-query attention rows."""
         B, H, Nq, S = _dev(attn, torch.float32).shape
-        m2d = torch.empty(B, n_patch, dtype=torch.float32, device=attn.device)
-        m3d = torch.empty_like(m2d)
+        if out is None:
+            m2d = torch.empty(B, n_patch, dtype=torch.float32, device=attn.device)
+            m3d = torch.empty_like(m2d)
+        else:
+            m2d, m3d = out
         _check(load().mvla_modality_decompose(self._h, attn.data_ptr(), B, H, Nq, S, n_patch,
                                               m2d.data_ptr(), m3d.data_ptr()),
                "mvla_modality_decompose")
@@ -228,6 +254,50 @@ class Context:
         _check(load().mvla_temporal_smooth(self._h, x_t.data_ptr(), x_hat.data_ptr(), x_t.numel(),
                                            t, k, beta), "mvla_temporal_smooth")
         return x_hat
+
+    def feature_share(self, feat: torch.Tensor, n_patch: int, out=None):
+        """Per-patch (M2D, M3D) of Eq. 1 from token features [B, S, D]."""
+        B, S, D = _dev(feat, torch.bfloat16).shape
+        if out is None:
+            m2d = torch.empty(B, n_patch, dtype=torch.float32, device=feat.device)
+            m3d = torch.empty_like(m2d)
+        else:
+            m2d, m3d = out
+        _check(load().mvla_feature_share(self._h, feat.data_ptr(), B, S, D, n_patch,
+                                         m2d.data_ptr(), m3d.data_ptr()), "mvla_feature_share")
+        return m2d, m3d
+
+    def candidate_masks(self, x_hat: torch.Tensor, sal: torch.Tensor, u: torch.Tensor,
+                        n_text: int, rules: Optional[MaskRules] = None, out=None):
+        """Retention masks of Algorithm 1 from smoothed indicators [4, B, P], salience [B, 2P]
+        and uniform draws [B, P].  Returns (mask2d, mask3d, sem, kept_len)."""
+        four, B, P = _dev(x_hat, torch.float32).shape
+        assert four == 4 and _dev(sal, torch.float32).shape == (B, 2 * P)
+        assert _dev(u, torch.float32).shape == (B, P)
+        rules = rules or MaskRules.default()
+        if out is None:
+            mask2d = torch.empty(B, P, dtype=torch.uint8, device=sal.device)
+            mask3d = torch.empty_like(mask2d)
+            sem = torch.empty_like(mask2d)
+            kept_len = torch.empty(B, dtype=torch.int32, device=sal.device)
+        else:
+            mask2d, mask3d, sem, kept_len = out
+        _check(load().mvla_candidate_masks(self._h, x_hat.data_ptr(), sal.data_ptr(), u.data_ptr(),
+                                           B, P, n_text, C.byref(rules), mask2d.data_ptr(),
+                                           mask3d.data_ptr(), _ptr(sem), kept_len.data_ptr()),
+               "mvla_candidate_masks")
+        return mask2d, mask3d, sem, kept_len
+
+    def mask_indices(self, mask2d: torch.Tensor, mask3d: torch.Tensor, n_text: int, S_pad: int,
+                     out: Optional[torch.Tensor] = None):
+        B, P = _dev(mask2d, torch.uint8).shape
+        assert _dev(mask3d, torch.uint8).shape == (B, P)
+        if out is None:
+            out = torch.empty(B, S_pad, dtype=torch.int32, device=mask2d.device)
+        assert out.shape == (B, S_pad) and out.dtype == torch.int32 and out.is_contiguous()
+        _check(load().mvla_mask_indices(self._h, mask2d.data_ptr(), mask3d.data_ptr(), B, P,
+                                        n_text, S_pad, out.data_ptr()), "mvla_mask_indices")
+        return out
 
     def prune_step(self, attn, h, pos, n2, n3, n_text, k_total, min2=0, min3=0, out=None):
         B, H, Nq, S = _dev(attn, torch.float32).shape
@@ -385,3 +455,70 @@ class PrefillPlan:
             self.ctx.prefill_layer(self.cfg, self.structs[li], h, pos, y)
             h = y
         return h
+
+
+class MaskedPrefill:
+    """One episode of action iterations with the masks of Algorithm 1 (needs one 3D token per
+    2D token and p >= 1).  Each ``step`` enqueues: p layers on all tokens, the four per-patch
+    indicators, their smoothing, and for t > 1 the masks, the index scan, the gather and the
+    remaining layers.  The kept length differs per sample; rows are padded at the end up to
+    the longest sample of the step, which takes one read-back of B integers."""
+
+    def __init__(self, plan: PrefillPlan, rules: Optional[MaskRules] = None, k: int = 7,
+                 beta: float = 0.85):
+        assert plan.n2 == plan.n3 and plan.p >= 1
+        self.plan, self.rules, self.k, self.beta = plan, rules or MaskRules.default(), k, beta
+        B, P, S, D = plan.B, plan.n2, plan.S, plan.cfg.D
+        dev = plan.ctx.device
+        f32, u8, i32 = torch.float32, torch.uint8, torch.int32
+        self.P = P
+        self.x_t = torch.zeros(4, B, P, dtype=f32, device=dev)
+        self.x_hat = torch.zeros(4, B, P, dtype=f32, device=dev)
+        self.sal = torch.empty(B, 2 * P, dtype=f32, device=dev)
+        self.mask2d = torch.empty(B, P, dtype=u8, device=dev)
+        self.mask3d = torch.empty(B, P, dtype=u8, device=dev)
+        self.sem = torch.empty(B, P, dtype=u8, device=dev)
+        self.kept_len = torch.empty(B, dtype=i32, device=dev)
+        self.kept_idx = torch.empty(B * S, dtype=i32, device=dev)
+        self.pos_kept = torch.empty(B * S, dtype=i32, device=dev)
+        self.h_kept = [torch.empty(B * S * D, dtype=torch.bfloat16, device=dev) for _ in range(2)]
+
+    def step(self, t: int, x: torch.Tensor, pos: torch.Tensor, u: torch.Tensor,
+             key_bias: Optional[torch.Tensor] = None):
+        """Timestep t (1-based).  Returns (y [B, S_pad, D], lengths): row i of sample b is valid
+        for i < lengths[b]; at t == 1 nothing is pruned."""
+        pl = self.plan
+        ctx, cfg, B, P, D = pl.ctx, pl.cfg, pl.B, self.P, pl.cfg.D
+        h = x
+        for li in range(pl.p):
+            tail = pl.nt if li == pl.p - 1 else 0
+            y = pl.h_full[li & 1]
+            ctx.prefill_layer(cfg, pl.structs[li], h, pos, y, tail, key_bias,
+                              pl.probs if tail else None)
+            h = y
+        ctx.salience(pl.probs, 2 * P, out=self.sal)
+        ctx.feature_share(h, P, out=(self.x_t[0], self.x_t[1]))
+        ctx.modality_decompose(pl.probs, P, out=(self.x_t[2], self.x_t[3]))
+        ctx.temporal_smooth(self.x_t, self.x_hat, t, self.k, self.beta)
+        if t == 1:
+            for li in range(pl.p, pl.L):
+                y = pl.h_full[li & 1]
+                ctx.prefill_layer(cfg, pl.structs[li], h, pos, y)
+                h = y
+            return h, [pl.S] * B
+        ctx.candidate_masks(self.x_hat, self.sal, u, pl.nt, self.rules,
+                            out=(self.mask2d, self.mask3d, self.sem, self.kept_len))
+        lengths = self.kept_len.cpu().tolist()          # the one host read-back of the step
+        S_pad = max(lengths)
+        kept = self.kept_idx[:B * S_pad].view(B, S_pad)
+        ctx.mask_indices(self.mask2d, self.mask3d, pl.nt, S_pad, out=kept)
+        hk = self.h_kept[0][:B * S_pad * D].view(B, S_pad, D)
+        pk = self.pos_kept[:B * S_pad].view(B, S_pad)
+        ctx.compact(h, pos, kept, out=(hk, pk))
+        h = hk
+        for li in range(pl.p, pl.L):
+            y = self.h_kept[(li - pl.p + 1) & 1][:B * S_pad * D].view(B, S_pad, D)
+            ctx.prefill_layer(cfg, pl.structs[li], h, pk, y)
+            h = y
+        self.kept, self.pos_out = kept, pk
+        return h, lengths

@@ -92,7 +92,7 @@ struct Timed {
 const char* const kKernelNames[KID_COUNT] = {
     "rmsnorm", "gemm_qkv", "rope_split", "score_probs", "attention", "gemm_o", "rmsnorm_mlp",
     "gemm_gateup", "gemm_down", "salience", "budget", "select", "compact", "rope_table",
-    "prune_fused", "smooth", "decompose"};
+    "prune_fused", "smooth", "decompose", "feature_share", "candidate_masks", "mask_indices"};
 
 }  // namespace
 
@@ -299,6 +299,54 @@ int mvla_temporal_smooth(mvla_ctx* ctx, const float* x_t, float* x_hat, size_t n
     int rc;
     TIMED(ctx, KID_SMOOTH, (int)(n > 0x7fffffff ? 0x7fffffff : n),
           launch_smooth(x_t, x_hat, n, t, k, beta, ctx->stream));
+    return MVLA_OK;
+}
+
+int mvla_feature_share(mvla_ctx* ctx, const void* feat, int B, int S, int D, int n_patch,
+                       float* m2d, float* m3d) {
+    if (!ctx || !feat || !m2d || !m3d) return MVLA_EINVAL;
+    if (B <= 0 || S <= 0 || D <= 0 || D % 8 != 0 || n_patch <= 0 || 2 * (long)n_patch > S)
+        return MVLA_EINVAL;
+    int rc;
+    TIMED(ctx, KID_FEATURE_SHARE, B * n_patch,
+          launch_feature_share(static_cast<const bf16_t*>(feat), B, S, D, n_patch, m2d, m3d,
+                               ctx->stream));
+    return MVLA_OK;
+}
+
+void mvla_mask_rules_default(mvla_mask_rules* r) {
+    if (!r) return;
+    r->tau_2d = 0.08f;
+    r->tau_3d = 0.20f;
+    r->bg_drop = 0.9f;
+    r->obj_2d_min = 0.9f;
+    r->obj_3d_max = 0.01f;
+    r->kmeans_max_iter = 32;
+}
+
+int mvla_candidate_masks(mvla_ctx* ctx, const float* x_hat, const float* sal, const float* u, int B,
+                         int n_patch, int n_text, const mvla_mask_rules* rules, uint8_t* mask2d,
+                         uint8_t* mask3d, uint8_t* sem, int32_t* kept_len) {
+    if (!ctx || !x_hat || !sal || !u || !rules || !mask2d || !mask3d || !kept_len)
+        return MVLA_EINVAL;
+    if (B <= 0 || n_patch <= 0 || n_text < 0 || rules->kmeans_max_iter < 1) return MVLA_EINVAL;
+    if (!(rules->tau_2d <= rules->tau_3d) || !(rules->bg_drop >= 0.f && rules->bg_drop <= 1.f))
+        return MVLA_EINVAL;
+    if (n_patch > 16384) return MVLA_EUNSUPPORTED;   // scores and labels are staged in LDS
+    int rc;
+    TIMED(ctx, KID_CANDIDATE, B,
+          launch_candidate_masks(x_hat, sal, u, B, n_patch, n_text, *rules, mask2d, mask3d, sem,
+                                 kept_len, ctx->stream));
+    return MVLA_OK;
+}
+
+int mvla_mask_indices(mvla_ctx* ctx, const uint8_t* mask2d, const uint8_t* mask3d, int B,
+                      int n_patch, int n_text, int S_pad, int32_t* kept_idx) {
+    if (!ctx || !mask2d || !mask3d || !kept_idx) return MVLA_EINVAL;
+    if (B <= 0 || n_patch <= 0 || n_text < 0 || S_pad <= 0) return MVLA_EINVAL;
+    int rc;
+    TIMED(ctx, KID_MASK_INDEX, B,
+          launch_mask_indices(mask2d, mask3d, B, n_patch, n_text, S_pad, kept_idx, ctx->stream));
     return MVLA_OK;
 }
 

@@ -14,7 +14,8 @@ typedef uint16_t bf16_t;  // raw bf16 storage
 enum KernelId {
     KID_RMSNORM = 0, KID_GEMM_QKV, KID_ROPE_SPLIT, KID_SCORE_PROBS, KID_ATTENTION, KID_GEMM_O,
     KID_RMSNORM_MLP, KID_GEMM_GATEUP, KID_GEMM_DOWN, KID_SALIENCE, KID_BUDGET, KID_SELECT,
-    KID_COMPACT, KID_ROPE_TABLE, KID_PRUNE_FUSED, KID_SMOOTH, KID_DECOMPOSE, KID_COUNT
+    KID_COMPACT, KID_ROPE_TABLE, KID_PRUNE_FUSED, KID_SMOOTH, KID_DECOMPOSE, KID_FEATURE_SHARE,
+    KID_CANDIDATE, KID_MASK_INDEX, KID_COUNT
 };
 
 struct ProfRecord {
@@ -73,6 +74,15 @@ int launch_decompose(const float* attn, int B, int H, int Nq, int S, int n_patch
                      float* m3d, hipStream_t st);
 int launch_smooth(const float* x_t, float* x_hat, size_t n, int t, int k, double beta,
                   hipStream_t st);
+
+// mask_kernels.hip
+int launch_feature_share(const bf16_t* feat, int B, int S, int D, int n_patch, float* m2d,
+                         float* m3d, hipStream_t st);
+int launch_candidate_masks(const float* x_hat, const float* sal, const float* u, int B, int P,
+                           int n_text, const mvla_mask_rules& rules, uint8_t* mask2d,
+                           uint8_t* mask3d, uint8_t* sem, int32_t* kept_len, hipStream_t st);
+int launch_mask_indices(const uint8_t* mask2d, const uint8_t* mask3d, int B, int P, int n_text,
+                        int S_pad, int32_t* kept_idx, hipStream_t st);
 
 // layer_kernels.hip
 int launch_rmsnorm(const bf16_t* x, const bf16_t* gain, int M, int D, float eps, bf16_t* out,

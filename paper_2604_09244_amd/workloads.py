@@ -205,3 +205,45 @@ def next_timestep(w: Workload, x_prev: torch.Tensor, step: int) -> torch.Tensor:
                             dtype=torch.float32)
         x[b, idx] = fresh + mu[(idx >= w.n2).long()]
     return x.to(torch.bfloat16)
+
+
+def _beta(a: int, b: int, shape, g: torch.Generator) -> torch.Tensor:
+    """Beta(a, b) for integer a, b from sums of seeded exponentials."""
+    ea = -torch.log(torch.rand(a, *shape, generator=g).clamp_min(1e-12)).sum(0)
+    eb = -torch.log(torch.rand(b, *shape, generator=g).clamp_min(1e-12)).sum(0)
+    return ea / (ea + eb)
+
+
+def uniform_draws(w: Workload, device="cpu", B: Optional[int] = None,
+                  step: int = 0) -> torch.Tensor:
+    """The random numbers the background rule of the mask generation consumes:
+    one uniform in [0, 1) per patch, [B, n2] fp32."""
+    B = w.B if B is None else B
+    g = _gen(w.seed * 41 + 613 * step + 7, "cpu")
+    return torch.rand(B, w.n2, generator=g, dtype=torch.float32).to(device)
+
+
+def weaken_3d(w: Workload, x: torch.Tensor) -> torch.Tensor:
+    """Scale every 3D token by a per-patch log-normal factor (median 0.12,
+    sigma 0.6), so that the 3D share of a patch's feature norm spreads around
+    the ~10 % the paper's Table 1 shows instead of the 50 % of i.i.d. tokens."""
+    g = _gen(w.seed * 43 + 19, "cpu")
+    f = 0.12 * torch.exp(0.6 * torch.randn(x.shape[0], w.n3, 1, generator=g))
+    y = x.to(torch.float32).clone()
+    y[:, w.n2:w.n_vis] *= f.to(x.device)
+    return y.to(torch.bfloat16)
+
+
+def synthetic_indicators(w: Workload, device="cpu", B: Optional[int] = None,
+                         n_patch: Optional[int] = None, seed: int = 0) -> torch.Tensor:
+    """Stand-alone smoothed indicators [4, B, P] fp32 in the order
+    (M2D^S1, M3D^S1, M2D^S2, M3D^S2) for the mask-kernel tests: 3D feature
+    share ~ Beta(2,12) (mean 0.14), 2D attention share ~ Beta(4,3), orthogonal
+    3D share = (1 - 2D share) * Beta(1,4)."""
+    B = w.B if B is None else B
+    P = w.n2 if n_patch is None else n_patch
+    g = _gen(w.seed * 47 + 23 + 131 * seed, "cpu")
+    m3_s1 = _beta(2, 12, (B, P), g)
+    m2_s2 = _beta(4, 3, (B, P), g)
+    m3_s2 = (1 - m2_s2) * _beta(1, 4, (B, P), g)
+    return torch.stack([1 - m3_s1, m3_s1, m2_s2, m3_s2]).to(torch.float32).contiguous().to(device)

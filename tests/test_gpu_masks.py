@@ -1,0 +1,256 @@
+"""GPU parity of the mask generation of Algorithm 1 (feature share, candidate masks, index
+scan) through the C ABI, and of an action-iteration episode that uses the masks."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from paper_2604_09244_amd import binding as mv
+from paper_2604_09244_amd import workloads as W
+from helpers import assert_layer_close, layer_cfg, oracle_weights, to64
+
+pytestmark = pytest.mark.gpu
+f32 = np.float32
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = mv.Context(B=4, S=544, D=4096, H=32, F=11008, n_query_tail=32)
+    yield c
+    c.close()
+
+
+# ---------------------------------------------------------------------------------------------
+# Eq. 1
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("B,P,nt,D", [(1, 1, 0, 8), (2, 5, 3, 264), (1, 64, 16, 256),
+                                      (4, 256, 32, 4096), (2, 1024, 48, 4096)])
+def test_feature_share_parity(ctx, B, P, nt, D):
+    g = torch.Generator().manual_seed(B * 1000 + P)
+    x = torch.randn(B, 2 * P + nt, D, generator=g)
+    x[:, P:2 * P] *= 0.12 * torch.exp(0.6 * torch.randn(B, P, 1, generator=g))
+    if P > 1:
+        x[0, 1] = 0                                   # a patch with both rows zero
+        x[0, P + 1] = 0
+    xb = x.to(torch.bfloat16)
+    m2, m3 = ctx.feature_share(xb.cuda(), P)
+    torch.cuda.synchronize()
+    r2, r3 = O.feature_share(to64(xb), P)
+    for got, ref in ((to64(m2), r2), (to64(m3), r3)):
+        assert np.all(np.abs(got - ref) <= 1e-5 * np.abs(ref))
+    if P > 1:
+        assert m2[0, 1].item() == 0.0 and m3[0, 1].item() == 0.0
+
+
+def test_feature_share_argument_errors(ctx):
+    x = torch.zeros(1, 8, 16, dtype=torch.bfloat16, device="cuda")
+    o = torch.zeros(4, device="cuda")
+    lib = mv.load()
+    call = lambda B, S, D, P: lib.mvla_feature_share(ctx.handle, x.data_ptr(), B, S, D, P,
+                                                     o.data_ptr(), o.data_ptr())
+    assert call(1, 8, 16, 5) == -1          # 2 * n_patch > S
+    assert call(1, 8, 12, 2) == -1          # D not a multiple of 8
+    assert call(0, 8, 16, 2) == -1
+    assert lib.mvla_feature_share(ctx.handle, None, 1, 8, 16, 2, o.data_ptr(), o.data_ptr()) == -1
+
+
+# ---------------------------------------------------------------------------------------------
+# Candidate sets -> masks
+# ---------------------------------------------------------------------------------------------
+def _mask_case(ctx, x_hat, sal, u, n_text, **rule_kw):
+    """Runs both sides on the same fp32 inputs and compares everything that is an integer."""
+    rules = mv.MaskRules.default(**{{"max_iter": "kmeans_max_iter"}.get(k, k): v
+                                    for k, v in rule_kw.items()})
+    m2, m3, sem, klen = ctx.candidate_masks(x_hat.cuda(), sal.cuda(), u.cuda(), n_text, rules)
+    torch.cuda.synchronize()
+    P = x_hat.shape[2]
+    ref = O.candidate_masks(x_hat.numpy(), O.patch_score(sal.numpy(), P), u.numpy(), **rule_kw)
+    # samples on a rounding knife-edge (none with these seeds) could legitimately differ
+    assert np.all(ref["kmeans_margin"] > 1e-9)
+    assert P == 1 or np.all(ref["mu_margin"] > 1e-9)       # a single patch is its own mean
+    assert np.array_equal(sem.cpu().numpy(), ref["sem"])
+    assert np.array_equal(m2.cpu().numpy(), ref["mask2d"])
+    assert np.array_equal(m3.cpu().numpy(), ref["mask3d"])
+    want_len = ref["mask2d"].sum(1).astype(np.int64) + ref["mask3d"].sum(1) + n_text
+    assert np.array_equal(klen.cpu().numpy(), want_len)
+    return ref, (m2, m3, sem, klen)
+
+
+@pytest.mark.parametrize("B,P", [(1, 1), (2, 3), (3, 64), (4, 256), (2, 257), (2, 1024), (1, 4096),
+                                 (1, 16384)])
+def test_candidate_masks_bit_exact(ctx, B, P):
+    wl = W.WORKLOADS["single_view"]
+    x_hat = W.synthetic_indicators(wl, B=B, n_patch=P, seed=P)
+    sal = W.synthetic_salience(replace(wl, n2=P, n3=P), B=B)
+    u = W.uniform_draws(replace(wl, n2=P), B=B, step=P)
+    ref, _ = _mask_case(ctx, x_hat, sal, u, 7)
+    if P >= 256:                                       # every branch of the rules is exercised
+        assert set(np.unique(ref["sem"])) == {0, 1, 2}
+        both = ref["mask2d"] & ref["mask3d"]
+        assert both.any() and (ref["mask2d"] & ~ref["mask3d"] & 1).any()
+        assert (ref["mask3d"] & ~ref["mask2d"] & 1).any()
+
+
+@pytest.mark.parametrize("kw", [dict(max_iter=1), dict(max_iter=2), dict(bg_drop=0.0),
+                                dict(bg_drop=1.0), dict(tau_2d=0.0, tau_3d=1.0),
+                                dict(tau_2d=0.3, tau_3d=0.3), dict(obj_2d_min=0.3, obj_3d_max=0.2)])
+def test_candidate_masks_rule_constants(ctx, kw):
+    wl = W.WORKLOADS["single_view"]
+    x_hat = W.synthetic_indicators(wl, B=3, seed=11)
+    sal = W.synthetic_salience(wl, B=3)
+    u = W.uniform_draws(wl, B=3, step=5)
+    _mask_case(ctx, x_hat, sal, u, wl.nt, **kw)
+
+
+def test_candidate_masks_ties_and_degenerate_scores(ctx):
+    wl = W.WORKLOADS["single_view"]
+    B, P = 3, 256
+    x_hat = W.synthetic_indicators(wl, B=B, seed=3)
+    u = W.uniform_draws(wl, B=B, step=9)
+    sal = torch.empty(B, 2 * P)
+    sal[0] = 0.125                                     # one value only: every patch is background
+    sal[1] = W.synthetic_salience(wl, B=1, levels=2)[0]    # two distinct levels
+    sal[2] = W.synthetic_salience(wl, B=1, levels=8)[0]    # heavy ties
+    ref, _ = _mask_case(ctx, x_hat, sal, u, wl.nt)
+    assert np.all(ref["sem"][0] == 0)
+
+
+def test_candidate_masks_argument_errors(ctx):
+    lib = mv.load()
+    z = torch.zeros(64, device="cuda")
+    m = torch.zeros(64, dtype=torch.uint8, device="cuda")
+    k = torch.zeros(4, dtype=torch.int32, device="cuda")
+    import ctypes as C
+    r = mv.MaskRules.default()
+    call = lambda rules, P=4: lib.mvla_candidate_masks(
+        ctx.handle, z.data_ptr(), z.data_ptr(), z.data_ptr(), 1, P, 2, C.byref(rules),
+        m.data_ptr(), m.data_ptr(), None, k.data_ptr())
+    assert call(r) == 0
+    assert call(mv.MaskRules.default(kmeans_max_iter=0)) == -1
+    assert call(mv.MaskRules.default(tau_2d=0.5, tau_3d=0.1)) == -1
+    assert call(mv.MaskRules.default(bg_drop=1.5)) == -1
+    assert call(r, P=16385) == -4                      # beyond what one workgroup stages in LDS
+    assert lib.mvla_candidate_masks(ctx.handle, z.data_ptr(), z.data_ptr(), z.data_ptr(), 1, 4, 2,
+                                    None, m.data_ptr(), m.data_ptr(), None, k.data_ptr()) == -1
+    torch.cuda.synchronize()
+
+
+# ---------------------------------------------------------------------------------------------
+# Masks -> indices
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("B,P,nt,extra", [(1, 1, 0, 0), (2, 5, 3, 2), (4, 256, 32, 0), (3, 257, 1, 5),
+                                          (2, 4096, 64, 0)])
+def test_mask_indices_bit_exact(ctx, B, P, nt, extra):
+    r = np.random.default_rng(P)
+    m2 = (r.uniform(size=(B, P)) < 0.45).astype(np.uint8)
+    m3 = (r.uniform(size=(B, P)) < 0.2).astype(np.uint8)
+    m2[0, 0] = 1                                       # at least one kept token
+    if B > 1:
+        m2[1] = 0                                      # a sample that keeps only language tokens
+        m3[1] = 0
+    if B > 2:
+        m2[2] = 1                                      # a sample that keeps everything
+        m3[2] = 1
+    ref = O.mask_indices(m2, m3, nt)
+    S_pad = max(len(x) for x in ref) + extra
+    got = ctx.mask_indices(torch.from_numpy(m2).cuda(), torch.from_numpy(m3).cuda(), nt, S_pad)
+    torch.cuda.synchronize()
+    got = got.cpu().numpy()
+    last = 2 * P + nt - 1
+    for b in range(B):
+        n = len(ref[b])
+        assert np.array_equal(got[b, :n], ref[b])
+        assert np.all(got[b, n:] == last)
+
+
+def test_mask_indices_short_row_is_cut_not_overrun(ctx):
+    m = torch.ones(1, 8, dtype=torch.uint8, device="cuda")
+    out = torch.full((2, 6), -7, dtype=torch.int32, device="cuda")
+    ctx.mask_indices(m, m, 4, 6, out=out[:1])
+    torch.cuda.synchronize()
+    assert out[0].tolist() == [0, 1, 2, 3, 4, 5] and out[1].tolist() == [-7] * 6
+
+
+# ---------------------------------------------------------------------------------------------
+# Episode with masks
+# ---------------------------------------------------------------------------------------------
+def test_masked_episode_against_oracle(ctx):
+    """Three drifting steps at the single-view shape (3 layers, pruning after 2), B = 2.  Step 1
+    is the cold start.  At steps 2 and 3 every stage is compared with the oracle on the oracle's
+    own inputs (indicators 1e-5, masks / indices / gathered rows bit-exact, kept-token layer at
+    the layer bar on the valid rows of the padded batch), and the free-running GPU episode must
+    end up with nearly the same kept sets."""
+    wl = replace(W.WORKLOADS["action_iter"], L=3, B=2)
+    P, nt, S, D = wl.n2, wl.nt, wl.S, wl.D
+    ws_cpu = [W.layer_weights(wl, l) for l in range(wl.L)]
+    ow = [oracle_weights(w) for w in ws_cpu]
+    layers = [mv.pack_layer({k: v.cuda() for k, v in w.items()}) for w in ws_cpu]
+    plan = mv.PrefillPlan(ctx, layer_cfg(wl), layers, wl.B, wl.n2, wl.n3, nt, wl.k_total, wl.p)
+    ep = mv.MaskedPrefill(plan)
+    x, pos = W.hidden_states(wl, device="cuda")
+    x = W.weaken_3d(wl, x)
+    pos_np = pos.cpu().numpy()
+    hat_ref = None
+    for t in (1, 2, 3):
+        if t > 1:
+            x = W.next_timestep(wl, x, t)
+        kb = W.scoring_bias(wl, device="cuda", step=t)
+        u = W.uniform_draws(wl, device="cuda", step=t)
+        y, lengths = ep.step(t, x, pos, u, kb)
+        torch.cuda.synchronize()
+        ora = O.masked_prefill(to64(x), pos_np, ow, wl.H, P, nt, wl.p, t, hat_ref,
+                               u.cpu().numpy(), wl.rms_eps, wl.rope_base, kb.cpu().numpy())
+        hat_ref = ora["x_hat"]
+        print(f"[episode] t={t} oracle lengths {[len(k) for k in ora['kept']]} gpu {lengths}",
+              flush=True)
+        # --- indicators, teacher-forced on the oracle's tensors ---------------------------------
+        feat_b = torch.from_numpy(ora["feat"]).to(torch.bfloat16)
+        m2, m3 = ctx.feature_share(feat_b.cuda(), P)
+        r2, r3 = O.feature_share(to64(feat_b), P)
+        assert np.all(np.abs(to64(m3) - r3) <= 1e-5 * r3) and np.all(np.abs(to64(m2) - r2) <= 1e-5 * r2)
+        probs32 = ora["probs"].astype(f32)
+        d2, d3 = ctx.modality_decompose(torch.from_numpy(probs32).cuda(), P)
+        q2, q3 = O.modality_decompose(probs32, P)
+        assert np.all(np.abs(to64(d2) - q2) <= 1e-5 * q2 + 1e-12)
+        assert np.all(np.abs(to64(d3) - q3) <= 1e-5 * q3 + 1e-12)
+        # free-running indicators (bf16 layers underneath) stay close to the oracle's
+        drift = float(np.max(np.abs(to64(ep.x_t) - ora["x_t"])))
+        print(f"[episode] t={t} free-running indicators: max |diff| {drift:.2e}", flush=True)
+        assert drift < 5e-2
+        if t == 1:
+            assert lengths == [S, S] and y.shape == (wl.B, S, D)
+            assert torch.equal(ep.x_hat, ep.x_t)
+            continue
+        # --- masks and indices from the oracle's fp32 state -------------------------------------
+        xh32 = torch.from_numpy(ora["x_hat"].astype(f32))
+        sal32 = torch.from_numpy(ora["sal"])
+        ref, (g2, g3, _, klen) = _mask_case(ctx, xh32, sal32, u.cpu(), nt)
+        assert np.array_equal(ref["mask2d"], ora["masks"]["mask2d"])
+        S_pad = int(klen.max().item())
+        kept = ctx.mask_indices(g2, g3, nt, S_pad)
+        hk, pk = ctx.compact(feat_b.cuda(), pos, kept)
+        torch.cuda.synchronize()
+        for b in range(wl.B):
+            n = len(ora["kept"][b])
+            assert np.array_equal(kept[b, :n].cpu().numpy(), ora["kept"][b])
+            assert torch.equal(hk[b, :n].cpu(), feat_b[b][torch.from_numpy(ora["kept"][b]).long()])
+            assert np.array_equal(pk[b, :n].cpu().numpy(), pos_np[b][ora["kept"][b]])
+        # --- kept-token layer on the padded batch: valid rows match the ragged oracle rows ------
+        yk = torch.empty_like(hk)
+        ctx.prefill_layer(plan.cfg, plan.structs[wl.p], hk, pk, yk)
+        torch.cuda.synchronize()
+        for b in range(wl.B):
+            n = len(ora["kept"][b])
+            want, _ = O.decoder_layer(to64(hk[b, :n]), pk[b, :n].cpu().numpy(), ow[wl.p], wl.H,
+                                      wl.rms_eps, wl.rope_base)
+            assert_layer_close(yk[b, :n], want, f"masked step t={t} sample {b} ({n} of {S_pad} rows)", D)
+        # --- free-running episode: same decisions up to the bf16 noise of the layers below ------
+        for b in range(wl.B):
+            a = set(ep.kept[b, :lengths[b]].cpu().tolist())
+            o = set(ora["kept"][b].tolist())
+            jac = len(a & o) / len(a | o)
+            print(f"[episode] t={t} sample {b}: kept-set Jaccard {jac:.3f}", flush=True)
+            assert jac > 0.8
+        assert y.shape == (wl.B, max(lengths), D)
