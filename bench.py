@@ -70,6 +70,9 @@ def main():
                          "that hardware byte counters can be scaled against a known size")
     ap.add_argument("--separate-prune-calls", action="store_true",
                     help="issue the four pruning calls one by one instead of mvla_prune_step")
+    ap.add_argument("--masks", action="store_true",
+                    help="also time an action-iteration episode that prunes with the masks of "
+                         "Algorithm 1 (needs n2 == n3 and p >= 1); reported as 'masked_episode'")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this library has no multi-GPU path (batch samples are "
@@ -193,6 +196,38 @@ def main():
         run_full()
     sec_full = timed(run_full, K)
 
+    # ---- optional: episode with Algorithm 1's masks (ragged kept lengths, padded per step) -----
+    masked = None
+    if args.masks:
+        assert wl.n2 == wl.n3 and wl.p >= 1, "--masks needs one 3D token per 2D token and p >= 1"
+        ep = mv.MaskedPrefill(plan)
+        xs = W.weaken_3d(wl, x)
+        n_steps = max(wl.steps, 8)
+        us = [W.uniform_draws(wl, device=dev, step=t) for t in range(n_steps + 1)]
+        ep.step(1, xs, pos, us[0], kb)                       # cold start, fills the state
+        ep.step(2, xs, pos, us[1], kb)                       # warm-up of the masked path
+        ctx.profile_enable(None, max_records=n_steps * (wl.L * 10 + 16))
+        lens, xt = [], xs
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for t in range(2, n_steps + 1):
+            _, l = ep.step(t, xt, pos, us[t], kb)
+            lens.append(l)
+        torch.cuda.synchronize()
+        sec_masked = (time.perf_counter() - t0) / (n_steps - 1)
+        macc = defaultdict(list)
+        for name, tag, ms in ctx.profile_read():
+            macc[name].append(ms)
+        ctx.profile_enable([], 0)
+        mk = ("salience", "feature_share", "decompose", "smooth", "candidate_masks", "mask_indices",
+              "compact")
+        masked = dict(ms_per_step=sec_masked * 1e3, steps=n_steps - 1,
+                      note="instrumented (HIP events around every kernel) and includes the "
+                           "per-step read-back of the kept lengths",
+                      mean_kept_tokens=float(sum(sum(l) for l in lens)) / (len(lens) * wl.B),
+                      max_kept_tokens=max(max(l) for l in lens),
+                      mask_step_us={n: 1e3 * sum(macc[n]) / (n_steps - 1) for n in mk if n in macc})
+
     # ---- CPU oracle on a bounded sample: sample 0, whole path, all layers up to 4 --------------
     cpu = None
     if not args.no_cpu_baseline:
@@ -245,6 +280,7 @@ def main():
         "roofline_other": extra,
         "kernels": kernels,
         "cpu_baseline": cpu,
+        "masked_episode": masked,
         "paper_context": {"speedup": 2.55, "overhead_pct": 5.8,
                           "hardware": "1x A100-PCIE-40GB + Xeon Gold 6348, end-to-end action step"},
     }

@@ -487,34 +487,40 @@ int launch_compact(const bf16_t* h, const int32_t* pos, const int32_t* kept_idx,
 // Eqs. 4-6): the 3D attention vector of a patch (over the head x query rows)
 // is split into its projection on the 2D vector and the orthogonal rest; the
 // outputs are the L1 shares |a2| / (|a2|+|a3|) and |a3_ortho| / (|a2|+|a3|).
-// One workgroup handles 64 patches of one sample: 4 row-groups x 64 lanes, a
-// lane owns a patch (coalesced 256-byte row segments); pass 1 accumulates
-// <a2,a2>, <a2,a3>, |a2|, |a3|, pass 2 the L1 norm of the residual.
+// One workgroup handles 8 patches of one sample with 32 row-groups (a thread
+// owns a patch and every 32nd row; small patch groups keep the launch wide at
+// batch 1); pass 1 accumulates <a2,a2>, <a2,a3>, |a2|, |a3|, pass 2 the L1 norm
+// of the residual (second read served by the L2).
 // ---------------------------------------------------------------------------
 constexpr int DEC_THREADS = 256;
+constexpr int DEC_PP = 8;                       // patches per workgroup
+constexpr int DEC_RG = DEC_THREADS / DEC_PP;    // row groups
 
 __global__ __launch_bounds__(DEC_THREADS) void decompose_kernel(const float* __restrict__ attn,
                                                                 int R, int S, int n_patch,
                                                                 float* __restrict__ m2d,
                                                                 float* __restrict__ m3d) {
-    __shared__ float red[4][DEC_THREADS / 64][64];
-    __shared__ float coef[64];
-    const int b = blockIdx.y, p = blockIdx.x * 64 + (threadIdx.x & 63), g = threadIdx.x >> 6;
+    __shared__ float red[4][DEC_RG][DEC_PP];
+    __shared__ float coef[DEC_PP];
+    const int lp = threadIdx.x % DEC_PP, g = threadIdx.x / DEC_PP;
+    const int b = blockIdx.y, p = blockIdx.x * DEC_PP + lp;
     const bool live = p < n_patch;
     const float* base = attn + (size_t)b * R * S;
     float s22 = 0.f, s23 = 0.f, l2 = 0.f, l3 = 0.f;
-    if (live)
-        for (int r = g; r < R; r += DEC_THREADS / 64) {
+    if (live) {
+#pragma unroll 4
+        for (int r = g; r < R; r += DEC_RG) {
             const float a2 = base[(size_t)r * S + p], a3 = base[(size_t)r * S + n_patch + p];
             s22 += a2 * a2;
             s23 += a2 * a3;
             l2 += fabsf(a2);
             l3 += fabsf(a3);
         }
-    red[0][g][threadIdx.x & 63] = s22;
-    red[1][g][threadIdx.x & 63] = s23;
-    red[2][g][threadIdx.x & 63] = l2;
-    red[3][g][threadIdx.x & 63] = l3;
+    }
+    red[0][g][lp] = s22;
+    red[1][g][lp] = s23;
+    red[2][g][lp] = l2;
+    red[3][g][lp] = l3;
     __syncthreads();
     float den = 0.f, n2 = 0.f;
     if (g == 0) {
@@ -522,28 +528,27 @@ __global__ __launch_bounds__(DEC_THREADS) void decompose_kernel(const float* __r
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             t[q] = 0.f;
-#pragma unroll
-            for (int w = 0; w < DEC_THREADS / 64; ++w) t[q] += red[q][w][threadIdx.x];
+            for (int w = 0; w < DEC_RG; ++w) t[q] += red[q][w][lp];
         }
-        coef[threadIdx.x] = t[0] > 0.f ? t[1] / t[0] : 0.f;
+        coef[lp] = t[0] > 0.f ? t[1] / t[0] : 0.f;
         n2 = t[2];
         den = t[2] + t[3];
     }
     __syncthreads();
-    const float c = coef[threadIdx.x & 63];
+    const float c = coef[lp];
     float lo = 0.f;
-    if (live)
-        for (int r = g; r < R; r += DEC_THREADS / 64) {
+    if (live) {
+#pragma unroll 4
+        for (int r = g; r < R; r += DEC_RG) {
             const float a2 = base[(size_t)r * S + p], a3 = base[(size_t)r * S + n_patch + p];
             lo += fabsf(a3 - c * a2);
         }
-    __syncthreads();
-    red[0][g][threadIdx.x & 63] = lo;
+    }
+    red[0][g][lp] = lo;
     __syncthreads();
     if (g == 0 && live) {
         float t = 0.f;
-#pragma unroll
-        for (int w = 0; w < DEC_THREADS / 64; ++w) t += red[0][w][threadIdx.x];
+        for (int w = 0; w < DEC_RG; ++w) t += red[0][w][lp];
         m2d[(size_t)b * n_patch + p] = den > 0.f ? n2 / den : 0.f;
         m3d[(size_t)b * n_patch + p] = den > 0.f ? t / den : 0.f;
     }
@@ -551,8 +556,8 @@ __global__ __launch_bounds__(DEC_THREADS) void decompose_kernel(const float* __r
 
 int launch_decompose(const float* attn, int B, int H, int Nq, int S, int n_patch, float* m2d,
                      float* m3d, hipStream_t st) {
-    hipLaunchKernelGGL(decompose_kernel, dim3((n_patch + 63) / 64, B), dim3(DEC_THREADS), 0, st, attn,
-                       H * Nq, S, n_patch, m2d, m3d);
+    hipLaunchKernelGGL(decompose_kernel, dim3((n_patch + DEC_PP - 1) / DEC_PP, B), dim3(DEC_THREADS),
+                       0, st, attn, H * Nq, S, n_patch, m2d, m3d);
     MVLA_HIP_CHECK(hipGetLastError());
     return MVLA_OK;
 }
