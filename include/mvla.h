@@ -268,6 +268,32 @@ int mvla_prefill_layer(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_laye
                        const void* x, const int32_t* pos, int B, int S, void* y, int n_query_tail,
                        const float* key_bias, float* probs_out);
 
+/* The same layer with the scoring rows reduced on the fly (Sec. 3.2, Eq. 3):
+ * instead of the probabilities it writes sal[b, j], j < n_vis, as
+ * mvla_salience would from them; the [B, H, n_query_tail, S] tensor is never
+ * materialised (column sums are formed per 32-query tile in registers, then
+ * reduced over heads and tiles in a fixed order).  Differs from the two-call
+ * route only in summation order.  n_query_tail >= 1, 1 <= n_vis <= S.
+ * sal: device fp32 [B, n_vis].  Other arguments as mvla_prefill_layer. */
+int mvla_prefill_layer_salience(mvla_ctx* ctx, const mvla_layer_cfg* cfg,
+                                const mvla_layer_weights* w, const void* x, const int32_t* pos,
+                                int B, int S, void* y, int n_query_tail, const float* key_bias,
+                                int n_vis, float* sal);
+
+/* The last full-sequence layer and the whole pruning step in one call: the
+ * layer as above on S = n2 + n3 + n_text tokens with the n_text language
+ * rows as scoring queries, salience reduced on the fly, budget split and
+ * per-modality top-k (as mvla_modality_budget / mvla_select_topk), then the
+ * gather of the kept rows of the layer output y and of pos (as mvla_compact).
+ * y: device bf16 [B, S, D] (the full layer output, also an output); h_out:
+ * device bf16 [B, k_total + n_text, D], must not overlap y; pos_out, sal, k2k3,
+ * kept_idx as in mvla_prune_step. */
+int mvla_prefill_layer_prune(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weights* w,
+                             const void* x, const int32_t* pos, int B, int S, void* y, int n2, int n3,
+                             int n_text, int k_total, int min2, int min3, const float* key_bias,
+                             float* sal, int32_t* k2k3, int32_t* kept_idx, void* h_out,
+                             int32_t* pos_out);
+
 /* Scoring pass alone, for pruning before any layer has run: RMSNorm, query
  * projection of the last n_query_tail rows, key projection of all rows, RoPE,
  * causal softmax (+ key_bias).  Writes probs_out as above. */

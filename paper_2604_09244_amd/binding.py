@@ -24,7 +24,8 @@ EXPORTS = [
     "mvla_prune_step", "mvla_rope_table", "mvla_prefill_layer", "mvla_score_only",
     "mvla_profile_enable", "mvla_profile_read", "mvla_kernel_name", "mvla_temporal_smooth",
     "mvla_modality_decompose", "mvla_feature_share", "mvla_mask_rules_default",
-    "mvla_candidate_masks", "mvla_mask_indices",
+    "mvla_candidate_masks", "mvla_mask_indices", "mvla_prefill_layer_salience",
+    "mvla_prefill_layer_prune",
 ]
 
 
@@ -90,6 +91,10 @@ def load() -> C.CDLL:
     lib.mvla_rope_table.argtypes = [vp, C.c_double, i, i, vp, vp]
     lib.mvla_prefill_layer.argtypes = [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeightsC), vp, vp,
                                        i, i, vp, i, vp, vp]
+    lib.mvla_prefill_layer_salience.argtypes = [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeightsC),
+                                                vp, vp, i, i, vp, i, vp, i, vp]
+    lib.mvla_prefill_layer_prune.argtypes = [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeightsC), vp,
+                                             vp, i, i, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp]
     lib.mvla_score_only.argtypes = [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeightsC), vp, vp,
                                     i, i, i, vp, vp]
     lib.mvla_modality_decompose.argtypes = [vp, vp, i, i, i, i, i, vp, vp]
@@ -352,6 +357,47 @@ class Context:
                                          _ptr(key_bias), _ptr(probs_out)), "mvla_prefill_layer")
         return (y, probs_out) if n_query_tail > 0 else y
 
+    def prefill_layer_salience(self, cfg: LayerCfg, w: LayerWeightsC, x: torch.Tensor,
+                               pos: torch.Tensor, n_query_tail: int, n_vis: int,
+                               y: Optional[torch.Tensor] = None,
+                               key_bias: Optional[torch.Tensor] = None,
+                               sal: Optional[torch.Tensor] = None):
+        """Layer + salience of its last n_query_tail rows, without materialising the
+        probabilities.  Returns (y, sal [B, n_vis])."""
+        B, S, D = _dev(x, torch.bfloat16).shape
+        _dev(pos, torch.int32)
+        y = torch.empty_like(x) if y is None else y
+        if sal is None:
+            sal = torch.empty(B, n_vis, dtype=torch.float32, device=x.device)
+        if key_bias is not None:
+            _dev(key_bias, torch.float32)
+        _check(load().mvla_prefill_layer_salience(self._h, C.byref(cfg), C.byref(w), x.data_ptr(),
+                                                  pos.data_ptr(), B, S, y.data_ptr(), n_query_tail,
+                                                  _ptr(key_bias), n_vis, sal.data_ptr()),
+               "mvla_prefill_layer_salience")
+        return y, sal
+
+    def prefill_layer_prune(self, cfg: LayerCfg, w: LayerWeightsC, x: torch.Tensor,
+                            pos: torch.Tensor, y: torch.Tensor, n2: int, n3: int, n_text: int,
+                            k_total: int, key_bias: Optional[torch.Tensor] = None, min2: int = 0,
+                            min3: int = 0, out=None):
+        """Last full-sequence layer + salience + budget + selection + gather in one call.
+        ``out``: dict(sal, k2k3, kept_idx, h, pos) of pre-allocated tensors (as prune_step)."""
+        B, S, D = _dev(x, torch.bfloat16).shape
+        dev = x.device
+        if out is None:
+            out = dict(sal=torch.empty(B, n2 + n3, dtype=torch.float32, device=dev),
+                       k2k3=torch.empty(B, 2, dtype=torch.int32, device=dev),
+                       kept_idx=torch.empty(B, k_total + n_text, dtype=torch.int32, device=dev),
+                       h=torch.empty(B, k_total + n_text, D, dtype=torch.bfloat16, device=dev),
+                       pos=torch.empty(B, k_total + n_text, dtype=torch.int32, device=dev))
+        _check(load().mvla_prefill_layer_prune(
+            self._h, C.byref(cfg), C.byref(w), x.data_ptr(), pos.data_ptr(), B, S, y.data_ptr(), n2,
+            n3, n_text, k_total, min2, min3, _ptr(key_bias), out["sal"].data_ptr(),
+            out["k2k3"].data_ptr(), out["kept_idx"].data_ptr(), out["h"].data_ptr(),
+            out["pos"].data_ptr()), "mvla_prefill_layer_prune")
+        return out
+
     def score_only(self, cfg: LayerCfg, w: LayerWeightsC, x, pos, n_query_tail, key_bias=None,
                    probs_out=None):
         B, S, D = _dev(x, torch.bfloat16).shape
@@ -390,7 +436,7 @@ class PrefillPlan:
 
     def run(self, x: torch.Tensor, pos: torch.Tensor, key_bias: Optional[torch.Tensor] = None,
             fused_prune: bool = True, smooth_step: int = 0, smooth_k: int = 7,
-            smooth_beta: float = 0.85):
+            smooth_beta: float = 0.85, on_the_fly: bool = False):
         """Pruned prefill: p full layers, pruning step, L-p layers on kept tokens.
 
         smooth_step > 0 turns on the action-iteration smoothing of the salience: the call is
@@ -399,6 +445,23 @@ class PrefillPlan:
         ctx, cfg = self.ctx, self.cfg
         if smooth_step == 1:
             return self._cold_start(x, pos, key_bias, smooth_k, smooth_beta)
+        if on_the_fly:
+            # the pruning step rides on the last full-sequence layer; no probability tensor
+            assert self.p >= 1 and smooth_step == 0
+            h = x
+            for li in range(self.p - 1):
+                y = self.h_full[li & 1]
+                ctx.prefill_layer(cfg, self.structs[li], h, pos, y)
+                h = y
+            y = self.h_full[(self.p - 1) & 1]
+            ctx.prefill_layer_prune(cfg, self.structs[self.p - 1], h, pos, y, self.n2, self.n3,
+                                    self.nt, self.k_total, key_bias, out=self.prune)
+            h, pk = self.prune["h"], self.prune["pos"]
+            for li in range(self.p, self.L):
+                y = self.h_kept[(li - self.p + 1) & 1]
+                ctx.prefill_layer(cfg, self.structs[li], h, pk, y)
+                h = y
+            return h
         h = x
         for li in range(self.p):
             tail = self.nt if li == self.p - 1 else 0

@@ -207,7 +207,7 @@ int mvla_salience(mvla_ctx* ctx, const float* attn, int B, int H, int Nq, int S,
     int rc;
     TIMED(ctx, KID_SALIENCE, B, launch_salience(attn, B, H, Nq, S, n_vis, sal,
                                                 reinterpret_cast<float*>(ctx->scratch),
-                                                ctx->counters, ctx->stream));
+                                                ctx->counters, 0, ctx->stream));
     return MVLA_OK;
 }
 
@@ -277,7 +277,7 @@ int mvla_prune_step(mvla_ctx* ctx, const float* attn, int H, int Nq, const void*
     int rc;
     TIMED(ctx, KID_PRUNE_FUSED, B,
           launch_prune_fused(attn, B, H, Nq, S, n2, n3, n_text, k_total, min2, min3, sal, k2k3,
-                             kept_idx, reinterpret_cast<float*>(ctx->scratch), ctx->counters,
+                             kept_idx, reinterpret_cast<float*>(ctx->scratch), ctx->counters, 0,
                              ctx->stream));
     return mvla_compact(ctx, h, pos, kept_idx, B, S, k_total + n_text, D, h_out, pos_out);
 }
@@ -361,10 +361,20 @@ int mvla_rope_table(mvla_ctx* ctx, double base, int rope_len, int dh, float* cos
     return MVLA_OK;
 }
 
-int mvla_prefill_layer(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weights* w,
-                       const void* x, const int32_t* pos, int B, int S, void* y, int n_query_tail,
-                       const float* key_bias, float* probs_out) {
-    int rc = check_layer_args(ctx, cfg, w, x, pos, B, S, n_query_tail, probs_out, true);
+// What the scoring rows of a layer are reduced to when the probabilities are not wanted:
+// the salience alone, or salience + budget + selection (kept_idx != null).
+struct ScoreReduce {
+    int n2, n3, n_text, k_total, min2, min3;
+    float* sal;
+    int32_t* k2k3;
+    int32_t* kept_idx;
+};
+
+static int run_layer(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weights* w,
+                     const void* x, const int32_t* pos, int B, int S, void* y, int n_query_tail,
+                     const float* key_bias, float* probs_out, const ScoreReduce* red) {
+    int rc = check_layer_args(ctx, cfg, w, x, pos, B, S, n_query_tail,
+                              red ? red->sal : probs_out, true);
     if (rc) return rc;
     if (!y || !aligned(y, 16)) return MVLA_EINVAL;
     const int D = cfg->D, H = cfg->H, dh = cfg->dh, F = cfg->F;
@@ -383,10 +393,33 @@ int mvla_prefill_layer(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_laye
     TIMED(ctx, KID_ROPE_SPLIT, M,
           launch_rope_split(lb.qkv, pos, w->rope_cos, w->rope_sin, w->rope_len, B, S, H, dh,
                             lb.S_pad, lb.vt, st));
-    if (n_query_tail > 0) {
+    if (n_query_tail > 0 && !red) {
         TIMED(ctx, KID_SCORE_PROBS, M,
               launch_score_probs(lb.qkv, 3 * D, lb.qkv + D, 3 * D, key_bias, B, S, H, dh,
-                                 n_query_tail, probs_out, st));
+                                 n_query_tail, probs_out, 0, st));
+    } else if (n_query_tail > 0) {
+        // Column sums per 32-query tile go to the (still unused) MLP activation buffer, the
+        // row-split partials of their reduction to the attention output buffer.
+        const int n_vis = red->n2 + red->n3, tiles = (n_query_tail + 31) / 32;
+        float* colsum = reinterpret_cast<float*>(lb.act);
+        if ((size_t)B * H * tiles * n_vis * 4 > (size_t)M * F * 2 ||
+            salience_scratch_bytes(B, H, tiles, n_vis) > (size_t)M * D * 2)
+            return MVLA_ENOMEM;
+        TIMED(ctx, KID_SCORE_PROBS, M,
+              launch_score_probs(lb.qkv, 3 * D, lb.qkv + D, 3 * D, key_bias, B, S, H, dh,
+                                 n_query_tail, colsum, n_vis, st));
+        if (red->kept_idx) {
+            TIMED(ctx, KID_PRUNE_FUSED, B,
+                  launch_prune_fused(colsum, B, H, tiles, n_vis, red->n2, red->n3, red->n_text,
+                                     red->k_total, red->min2, red->min3, red->sal, red->k2k3,
+                                     red->kept_idx, reinterpret_cast<float*>(lb.attn),
+                                     ctx->counters, H * n_query_tail, st));
+        } else {
+            TIMED(ctx, KID_SALIENCE, B,
+                  launch_salience(colsum, B, H, tiles, n_vis, n_vis, red->sal,
+                                  reinterpret_cast<float*>(lb.attn), ctx->counters,
+                                  H * n_query_tail, st));
+        }
     }
     TIMED(ctx, KID_ATTENTION, M,
           launch_attention(lb.qkv, lb.qkv + D, 3 * D, lb.vt, lb.S_pad, B, S, H, dh, lb.attn, D, st));
@@ -403,6 +436,46 @@ int mvla_prefill_layer(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_laye
           launch_gemm(lb.act, F, static_cast<const bf16_t*>(w->w_down), M, D, F, y, D, lb.x1, D,
                       EPI_RES_F32_TO_BF16, GEMM_WS(ctx), st));
     return MVLA_OK;
+}
+
+int mvla_prefill_layer(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weights* w,
+                       const void* x, const int32_t* pos, int B, int S, void* y, int n_query_tail,
+                       const float* key_bias, float* probs_out) {
+    return run_layer(ctx, cfg, w, x, pos, B, S, y, n_query_tail, key_bias, probs_out, nullptr);
+}
+
+int mvla_prefill_layer_salience(mvla_ctx* ctx, const mvla_layer_cfg* cfg,
+                                const mvla_layer_weights* w, const void* x, const int32_t* pos,
+                                int B, int S, void* y, int n_query_tail, const float* key_bias,
+                                int n_vis, float* sal) {
+    if (!sal || n_query_tail <= 0 || n_vis <= 0 || n_vis > S) return MVLA_EINVAL;
+    const ScoreReduce red{n_vis, 0, 0, 0, 0, 0, sal, nullptr, nullptr};
+    return run_layer(ctx, cfg, w, x, pos, B, S, y, n_query_tail, key_bias, nullptr, &red);
+}
+
+int mvla_prefill_layer_prune(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weights* w,
+                             const void* x, const int32_t* pos, int B, int S, void* y, int n2, int n3,
+                             int n_text, int k_total, int min2, int min3, const float* key_bias,
+                             float* sal, int32_t* k2k3, int32_t* kept_idx, void* h_out,
+                             int32_t* pos_out) {
+    if (!sal || !k2k3 || !kept_idx || !h_out || !pos_out || !y) return MVLA_EINVAL;
+    if (n2 < 0 || n3 < 0 || n2 + n3 <= 0 || n_text <= 0 || (long)n2 + n3 + n_text != S)
+        return MVLA_EINVAL;
+    if (k_total < 0 || k_total > n2 + n3) return MVLA_EINVAL;
+    if (min2 < 0 || min3 < 0 || min2 > n2 || min3 > n3 || min2 + min3 > k_total)
+        return MVLA_EINVAL;
+    if (n2 > 16384 || n3 > 16384) return MVLA_EUNSUPPORTED;
+    if (!aligned(h_out, 16)) return MVLA_EINVAL;
+    if (cfg && B > 0) {   // the gathered rows must not overlap the layer output they are read from
+        const char* a = static_cast<const char*>(y);
+        const char* bb = static_cast<const char*>(h_out);
+        const size_t na = (size_t)B * S * cfg->D * 2, nb = (size_t)B * (k_total + n_text) * cfg->D * 2;
+        if (a < bb + nb && bb < a + na) return MVLA_EINVAL;
+    }
+    const ScoreReduce red{n2, n3, n_text, k_total, min2, min3, sal, k2k3, kept_idx};
+    int rc = run_layer(ctx, cfg, w, x, pos, B, S, y, n_text, key_bias, nullptr, &red);
+    if (rc) return rc;
+    return mvla_compact(ctx, y, pos, kept_idx, B, S, k_total + n_text, cfg->D, h_out, pos_out);
 }
 
 int mvla_score_only(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weights* w,
@@ -429,7 +502,7 @@ int mvla_score_only(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_w
                             lb.S_pad, nullptr, st));
     TIMED(ctx, KID_SCORE_PROBS, M,
           launch_score_probs(lb.qkv, 2 * D, lb.qkv + D, 2 * D, key_bias, B, S, H, dh,
-                             n_query_tail, probs_out, st));
+                             n_query_tail, probs_out, 0, st));
     return MVLA_OK;
 }
 

@@ -58,11 +58,12 @@ namespace mvla {
 // prune_kernels.hip
 size_t salience_scratch_bytes(int B, int H, int Nq, int n_vis);
 int launch_salience(const float* attn, int B, int H, int Nq, int S, int n_vis, float* sal,
-                    float* partial, uint32_t* counters, hipStream_t st);
+                    float* partial, uint32_t* counters, int mean_rows, hipStream_t st);
 // salience + budget + selection in one launch (same results as the three separate launches)
 int launch_prune_fused(const float* attn, int B, int H, int Nq, int S, int n2, int n3, int n_text,
                        int k_total, int min2, int min3, float* sal, int32_t* k2k3,
-                       int32_t* kept_idx, float* partial, uint32_t* counters, hipStream_t st);
+                       int32_t* kept_idx, float* partial, uint32_t* counters, int mean_rows,
+                       hipStream_t st);
 int launch_budget(const float* sal, int B, int n2, int n3, int k_total, int min2, int min3,
                   int32_t* k2k3, float* mass, hipStream_t st);
 int launch_select(const float* sal, const int32_t* k2k3, int B, int n2, int n3, int n_text,
@@ -96,8 +97,8 @@ int launch_rope_split(bf16_t* qkv, const int32_t* pos, const float* rc, const fl
                       hipStream_t st);
 // scoring probabilities of the last nq rows: probs [B,H,nq,S] fp32
 int launch_score_probs(const bf16_t* q, int q_row_stride, const bf16_t* k, int k_row_stride,
-                       const float* key_bias, int B, int S, int H, int dh, int nq, float* probs,
-                       hipStream_t st);
+                       const float* key_bias, int B, int S, int H, int dh, int nq, float* out,
+                       int colsum_n, hipStream_t st);
 
 // gemm.hip:  C[M,N] = A[M,K] * W[N,K]^T  (bf16 in, fp32 accumulate)
 // EPI_STORE: C bf16.  EPI_RES_BF16_TO_F32: C fp32 = acc + R(bf16).  EPI_RES_F32_TO_BF16:

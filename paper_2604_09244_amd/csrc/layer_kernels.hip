@@ -232,11 +232,14 @@ int launch_rope_split(bf16_t* qkv, const int32_t* pos, const float* rc, const fl
 // ---------------------------------------------------------------------------
 constexpr int SC_THREADS = 256;
 
-template <int DH>
+// COLSUM: instead of the probabilities, write for every key column j < n_out the sum of the
+// probabilities over the tile's (up to 32) queries: out[b, h, tile, j].  The salience
+// reduction then runs over H * tiles short rows and the [B,H,nq,S] tensor never exists.
+template <int DH, bool COLSUM>
 __global__ __launch_bounds__(SC_THREADS) void score_probs_kernel(
     const bf16_t* __restrict__ q, int ldq, const bf16_t* __restrict__ k, int ldk,
     const float* __restrict__ key_bias, int S, int H, int nq, float scale,
-    float* __restrict__ probs) {
+    float* __restrict__ probs, int n_out) {
     constexpr int STEPS = DH / 16;
     const int qt = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -276,6 +279,7 @@ __global__ __launch_bounds__(SC_THREADS) void score_probs_kernel(
                 acc = mfma32(qf[st], kf, acc);
             }
             const float kbias = (bias && key < S) ? bias[key] : 0.f;
+            float csum = 0.f;
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int qi = qi0 + mfma32_row(v, lane);
@@ -290,8 +294,14 @@ __global__ __launch_bounds__(SC_THREADS) void score_probs_kernel(
                     }
                 } else if (qi < nq && key < S) {
                     const float p = valid ? __expf(logit - run_m[v]) * run_l[v] : 0.f;
-                    probs[(((size_t)b * H + h) * nq + qi) * S + key] = p;
+                    if (COLSUM) csum += p;
+                    else probs[(((size_t)b * H + h) * nq + qi) * S + key] = p;
                 }
+            }
+            if (COLSUM && pass == 1) {
+                csum += __shfl_xor(csum, 32);      // the other 16 query rows of the tile
+                if (fg == 0 && key < n_out)
+                    probs[(((size_t)b * H + h) * gridDim.x + qt) * n_out + key] = csum;
             }
         }
         if (pass == 0) {
@@ -335,11 +345,11 @@ __global__ __launch_bounds__(SC_THREADS) void score_probs_kernel(
 constexpr int SCR_THREADS = 512;
 constexpr int SCR_WAVES = SCR_THREADS / 64;
 
-template <int DH, int KBW>
+template <int DH, int KBW, bool COLSUM>
 __global__ __launch_bounds__(SCR_THREADS) void score_probs_reg_kernel(
     const bf16_t* __restrict__ q, int ldq, const bf16_t* __restrict__ k, int ldk,
     const float* __restrict__ key_bias, int S, int H, int nq, float scale,
-    float* __restrict__ probs) {
+    float* __restrict__ probs, int n_out) {
     constexpr int STEPS = DH / 16;
     const int qt = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -431,7 +441,15 @@ __global__ __launch_bounds__(SCR_THREADS) void score_probs_reg_kernel(
     for (int i = 0; i < KBW; ++i) {
         const int kb = wave + SCR_WAVES * i;
         const int key = kb * 32 + fr;
-        if (kb < n_kb && key < S) {
+        if (COLSUM) {
+            float csum = 0.f;   // masked entries hold exp(-inf) = 0
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                if (qi0 + mfma32_row(v, lane) < nq) csum += lg[i][v] * run_l[v];
+            csum += __shfl_xor(csum, 32);
+            if (fg == 0 && kb < n_kb && key < n_out)
+                probs[(((size_t)b * H + h) * gridDim.x + qt) * n_out + key] = csum;
+        } else if (kb < n_kb && key < S) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int qi = qi0 + mfma32_row(v, lane);
@@ -441,15 +459,15 @@ __global__ __launch_bounds__(SCR_THREADS) void score_probs_reg_kernel(
     }
 }
 
-template <int DH>
+template <int DH, bool COLSUM>
 static bool launch_score_reg(const bf16_t* q, int ldq, const bf16_t* k, int ldk,
                              const float* key_bias, int B, int S, int H, int nq, float scale,
-                             float* probs, hipStream_t st) {
+                             float* out, int n_out, hipStream_t st) {
     dim3 grid((nq + 31) / 32, H, B);
     const int need = ((S + 31) / 32 + SCR_WAVES - 1) / SCR_WAVES;  // key blocks per wave
-#define MVLA_SCR(KBW)                                                                          \
-    hipLaunchKernelGGL((score_probs_reg_kernel<DH, KBW>), grid, dim3(SCR_THREADS), 0, st, q, ldq, \
-                       k, ldk, key_bias, S, H, nq, scale, probs)
+#define MVLA_SCR(KBW)                                                                       \
+    hipLaunchKernelGGL((score_probs_reg_kernel<DH, KBW, COLSUM>), grid, dim3(SCR_THREADS), 0, st, \
+                       q, ldq, k, ldk, key_bias, S, H, nq, scale, out, n_out)
     if (need <= 3) MVLA_SCR(3);
     else if (need <= 6) MVLA_SCR(6);
     else if (need <= 8) MVLA_SCR(8);
@@ -458,31 +476,36 @@ static bool launch_score_reg(const bf16_t* q, int ldq, const bf16_t* k, int ldk,
     return true;
 }
 
-int launch_score_probs(const bf16_t* q, int q_row_stride, const bf16_t* k, int k_row_stride,
-                       const float* key_bias, int B, int S, int H, int dh, int nq, float* probs,
-                       hipStream_t st) {
-    if (B <= 0 || nq <= 0) return MVLA_OK;
-    dim3 grid((nq + 31) / 32, H, B);
-    const float scale = 1.0f / sqrtf((float)dh);
+template <int DH, bool COLSUM>
+static void launch_score_dh(const bf16_t* q, int ldq, const bf16_t* k, int ldk,
+                            const float* key_bias, int B, int S, int H, int nq, float scale,
+                            float* out, int n_out, hipStream_t st) {
     // register-resident single pass when the row fits, else two passes
-    if (dh == 128 && launch_score_reg<128>(q, q_row_stride, k, k_row_stride, key_bias, B, S, H, nq,
-                                           scale, probs, st)) {
-        MVLA_HIP_CHECK(hipGetLastError());
-        return MVLA_OK;
-    }
-    if (dh == 64 && launch_score_reg<64>(q, q_row_stride, k, k_row_stride, key_bias, B, S, H, nq,
-                                         scale, probs, st)) {
-        MVLA_HIP_CHECK(hipGetLastError());
-        return MVLA_OK;
-    }
-    if (dh == 128)
-        hipLaunchKernelGGL(score_probs_kernel<128>, grid, dim3(SC_THREADS), 0, st, q, q_row_stride,
-                           k, k_row_stride, key_bias, S, H, nq, scale, probs);
-    else if (dh == 64)
-        hipLaunchKernelGGL(score_probs_kernel<64>, grid, dim3(SC_THREADS), 0, st, q, q_row_stride,
-                           k, k_row_stride, key_bias, S, H, nq, scale, probs);
-    else
+    if (launch_score_reg<DH, COLSUM>(q, ldq, k, ldk, key_bias, B, S, H, nq, scale, out, n_out, st))
+        return;
+    dim3 grid((nq + 31) / 32, H, B);
+    hipLaunchKernelGGL((score_probs_kernel<DH, COLSUM>), grid, dim3(SC_THREADS), 0, st, q, ldq, k,
+                       ldk, key_bias, S, H, nq, scale, out, n_out);
+}
+
+// colsum_n == 0: out = probabilities [B,H,nq,S]; colsum_n > 0: out = per-tile column sums
+// [B, H, ceil(nq/32), colsum_n] over the first colsum_n key columns.
+int launch_score_probs(const bf16_t* q, int q_row_stride, const bf16_t* k, int k_row_stride,
+                       const float* key_bias, int B, int S, int H, int dh, int nq, float* out,
+                       int colsum_n, hipStream_t st) {
+    if (B <= 0 || nq <= 0) return MVLA_OK;
+    const float scale = 1.0f / sqrtf((float)dh);
+#define MVLA_SC(DH_, CS_)                                                                       \
+    launch_score_dh<DH_, CS_>(q, q_row_stride, k, k_row_stride, key_bias, B, S, H, nq, scale, out, \
+                              colsum_n, st)
+    if (dh == 128) {
+        if (colsum_n > 0) MVLA_SC(128, true); else MVLA_SC(128, false);
+    } else if (dh == 64) {
+        if (colsum_n > 0) MVLA_SC(64, true); else MVLA_SC(64, false);
+    } else {
         return MVLA_EUNSUPPORTED;
+    }
+#undef MVLA_SC
     MVLA_HIP_CHECK(hipGetLastError());
     return MVLA_OK;
 }

@@ -177,9 +177,11 @@ size_t salience_scratch_bytes(int B, int H, int Nq, int n_vis) {
     return align_up((size_t)B * (size_t)(n_vis + 64) * (R / (2 * SAL_GROUPS) + 2) * 4, 256);
 }
 
+// mean_rows: the row count the sums are divided by; 0 means the R = H*Nq rows read.  (When the
+// rows are already sums over a tile of queries, the caller passes the original row count.)
 static int launch_salience_any(const float* attn, int B, int H, int Nq, int S, int n_vis,
                                float* sal, float* partial, uint32_t* counters,
-                               const FusedPrune* fused, hipStream_t st) {
+                               const FusedPrune* fused, int mean_rows, hipStream_t st) {
     const int R = H * Nq;
     const bool vec4 = (S % 4 == 0) && ((reinterpret_cast<uintptr_t>(attn) & 15) == 0);
     int chunks, n_split, rps;
@@ -187,7 +189,7 @@ static int launch_salience_any(const float* attn, int B, int H, int Nq, int S, i
     // counters: [0, B*chunks) chunk arrivals, then B sample arrivals (first half of the area)
     if ((long)B * chunks + B > kCounterWords / 2) return MVLA_EUNSUPPORTED;
     dim3 grid(chunks, n_split, B);
-    const float inv_rows = 1.0f / (float)R;
+    const float inv_rows = 1.0f / (float)(mean_rows > 0 ? mean_rows : R);
     FusedPrune f{};
     size_t lds = 0;
     if (fused) {
@@ -209,15 +211,18 @@ static int launch_salience_any(const float* attn, int B, int H, int Nq, int S, i
 }
 
 int launch_salience(const float* attn, int B, int H, int Nq, int S, int n_vis, float* sal,
-                    float* partial, uint32_t* counters, hipStream_t st) {
-    return launch_salience_any(attn, B, H, Nq, S, n_vis, sal, partial, counters, nullptr, st);
+                    float* partial, uint32_t* counters, int mean_rows, hipStream_t st) {
+    return launch_salience_any(attn, B, H, Nq, S, n_vis, sal, partial, counters, nullptr, mean_rows,
+                               st);
 }
 
 int launch_prune_fused(const float* attn, int B, int H, int Nq, int S, int n2, int n3, int n_text,
                        int k_total, int min2, int min3, float* sal, int32_t* k2k3,
-                       int32_t* kept_idx, float* partial, uint32_t* counters, hipStream_t st) {
+                       int32_t* kept_idx, float* partial, uint32_t* counters, int mean_rows,
+                       hipStream_t st) {
     FusedPrune f{n2, n3, n_text, k_total, min2, min3, k2k3, kept_idx, nullptr};
-    return launch_salience_any(attn, B, H, Nq, S, n2 + n3, sal, partial, counters, &f, st);
+    return launch_salience_any(attn, B, H, Nq, S, n2 + n3, sal, partial, counters, &f, mean_rows,
+                               st);
 }
 
 // ---------------------------------------------------------------------------
