@@ -70,6 +70,13 @@ def main():
                          "that hardware byte counters can be scaled against a known size")
     ap.add_argument("--separate-prune-calls", action="store_true",
                     help="issue the four pruning calls one by one instead of mvla_prune_step")
+    ap.add_argument("--materialise-probs", action="store_true",
+                    help="write the scoring probabilities to memory and reduce them in a second "
+                         "kernel (mvla_prefill_layer + mvla_prune_step) instead of the single call "
+                         "that reduces them on the fly")
+    ap.add_argument("--no-tune", action="store_true",
+                    help="let the built-in cost model choose the projection kernels' tile "
+                         "configurations instead of measuring them once at set-up")
     ap.add_argument("--masks", action="store_true",
                     help="also time an action-iteration episode that prunes with the masks of "
                          "Algorithm 1 (needs n2 == n3 and p >= 1); reported as 'masked_episode'")
@@ -105,7 +112,7 @@ def main():
     ctx = mv.Context(wl.B, wl.S, wl.D, wl.H, wl.F, wl.nt)
     cfg = mv.LayerCfg(wl.D, wl.H, wl.dh, wl.F, wl.rms_eps)
     plan = mv.PrefillPlan(ctx, cfg, layers, wl.B, wl.n2, wl.n3, wl.nt, wl.k_total, wl.p,
-                          rope_base=wl.rope_base)
+                          rope_base=wl.rope_base, tune=not args.no_tune)
     fused = not args.separate_prune_calls
     torch.cuda.synchronize()
     if args.calibrate_copy:
@@ -126,7 +133,8 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / steps
 
-    run_pruned = lambda: plan.run(x, pos, kb, fused_prune=fused)
+    otf = fused and wl.p >= 1 and not args.materialise_probs
+    run_pruned = lambda: plan.run(x, pos, kb, fused_prune=fused, on_the_fly=otf)
     run_full = lambda: plan.run_unpruned(x, pos)
 
     # ---- the timed region: K pruned prefills, nothing bracketed (an event pair around a launch
@@ -172,7 +180,8 @@ def main():
     extra = {}
     for sal_key in (("salience", wl.B), ("prune_fused", wl.B)):   # fused: + budget and selection
         if sal_key in acc:
-            b = 4.0 * wl.B * wl.H * wl.nt * wl.n_vis + 4.0 * wl.B * wl.n_vis
+            rows = (wl.nt + 31) // 32 if otf else wl.nt     # on the fly: one row per 32-query tile
+            b = 4.0 * wl.B * wl.H * rows * wl.n_vis + 4.0 * wl.B * wl.n_vis
             extra[sal_key[0]] = hbm_roofline(b, 1e-3 * sum(acc[sal_key]) / len(acc[sal_key]))
     cmp_key = ("compact", M_kept)
     if cmp_key in acc:
@@ -269,7 +278,8 @@ def main():
         "config": {"workload": wl.name, "B": wl.B, "S": wl.S, "S_kept": wl.S_kept, "n2": wl.n2,
                    "n3": wl.n3, "n_text": wl.nt, "layers": wl.L, "full_layers_before_pruning": wl.p,
                    "keep_permille": wl.keep_permille, "hidden": wl.D, "heads": wl.H, "mlp": wl.F,
-                   "fused_prune_call": fused},
+                   "fused_prune_call": fused, "scoring_reduced_on_the_fly": otf,
+                   "projection_kernels_measured_at_setup": not args.no_tune},
         "prune_step_us": prune_total_us,
         "prune_step_us_by_kernel": prune_us,
         "prune_pct_of_pruned_prefill": 100.0 * prune_total_us * 1e-6 / sec_instr,

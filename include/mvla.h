@@ -294,6 +294,23 @@ int mvla_prefill_layer_prune(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvl
                              float* sal, int32_t* k2k3, int32_t* kept_idx, void* h_out,
                              int32_t* pos_out);
 
+/* Optional set-up step: times every tile configuration / K-split policy of
+ * the four projections of a layer at M = B*S rows on this device, cycling
+ * through the n_layers weight sets so that weights come from HBM as in real
+ * use, and records the fastest per shape in the context; later layer calls at
+ * that shape use it instead of the built-in cost model.  Results of the layer
+ * calls change only in fp32 summation order.  Uses the context's workspace,
+ * runs on and SYNCHRONISES the context's stream (not for use under graph
+ * capture); takes a few tens of milliseconds.
+ * layers: HOST array of n_layers weight descriptors (device pointers inside). */
+int mvla_tune_layers(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weights* layers,
+                     int n_layers, int B, int S);
+/* The recorded choice for a projection shape: *cfg_out = configuration index
+ * or -1 when none is recorded, *split_pct_out its K-split threshold.
+ * epilogue: 0 q/k/v, 1 attention output, 2 MLP down, 3 gate/up. */
+int mvla_tuned_choice(mvla_ctx* ctx, int M, int N, int K, int epilogue, int* cfg_out,
+                      int* split_pct_out);
+
 /* Scoring pass alone, for pruning before any layer has run: RMSNorm, query
  * projection of the last n_query_tail rows, key projection of all rows, RoPE,
  * causal softmax (+ key_bias).  Writes probs_out as above. */

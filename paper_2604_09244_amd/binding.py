@@ -25,7 +25,7 @@ EXPORTS = [
     "mvla_profile_enable", "mvla_profile_read", "mvla_kernel_name", "mvla_temporal_smooth",
     "mvla_modality_decompose", "mvla_feature_share", "mvla_mask_rules_default",
     "mvla_candidate_masks", "mvla_mask_indices", "mvla_prefill_layer_salience",
-    "mvla_prefill_layer_prune",
+    "mvla_prefill_layer_prune", "mvla_tune_layers", "mvla_tuned_choice",
 ]
 
 
@@ -95,6 +95,8 @@ def load() -> C.CDLL:
                                                 vp, vp, i, i, vp, i, vp, i, vp]
     lib.mvla_prefill_layer_prune.argtypes = [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeightsC), vp,
                                              vp, i, i, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp]
+    lib.mvla_tune_layers.argtypes = [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeightsC), i, i, i]
+    lib.mvla_tuned_choice.argtypes = [vp, i, i, i, i, C.POINTER(C.c_int), C.POINTER(C.c_int)]
     lib.mvla_score_only.argtypes = [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeightsC), vp, vp,
                                     i, i, i, vp, vp]
     lib.mvla_modality_decompose.argtypes = [vp, vp, i, i, i, i, i, vp, vp]
@@ -398,6 +400,19 @@ class Context:
             out["pos"].data_ptr()), "mvla_prefill_layer_prune")
         return out
 
+    def tune_layers(self, cfg: LayerCfg, structs: Sequence[LayerWeightsC], B: int, S: int):
+        """Measure the projection kernels' tile configurations at M = B*S rows and keep the
+        fastest per shape in this context (synchronises the stream)."""
+        arr = (LayerWeightsC * len(structs))(*structs)
+        _check(load().mvla_tune_layers(self._h, C.byref(cfg), arr, len(structs), B, S),
+               "mvla_tune_layers")
+
+    def tuned_choice(self, M: int, N: int, K: int, epilogue: int):
+        c, p = C.c_int(), C.c_int()
+        _check(load().mvla_tuned_choice(self._h, M, N, K, epilogue, C.byref(c), C.byref(p)),
+               "mvla_tuned_choice")
+        return c.value, p.value
+
     def score_only(self, cfg: LayerCfg, w: LayerWeightsC, x, pos, n_query_tail, key_bias=None,
                    probs_out=None):
         B, S, D = _dev(x, torch.bfloat16).shape
@@ -415,7 +430,7 @@ class PrefillPlan:
 
     def __init__(self, ctx: Context, cfg: LayerCfg, layers: List[Dict[str, torch.Tensor]],
                  B: int, n2: int, n3: int, nt: int, k_total: int, p: int,
-                 rope_base: float = 10000.0, rope_len: Optional[int] = None):
+                 rope_base: float = 10000.0, rope_len: Optional[int] = None, tune: bool = False):
         self.ctx, self.cfg, self.B, self.n2, self.n3, self.nt = ctx, cfg, B, n2, n3, nt
         self.k_total, self.p, self.L = k_total, p, len(layers)
         self.S, self.S_kept = n2 + n3 + nt, k_total + nt
@@ -423,6 +438,10 @@ class PrefillPlan:
         self.rope = ctx.rope_table(rope_base, rope_len or self.S, cfg.dh)
         self.packed = layers
         self.structs = [ctx.layer_struct(l, self.rope) for l in layers]
+        if tune:   # measured kernel choices for the two row counts this plan runs at
+            ctx.tune_layers(cfg, self.structs, B, self.S)
+            if self.S_kept != self.S and self.S_kept > 0:
+                ctx.tune_layers(cfg, self.structs, B, self.S_kept)
         bf, i32, f32 = torch.bfloat16, torch.int32, torch.float32
         self.h_full = [torch.empty(B, self.S, cfg.D, dtype=bf, device=dev) for _ in range(2)]
         self.h_kept = [torch.empty(B, self.S_kept, cfg.D, dtype=bf, device=dev) for _ in range(2)]

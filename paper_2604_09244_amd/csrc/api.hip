@@ -64,6 +64,17 @@ int check_layer_args(const mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_
 
 #define GEMM_WS(ctx) (ctx)->gemm_partial, (ctx)->gemm_partial_bytes, (ctx)->counters + kCounterWords / 2, kCounterWords / 2
 
+// measured choice for this shape, or (-1, 0): let the cost model decide
+struct GemmPick {
+    int cfg, split_pct;
+};
+GemmPick gemm_pick(const mvla_ctx* ctx, int M, int N, int K, int epi) {
+    for (const auto& t : ctx->tuned)
+        if (t.M == M && t.N == N && t.K == K && t.epi == epi) return {t.cfg, t.split_pct};
+    return {-1, 0};
+}
+#define GEMM_PICK(ctx, M, N, K, epi) gemm_pick(ctx, M, N, K, epi).cfg, gemm_pick(ctx, M, N, K, epi).split_pct
+
 // Brackets one launch with a pair of pre-created events when its kernel id is selected.
 struct Timed {
     mvla_ctx* c;
@@ -389,7 +400,8 @@ static int run_layer(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_
     TIMED(ctx, KID_RMSNORM, M,
           launch_rmsnorm(xin, static_cast<const bf16_t*>(w->g_attn), M, D, cfg->rms_eps, lb.u, st));
     TIMED(ctx, KID_GEMM_QKV, M,
-          launch_gemm(lb.u, D, wqkv, M, 3 * D, D, lb.qkv, 3 * D, nullptr, 0, EPI_STORE, GEMM_WS(ctx), st));
+          launch_gemm(lb.u, D, wqkv, M, 3 * D, D, lb.qkv, 3 * D, nullptr, 0, EPI_STORE, GEMM_WS(ctx),
+                      GEMM_PICK(ctx, M, 3 * D, D, EPI_STORE), st));
     TIMED(ctx, KID_ROPE_SPLIT, M,
           launch_rope_split(lb.qkv, pos, w->rope_cos, w->rope_sin, w->rope_len, B, S, H, dh,
                             lb.S_pad, lb.vt, st));
@@ -425,16 +437,19 @@ static int run_layer(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_
           launch_attention(lb.qkv, lb.qkv + D, 3 * D, lb.vt, lb.S_pad, B, S, H, dh, lb.attn, D, st));
     TIMED(ctx, KID_GEMM_O, M,
           launch_gemm(lb.attn, D, static_cast<const bf16_t*>(w->wo), M, D, D, lb.x1, D, xin, D,
-                      EPI_RES_BF16_TO_F32, GEMM_WS(ctx), st));
+                      EPI_RES_BF16_TO_F32, GEMM_WS(ctx), GEMM_PICK(ctx, M, D, D, EPI_RES_BF16_TO_F32),
+                      st));
     TIMED(ctx, KID_RMSNORM_MLP, M,
           launch_rmsnorm_f32(lb.x1, static_cast<const bf16_t*>(w->g_mlp), M, D, cfg->rms_eps, lb.u,
                              st));
     TIMED(ctx, KID_GEMM_GATEUP, M,
           launch_gemm(lb.u, D, static_cast<const bf16_t*>(w->w_gateup), M, 2 * F, D, lb.act, F,
-                      nullptr, 0, EPI_SILU_MUL, GEMM_WS(ctx), st));
+                      nullptr, 0, EPI_SILU_MUL, GEMM_WS(ctx), GEMM_PICK(ctx, M, 2 * F, D, EPI_SILU_MUL),
+                      st));
     TIMED(ctx, KID_GEMM_DOWN, M,
           launch_gemm(lb.act, F, static_cast<const bf16_t*>(w->w_down), M, D, F, y, D, lb.x1, D,
-                      EPI_RES_F32_TO_BF16, GEMM_WS(ctx), st));
+                      EPI_RES_F32_TO_BF16, GEMM_WS(ctx), GEMM_PICK(ctx, M, D, F, EPI_RES_F32_TO_BF16),
+                      st));
     return MVLA_OK;
 }
 
@@ -478,6 +493,97 @@ int mvla_prefill_layer_prune(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvl
     return mvla_compact(ctx, y, pos, kept_idx, B, S, k_total + n_text, cfg->D, h_out, pos_out);
 }
 
+int mvla_tune_layers(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weights* layers,
+                     int n_layers, int B, int S) {
+    if (!ctx || !cfg || !layers || n_layers <= 0 || B <= 0 || S <= 0) return MVLA_EINVAL;
+    for (int l = 0; l < n_layers; ++l) {
+        static const int32_t dummy_pos = 0;
+        int rc = check_layer_args(ctx, cfg, &layers[l], layers[l].wqkv, &dummy_pos, B, S, 0, nullptr,
+                                  true);
+        if (rc) return rc;
+    }
+    const int D = cfg->D, F = cfg->F, M = B * S;
+    const LayerBuffers lb = layer_buffers(ctx->scratch, B, S, D, F);
+    if (lb.bytes > ctx->scratch_bytes) return MVLA_ENOMEM;
+    hipStream_t st = ctx->stream;
+    // operands of the timed launches: zeros (timing does not depend on the values)
+    MVLA_HIP_CHECK(hipMemsetAsync(lb.u, 0, (size_t)M * D * 2, st));
+    MVLA_HIP_CHECK(hipMemsetAsync(lb.attn, 0, (size_t)M * D * 2, st));
+    MVLA_HIP_CHECK(hipMemsetAsync(lb.x1, 0, (size_t)M * D * 4, st));
+    MVLA_HIP_CHECK(hipMemsetAsync(lb.act, 0, (size_t)M * F * 2, st));
+    hipEvent_t e0, e1;
+    MVLA_HIP_CHECK(hipEventCreate(&e0));
+    if (hipEventCreate(&e1) != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        return MVLA_EHIP;
+    }
+    struct Job {
+        const bf16_t* A;
+        int lda, N, K;
+        void* C;
+        int ldc;
+        const void* R;
+        int ldr, epi, which;
+    };
+    // the down projection writes into the (unused) q/k/v buffer instead of a layer output
+    const Job jobs[4] = {
+        {lb.u, D, 3 * D, D, lb.qkv, 3 * D, nullptr, 0, EPI_STORE, 0},
+        {lb.attn, D, D, D, lb.x1, D, lb.u, D, EPI_RES_BF16_TO_F32, 1},
+        {lb.u, D, 2 * F, D, lb.act, F, nullptr, 0, EPI_SILU_MUL, 2},
+        {lb.act, F, D, F, lb.qkv, D, lb.x1, D, EPI_RES_F32_TO_BF16, 3},
+    };
+    const int reps = n_layers >= 4 ? n_layers : 4;
+    static const int kSplitChoices[3] = {0, 50, 101};
+    int rc = MVLA_OK;
+    for (const Job& j : jobs) {
+        float best_ms = 0.f;
+        int best_cfg = -1, best_pct = 0;
+        for (int c = 0; c < gemm_num_configs() && rc == MVLA_OK; ++c)
+            for (int sp = 0; sp < 3 && rc == MVLA_OK; ++sp) {
+                for (int r = -1; r < reps; ++r) {   // r == -1: untimed first launch
+                    if (r == 0 && hipEventRecord(e0, st) != hipSuccess) rc = MVLA_EHIP;
+                    const mvla_layer_weights& w = layers[(r + n_layers) % n_layers];
+                    const void* wt = j.which == 0 ? w.wqkv : j.which == 1 ? w.wo
+                                     : j.which == 2 ? w.w_gateup : w.w_down;
+                    const int lrc = launch_gemm(j.A, j.lda, static_cast<const bf16_t*>(wt), M, j.N, j.K,
+                                                j.C, j.ldc, j.R, j.ldr, j.epi, GEMM_WS(ctx), c,
+                                                kSplitChoices[sp], st);
+                    if (lrc) rc = lrc;
+                }
+                float ms = 0.f;
+                if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                    hipEventElapsedTime(&ms, e0, e1) != hipSuccess)
+                    rc = MVLA_EHIP;
+                if (rc == MVLA_OK && (best_cfg < 0 || ms < best_ms)) {
+                    best_ms = ms;
+                    best_cfg = c;
+                    best_pct = kSplitChoices[sp];
+                }
+            }
+        if (rc != MVLA_OK) break;
+        bool found = false;
+        for (auto& t : ctx->tuned)
+            if (t.M == M && t.N == j.N && t.K == j.K && t.epi == j.epi) {
+                t.cfg = best_cfg;
+                t.split_pct = best_pct;
+                found = true;
+            }
+        if (!found) ctx->tuned.push_back({M, j.N, j.K, j.epi, best_cfg, best_pct});
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return rc;
+}
+
+int mvla_tuned_choice(mvla_ctx* ctx, int M, int N, int K, int epilogue, int* cfg_out,
+                      int* split_pct_out) {
+    if (!ctx || !cfg_out || !split_pct_out) return MVLA_EINVAL;
+    const GemmPick p = gemm_pick(ctx, M, N, K, epilogue);
+    *cfg_out = p.cfg;
+    *split_pct_out = p.split_pct;
+    return MVLA_OK;
+}
+
 int mvla_score_only(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weights* w,
                     const void* x, const int32_t* pos, int B, int S, int n_query_tail,
                     const float* key_bias, float* probs_out) {
@@ -496,7 +602,7 @@ int mvla_score_only(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_w
     // query and key projections only (first 2D rows of wqkv), stored with row stride 2D
     TIMED(ctx, KID_GEMM_QKV, M,
           launch_gemm(lb.u, D, static_cast<const bf16_t*>(w->wqkv), M, 2 * D, D, lb.qkv, 2 * D,
-                      nullptr, 0, EPI_STORE, GEMM_WS(ctx), st));
+                      nullptr, 0, EPI_STORE, GEMM_WS(ctx), GEMM_PICK(ctx, M, 2 * D, D, EPI_STORE), st));
     TIMED(ctx, KID_ROPE_SPLIT, M,
           launch_rope_split(lb.qkv, pos, w->rope_cos, w->rope_sin, w->rope_len, B, S, H, dh,
                             lb.S_pad, nullptr, st));

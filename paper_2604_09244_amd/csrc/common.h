@@ -39,6 +39,11 @@ struct mvla_ctx {
     size_t gemm_partial_bytes;
     char* scratch;       // everything after the fixed areas
     size_t scratch_bytes;
+    // tile configuration and K-split threshold measured fastest for a GEMM shape (mvla_tune_layers)
+    struct Tuned {
+        int M, N, K, epi, cfg, split_pct;
+    };
+    std::vector<Tuned> tuned;
 };
 
 constexpr int kCounterWords = 16384;
@@ -110,7 +115,9 @@ enum GemmEpilogue { EPI_STORE = 0, EPI_RES_BF16_TO_F32 = 1, EPI_RES_F32_TO_BF16 
 size_t gemm_partial_bytes();
 int launch_gemm(const bf16_t* A, int lda, const bf16_t* W, int M, int N, int K, void* C, int ldc,
                 const void* R, int ldr, int epilogue, float* partial, size_t partial_bytes,
-                uint32_t* counters, int n_counters, hipStream_t st);
+                uint32_t* counters, int n_counters, int force_cfg, int force_split_pct,
+                hipStream_t st);
+int gemm_num_configs();
 
 // attention.hip: causal flash attention; q,k rows inside qkv (row stride ldqkv), vt [B,H,dh,S_pad]
 int launch_attention(const bf16_t* q, const bf16_t* k, int ldqkv, const bf16_t* vt, int S_pad,

@@ -131,8 +131,6 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     constexpr int P = A_LD + B_LD;          // direct loads per thread per slab
     static_assert(BM * CPR % NT == 0 && BN * CPR % NT == 0, "tile/thread mismatch");
     static_assert(KS % 2 == 0 && NS >= 2, "");
-    // the K-split fix-up adds gate and up registers of one lane: needs both blocks in one wave
-    constexpr bool SK_OK = !(EPI == EPI_SILU_MUL && FN % 2 != 0);
 
     extern __shared__ uint4 lds[];
     __shared__ int sh_last;
@@ -276,7 +274,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
 #undef MVLA_MFMA
 
         // ---- K-split tiles: park the partial sums; the last piece to arrive finishes --------
-        const int n_pieces = (is_dp || !SK_OK) ? 1 : last_blk - first_blk + 1;
+        const int n_pieces = is_dp ? 1 : last_blk - first_blk + 1;
         if (n_pieces > 1) {
             // slot 0 of a workgroup holds the piece of the tile its range starts in, slot 1 the next
             const int my_slot = 2 * sk_id + (seg == 0 ? 0 : 1);
@@ -312,43 +310,40 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
             }
             __syncthreads();
             if (!sh_last) continue;
-            // Sum the pieces in piece order, one 32x32 block (gate and up blocks together) at a
-            // time, and send each element through the epilogue.
-            constexpr int JS2 = (EPI == EPI_SILU_MUL && SK_OK) ? 2 : 1;
+            // Sum the pieces in piece order into the accumulator registers (the own piece is read
+            // back like the others, so the order of additions never depends on who came last),
+            // a chunk of 16-byte loads in flight at a time; then the common epilogue below.
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+            constexpr int NQ = FM * FN * 4;                       // quads per thread per piece
+            // quads in flight: up to 16 when the accumulators are small, else up to 8
+            constexpr int CH_MAX = (NQ <= 16) ? 16 : 8;
+            constexpr int CH = (CH_MAX >= 16 && NQ % 16 == 0) ? 16
+                               : (CH_MAX >= 12 && NQ % 12 == 0) ? 12
+                               : (NQ % 8 == 0) ? 8 : 4;
+            static_assert(NQ % CH == 0 && CH % 4 == 0, "");
 #pragma unroll 1
-            for (int ij = 0; ij < FM * FN; ij += JS2) {
-                const int i = ij / FN, j = ij % FN;
-                f32q_t sum[JS2][4];
+            for (int pc = 0; pc < n_pieces; ++pc) {
+                const float* src = partial + (size_t)sh_slot[pc] * (BM * BN) + tid * 4;
 #pragma unroll
-                for (int h = 0; h < JS2; ++h)
+                for (int q0 = 0; q0 < NQ; q0 += CH) {
+                    f32q_t t[CH];
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) sum[h][c] = f32q_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll 1
-                for (int pc = 0; pc < n_pieces; ++pc) {
-                    const float* src = partial + (size_t)sh_slot[pc] * (BM * BN) + tid * 4;
+                    for (int q = 0; q < CH; ++q) t[q] = ld16_coherent(&src[(size_t)(q0 + q) * NT * 4]);
 #pragma unroll
-                    for (int h = 0; h < JS2; ++h) {
-                        f32q_t t0 = ld16_coherent(&src[((ij + h) * 4 + 0) * NT * 4]);
-                        f32q_t t1 = ld16_coherent(&src[((ij + h) * 4 + 1) * NT * 4]);
-                        f32q_t t2 = ld16_coherent(&src[((ij + h) * 4 + 2) * NT * 4]);
-                        f32q_t t3 = ld16_coherent(&src[((ij + h) * 4 + 3) * NT * 4]);
-                        settle(t0, t1, t2, t3);
-                        sum[h][0] += t0; sum[h][1] += t1; sum[h][2] += t2; sum[h][3] += t3;
-                    }
-                }
-                const int ncol = n0 + wn * TN + j * 32;
-                if (ncol + (JS2 - 1) * 32 + fr < N) {
+                    for (int q = 0; q < CH; q += 4) settle(t[q], t[q + 1], t[q + 2], t[q + 3]);
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int row = m0 + wm * TM + i * 32 + mfma32_row(v, lane);
-                        if (row < M)
-                            store_elem<EPI>(Cv, ldc, Rv, ldr, row,
-                                            JS2 == 2 ? (ncol >> 1) + fr : ncol + fr,
-                                            sum[0][v >> 2][v & 3], sum[JS2 - 1][v >> 2][v & 3]);
+                    for (int q = 0; q < CH; ++q) {
+                        const int blk = (q0 + q) / 4, c = (q0 + q) % 4;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[blk / FN][blk % FN][4 * c + e] += t[q][e];
                     }
                 }
             }
-            continue;
         }
 
         // ---- epilogue through LDS: the accumulator tile (lane = column, registers = rows) is
@@ -474,9 +469,8 @@ static int launch_cfg(const bf16_t* A, int lda, const bf16_t* W, int M, int N, i
                       int ldc, const void* R, int ldr, int epi, int slots_per_cu, int sk_pct,
                       float* partial,
                       size_t partial_bytes, uint32_t* counters, int n_counters, hipStream_t st) {
-    constexpr bool sk_ok = !((BN / WN / 32) % 2 != 0);   // odd wave width: no K-split for gate/up
     GemmPlan plan = make_plan(M, N, K, BM, BN, BK, kNumCUs * slots_per_cu,
-                              (epi == EPI_SILU_MUL && !sk_ok) ? 0 : sk_pct);
+                              sk_pct);
     if (plan.sk_blocks > 0) {
         const size_t need = (size_t)2 * plan.sk_blocks * BM * BN * sizeof(float);
         if (need > partial_bytes || plan.sk_tiles > n_counters) {  // no room: whole tiles only
@@ -522,7 +516,7 @@ static const TileCfg kCfgs[kNumCfgs] = {
     {256, 256, 1, 110.f},  // K-slab 64, eight waves of 128x64, two stages
     {256, 128, 1, 62.f},   // K-slab 64, eight waves of 64x64, three stages
     {128, 128, 2, 67.f},   // K-slab 64, four waves of 64x64, two stages, two workgroups per CU
-    {128, 128, 1, 37.f},   // K-slab 64, four waves of 64x64, three stages
+    {128, 128, 1, 35.f},   // K-slab 64, eight waves of 32x64, three stages
     {288, 192, 1, 128.f},  // K-slab 64, six waves of 96x96, two stages (row counts just over 2x256)
 };
 constexpr int kSplitPct = 50;        // cut the last round along K only when it is under half full
@@ -539,29 +533,39 @@ static float estimate_us(const TileCfg& c, int M, int N, int K) {
     return rounds * c.round_us * (float)K / 4096.f;
 }
 
+int gemm_num_configs() { return kNumCfgs; }
+
+// force_cfg >= 0 picks that tile configuration and force_split_pct the K-split threshold
+// (0 = never, 101 = whenever the last round is not full); force_cfg < 0 uses the cost model.
 int launch_gemm(const bf16_t* A, int lda, const bf16_t* W, int M, int N, int K, void* C, int ldc,
                 const void* R, int ldr, int epilogue, float* partial, size_t partial_bytes,
-                uint32_t* counters, int n_counters, hipStream_t st) {
+                uint32_t* counters, int n_counters, int force_cfg, int force_split_pct,
+                hipStream_t st) {
     if (M <= 0 || N <= 0) return MVLA_OK;
     if (K < 64 || K % 64 != 0 || lda % 8 != 0) return MVLA_EUNSUPPORTED;
     if (epilogue == EPI_SILU_MUL && N % 64 != 0) return MVLA_EUNSUPPORTED;
     if (N % 8 != 0 || ldc % 8 != 0 || (R && ldr % 8 != 0)) return MVLA_EUNSUPPORTED;
-    int best = 0;
-    float best_us = estimate_us(kCfgs[0], M, N, K);
-    for (int i = 1; i < kNumCfgs; ++i) {
-        const float t = estimate_us(kCfgs[i], M, N, K);
-        if (t < best_us) {
-            best_us = t;
-            best = i;
+    int best = 0, split_pct = kSplitPct;
+    if (force_cfg >= 0 && force_cfg < kNumCfgs) {
+        best = force_cfg;
+        split_pct = force_split_pct;
+    } else {
+        float best_us = estimate_us(kCfgs[0], M, N, K);
+        for (int i = 1; i < kNumCfgs; ++i) {
+            const float t = estimate_us(kCfgs[i], M, N, K);
+            if (t < best_us) {
+                best_us = t;
+                best = i;
+            }
         }
     }
-#define MVLA_ARGS A, lda, W, M, N, K, C, ldc, R, ldr, epilogue, kCfgs[best].slots_per_cu, kSplitPct, \
+#define MVLA_ARGS A, lda, W, M, N, K, C, ldc, R, ldr, epilogue, kCfgs[best].slots_per_cu, split_pct, \
                   partial, partial_bytes, counters, n_counters, st
     switch (best) {
         case 0: return launch_cfg<256, 256, 64, 2, 4, 2>(MVLA_ARGS);
         case 1: return launch_cfg<256, 128, 64, 4, 2, 3>(MVLA_ARGS);
         case 2: return launch_cfg<128, 128, 64, 2, 2, 2>(MVLA_ARGS);
-        case 3: return launch_cfg<128, 128, 64, 2, 2, 3>(MVLA_ARGS);
+        case 3: return launch_cfg<128, 128, 64, 4, 2, 3>(MVLA_ARGS);
         default: return launch_cfg<288, 192, 64, 3, 2, 2>(MVLA_ARGS);
     }
 #undef MVLA_ARGS

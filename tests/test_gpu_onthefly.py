@@ -130,3 +130,31 @@ def test_plan_on_the_fly_equals_default_route():
     if same:
         assert torch.equal(y0, y1)
     ctx.close()
+
+
+def test_measured_kernel_choices_keep_the_results():
+    """mvla_tune_layers records a tile configuration per projection shape; layer outputs with
+    the recorded choices differ from the model-chosen ones only by fp32 summation order."""
+    wl = replace(W.WORKLOADS["action_iter"], B=2)
+    ctx = mv.Context(wl.B, wl.S, wl.D, wl.H, wl.F, wl.nt)
+    ws = [mv.pack_layer(W.layer_weights(wl, l, device="cuda")) for l in range(2)]
+    rope = ctx.rope_table(wl.rope_base, wl.S, wl.dh)
+    structs = [ctx.layer_struct(w, rope) for w in ws]
+    cfg = layer_cfg(wl)
+    x, pos = W.hidden_states(wl, device="cuda")
+    M = wl.B * wl.S
+    assert ctx.tuned_choice(M, 3 * wl.D, wl.D, 0) == (-1, 0)
+    y0 = ctx.prefill_layer(cfg, structs[0], x, pos).clone()
+    ctx.tune_layers(cfg, structs, wl.B, wl.S)
+    shapes = [(3 * wl.D, wl.D, 0), (wl.D, wl.D, 1), (wl.D, wl.F, 2), (2 * wl.F, wl.D, 3)]
+    for N, K, epi in shapes:
+        c, pct = ctx.tuned_choice(M, N, K, epi)
+        print(f"[tune] M={M} N={N} K={K} epilogue {epi}: config {c}, split below {pct} %", flush=True)
+        assert 0 <= c < 8 and pct in (0, 50, 101)
+    y1 = ctx.prefill_layer(cfg, structs[0], x, pos)
+    torch.cuda.synchronize()
+    a, b = to64(y0), to64(y1)
+    scale = float(np.sqrt(np.mean(a * a)))
+    assert np.max(np.abs(a - b)) <= 2e-2 * scale          # a bf16 rounding step at most
+    assert np.mean(a != b) < 0.05
+    ctx.close()
