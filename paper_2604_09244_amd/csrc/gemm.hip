@@ -310,37 +310,82 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
             }
             __syncthreads();
             if (!sh_last) continue;
-            // Sum the pieces in piece order into the accumulator registers (the own piece is read
-            // back like the others, so the order of additions never depends on who came last),
-            // a chunk of 16-byte loads in flight at a time; then the common epilogue below.
-#pragma unroll
-            for (int i = 0; i < FM; ++i)
-#pragma unroll
-                for (int j = 0; j < FN; ++j)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+            // Sum the pieces in piece order (so the order of additions never depends on who came
+            // last), several 16-byte loads in flight at a time; then the common epilogue below.
+            // With few accumulator registers the own piece is taken from a register copy instead
+            // of being read back, and two pieces are fetched per round trip.
             constexpr int NQ = FM * FN * 4;                       // quads per thread per piece
-            // quads in flight: up to 16 when the accumulators are small, else up to 8
-            constexpr int CH_MAX = (NQ <= 16) ? 16 : 8;
+            constexpr bool KEEP_OWN = NQ <= 16;
+            constexpr int CH_MAX = (NQ <= 16) ? 16 : 8;           // quads in flight
             constexpr int CH = (CH_MAX >= 16 && NQ % 16 == 0) ? 16
                                : (CH_MAX >= 12 && NQ % 12 == 0) ? 12
                                : (NQ % 8 == 0) ? 8 : 4;
             static_assert(NQ % CH == 0 && CH % 4 == 0, "");
+            constexpr int PPR = (KEEP_OWN && 2 * NQ <= 16) ? 2 : 1;   // pieces per round trip
+            f32x16_t own[KEEP_OWN ? FM : 1][KEEP_OWN ? FN : 1];
+            const int my_piece = KEEP_OWN ? (int)blockIdx.x - plan.dp_grid - first_blk : -1;
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j) {
+                    if (KEEP_OWN) own[i][j] = acc[i][j];
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+                }
 #pragma unroll 1
-            for (int pc = 0; pc < n_pieces; ++pc) {
-                const float* src = partial + (size_t)sh_slot[pc] * (BM * BN) + tid * 4;
+            for (int pc = 0; pc < n_pieces; pc += PPR) {
+                if (PPR == 2) {
+                    // both pieces of the pair in flight together (own piece: no load)
+                    f32q_t t[2][NQ];
+                    const int p1 = min(pc + 1, n_pieces - 1);
+                    const float* s0 = partial + (size_t)sh_slot[pc] * (BM * BN) + tid * 4;
+                    const float* s1 = partial + (size_t)sh_slot[p1] * (BM * BN) + tid * 4;
+                    if (pc != my_piece)
 #pragma unroll
-                for (int q0 = 0; q0 < NQ; q0 += CH) {
-                    f32q_t t[CH];
+                        for (int q = 0; q < NQ; ++q) t[0][q] = ld16_coherent(&s0[(size_t)q * NT * 4]);
+                    if (pc + 1 < n_pieces && pc + 1 != my_piece)
 #pragma unroll
-                    for (int q = 0; q < CH; ++q) t[q] = ld16_coherent(&src[(size_t)(q0 + q) * NT * 4]);
+                        for (int q = 0; q < NQ; ++q) t[1][q] = ld16_coherent(&s1[(size_t)q * NT * 4]);
 #pragma unroll
-                    for (int q = 0; q < CH; q += 4) settle(t[q], t[q + 1], t[q + 2], t[q + 3]);
+                    for (int h = 0; h < 2; ++h)
 #pragma unroll
-                    for (int q = 0; q < CH; ++q) {
-                        const int blk = (q0 + q) / 4, c = (q0 + q) % 4;
+                        for (int q = 0; q < NQ; q += 4) settle(t[h][q], t[h][q + 1], t[h][q + 2], t[h][q + 3]);
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) acc[blk / FN][blk % FN][4 * c + e] += t[q][e];
+                    for (int h = 0; h < 2; ++h) {
+                        if (pc + h >= n_pieces) break;
+                        const bool mine = (pc + h == my_piece);
+#pragma unroll
+                        for (int q = 0; q < NQ; ++q) {
+                            const int blk = q / 4, c = q % 4;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                acc[blk / FN][blk % FN][4 * c + e] +=
+                                    mine ? own[KEEP_OWN ? blk / FN : 0][KEEP_OWN ? blk % FN : 0][4 * c + e]
+                                         : t[h][q][e];
+                        }
+                    }
+                } else {
+                    const bool mine = (pc == my_piece);
+                    const float* src = partial + (size_t)sh_slot[pc] * (BM * BN) + tid * 4;
+#pragma unroll
+                    for (int q0 = 0; q0 < NQ; q0 += CH) {
+                        f32q_t t[CH];
+                        if (!mine) {
+#pragma unroll
+                            for (int q = 0; q < CH; ++q)
+                                t[q] = ld16_coherent(&src[(size_t)(q0 + q) * NT * 4]);
+                        }
+#pragma unroll
+                        for (int q = 0; q < CH; q += 4) settle(t[q], t[q + 1], t[q + 2], t[q + 3]);
+#pragma unroll
+                        for (int q = 0; q < CH; ++q) {
+                            const int blk = (q0 + q) / 4, c = (q0 + q) % 4;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                acc[blk / FN][blk % FN][4 * c + e] +=
+                                    mine ? own[KEEP_OWN ? blk / FN : 0][KEEP_OWN ? blk % FN : 0][4 * c + e]
+                                         : t[q][e];
+                        }
                     }
                 }
             }
