@@ -29,7 +29,7 @@ if ROOT not in sys.path:
 # plain copy of known size (see profiles/single_view_gemm_gateup_hbm_traffic.txt).  Valid only
 # for the GEMM source the counters were taken with: keyed by kernel shape and a hash of gemm.hip.
 MEASURED_TRAFFIC = {
-    ("gemm_gateup", 544, 22016, 4096): (232.8e6, "fba67ffa73d6fd87"),
+    ("gemm_gateup", 544, 22016, 4096): (232.8e6, "fd3862c1a8a70ac1"),
 }
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA

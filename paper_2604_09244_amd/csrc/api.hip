@@ -532,7 +532,7 @@ int mvla_tune_layers(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_
         {lb.u, D, 2 * F, D, lb.act, F, nullptr, 0, EPI_SILU_MUL, 2},
         {lb.act, F, D, F, lb.qkv, D, lb.x1, D, EPI_RES_F32_TO_BF16, 3},
     };
-    const int reps = n_layers >= 4 ? n_layers : 4;
+    const int reps = n_layers < 4 ? 4 : (n_layers > 8 ? 8 : n_layers);
     static const int kSplitChoices[3] = {0, 50, 101};
     int rc = MVLA_OK;
     for (const Job& j : jobs) {
