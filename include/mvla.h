@@ -305,6 +305,12 @@ int mvla_prefill_layer_prune(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvl
  * layers: HOST array of n_layers weight descriptors (device pointers inside). */
 int mvla_tune_layers(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weights* layers,
                      int n_layers, int B, int S);
+/* Record a choice by hand (e.g. one measured in an earlier run, for identical
+ * summation order across runs): configuration index 0 .. 4 (256x256, 256x128,
+ * 128x128 two per CU, 128x128 on eight waves, 288x192) and the K-split
+ * threshold in percent (0 never, 101 whenever the last round of tiles is not
+ * full); cfg < 0 removes the record.  Host-side only, nothing is launched. */
+int mvla_set_gemm_choice(mvla_ctx* ctx, int M, int N, int K, int epilogue, int cfg, int split_pct);
 /* The recorded choice for a projection shape: *cfg_out = configuration index
  * or -1 when none is recorded, *split_pct_out its K-split threshold.
  * epilogue: 0 q/k/v, 1 attention output, 2 MLP down, 3 gate/up. */

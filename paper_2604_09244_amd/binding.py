@@ -26,6 +26,7 @@ EXPORTS = [
     "mvla_modality_decompose", "mvla_feature_share", "mvla_mask_rules_default",
     "mvla_candidate_masks", "mvla_mask_indices", "mvla_prefill_layer_salience",
     "mvla_prefill_layer_prune", "mvla_tune_layers", "mvla_tuned_choice",
+    "mvla_set_gemm_choice",
 ]
 
 
@@ -96,6 +97,7 @@ def load() -> C.CDLL:
     lib.mvla_prefill_layer_prune.argtypes = [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeightsC), vp,
                                              vp, i, i, vp, i, i, i, i, i, i, vp, vp, vp, vp, vp, vp]
     lib.mvla_tune_layers.argtypes = [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeightsC), i, i, i]
+    lib.mvla_set_gemm_choice.argtypes = [vp, i, i, i, i, i, i]
     lib.mvla_tuned_choice.argtypes = [vp, i, i, i, i, C.POINTER(C.c_int), C.POINTER(C.c_int)]
     lib.mvla_score_only.argtypes = [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeightsC), vp, vp,
                                     i, i, i, vp, vp]
@@ -406,6 +408,10 @@ class Context:
         arr = (LayerWeightsC * len(structs))(*structs)
         _check(load().mvla_tune_layers(self._h, C.byref(cfg), arr, len(structs), B, S),
                "mvla_tune_layers")
+
+    def set_gemm_choice(self, M: int, N: int, K: int, epilogue: int, cfg: int, split_pct: int = 50):
+        _check(load().mvla_set_gemm_choice(self._h, M, N, K, epilogue, cfg, split_pct),
+               "mvla_set_gemm_choice")
 
     def tuned_choice(self, M: int, N: int, K: int, epilogue: int):
         c, p = C.c_int(), C.c_int()

@@ -575,6 +575,25 @@ int mvla_tune_layers(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_
     return rc;
 }
 
+int mvla_set_gemm_choice(mvla_ctx* ctx, int M, int N, int K, int epilogue, int cfg, int split_pct) {
+    if (!ctx || M <= 0 || N <= 0 || K <= 0 || epilogue < 0 || epilogue > 3) return MVLA_EINVAL;
+    if (cfg >= gemm_num_configs() || split_pct < 0 || split_pct > 101) return MVLA_EINVAL;
+    for (size_t i = 0; i < ctx->tuned.size(); ++i) {
+        auto& t = ctx->tuned[i];
+        if (t.M == M && t.N == N && t.K == K && t.epi == epilogue) {
+            if (cfg < 0) {
+                ctx->tuned.erase(ctx->tuned.begin() + (long)i);
+            } else {
+                t.cfg = cfg;
+                t.split_pct = split_pct;
+            }
+            return MVLA_OK;
+        }
+    }
+    if (cfg >= 0) ctx->tuned.push_back({M, N, K, epilogue, cfg, split_pct});
+    return MVLA_OK;
+}
+
 int mvla_tuned_choice(mvla_ctx* ctx, int M, int N, int K, int epilogue, int* cfg_out,
                       int* split_pct_out) {
     if (!ctx || !cfg_out || !split_pct_out) return MVLA_EINVAL;

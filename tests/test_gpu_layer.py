@@ -281,3 +281,30 @@ def test_action_iteration_sequence(ctx):
             assert np.array_equal(kept.cpu().numpy(), ora["kept_idx"])
             overlaps.append(len(set(kept_gpu[0]) & set(ora["kept_idx"][0])) / wl.S_kept)
     assert min(overlaps) > 0.9, overlaps
+
+
+@pytest.mark.parametrize("cfg_id", range(5))
+@pytest.mark.parametrize("split_pct", [0, 101])
+def test_every_projection_kernel_configuration(ctx, cfg_id, split_pct):
+    """Each tile configuration, with and without the K-split, forced for all four projections of
+    a layer at the single-view shapes (S = 544 and the ragged S' = 237): against the oracle
+    layer at the layer bar."""
+    wl = W.WORKLOADS["single_view"]
+    w_cpu = W.layer_weights(wl, 1)
+    packed, struct = device_layer(ctx, wl, w_cpu)
+    ow = oracle_weights(w_cpu)
+    x, pos = W.hidden_states(wl, device="cuda")
+    shapes = [(3 * wl.D, wl.D, 0), (wl.D, wl.D, 1), (wl.D, wl.F, 2), (2 * wl.F, wl.D, 3)]
+    for S in (wl.S, wl.S_kept):
+        M = wl.B * S
+        xs, ps = x[:, :S].contiguous(), pos[:, :S].contiguous()
+        for N, K, epi in shapes:
+            ctx.set_gemm_choice(M, N, K, epi, cfg_id, split_pct)
+        y = ctx.prefill_layer(layer_cfg(wl), struct, xs, ps)
+        torch.cuda.synchronize()
+        for N, K, epi in shapes:
+            assert ctx.tuned_choice(M, N, K, epi) == (cfg_id, split_pct)
+            ctx.set_gemm_choice(M, N, K, epi, -1, 0)          # back to the cost model
+            assert ctx.tuned_choice(M, N, K, epi) == (-1, 0)
+        ref, _ = O.decoder_layer(to64(xs[0]), ps[0].cpu().numpy(), ow, wl.H, wl.rms_eps, wl.rope_base)
+        assert_layer_close(y[0], ref, f"config {cfg_id} split {split_pct} S={S}", wl.D)

@@ -26,7 +26,7 @@ def _setup(name, B, layer=0):
 
 
 @pytest.mark.parametrize("name,B", [("tiny", 1), ("single_view", 1), ("action_iter", 4),
-                                    ("multi_view", 2), ("ratio_sweep", 1)])
+                                    ("multi_view", 8), ("ratio_sweep", 16)])    # full launch shapes
 def test_layer_salience_equals_two_call_route(name, B):
     """Same layer output bit for bit; salience equal to mvla_salience of the written
     probabilities up to summation order (1e-5 relative)."""
