@@ -315,7 +315,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
             // With few accumulator registers the own piece is taken from a register copy instead
             // of being read back, and two pieces are fetched per round trip.
             constexpr int NQ = FM * FN * 4;                       // quads per thread per piece
-            constexpr bool KEEP_OWN = NQ <= 16;
+            // (not for the shape that runs two workgroups per CU: the copy would cost it that)
+            constexpr bool KEEP_OWN = NQ <= 16 && !(NS == 2 && BM == 128 && BN == 128);
             constexpr int CH_MAX = (NQ <= 16) ? 16 : 8;           // quads in flight
             constexpr int CH = (CH_MAX >= 16 && NQ % 16 == 0) ? 16
                                : (CH_MAX >= 12 && NQ % 12 == 0) ? 12

@@ -367,6 +367,31 @@ __global__ __launch_bounds__(SCR_THREADS) void score_probs_reg_kernel(
     const float* bias = key_bias ? key_bias + (size_t)b * S : nullptr;
 
     f32x16_t lg[KBW];
+    // key fragments of block i+1 are requested before the products of block i are issued
+    // (rows past the end are clamped: loaded, never used)
+    uint4 kf[2][STEPS];
+    {
+        const bf16_t* ksrc = kbase + (size_t)min(wave * 32 + fr, S - 1) * ldk;
+#pragma unroll
+        for (int st = 0; st < STEPS; ++st) kf[0][st] = *reinterpret_cast<const uint4*>(ksrc + st * 16);
+    }
+#pragma unroll
+    for (int i = 0; i < KBW; ++i) {
+        const int kb = wave + SCR_WAVES * i;
+        const int key = kb * 32 + fr;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) lg[i][v] = 0.f;
+        if (i + 1 < KBW) {
+            const bf16_t* nsrc = kbase + (size_t)min(key + SCR_WAVES * 32, S - 1) * ldk;
+#pragma unroll
+            for (int st = 0; st < STEPS; ++st)
+                kf[(i + 1) & 1][st] = *reinterpret_cast<const uint4*>(nsrc + st * 16);
+        }
+        if (kb < n_kb) {   // wave-uniform
+#pragma unroll
+            for (int st = 0; st < STEPS; ++st) lg[i] = mfma32(qf[st], kf[i & 1][st], lg[i]);
+        }
+    }
     float run_m[16];
 #pragma unroll
     for (int v = 0; v < 16; ++v) run_m[v] = -INFINITY;
@@ -374,17 +399,6 @@ __global__ __launch_bounds__(SCR_THREADS) void score_probs_reg_kernel(
     for (int i = 0; i < KBW; ++i) {
         const int kb = wave + SCR_WAVES * i;
         const int key = kb * 32 + fr;
-        const int kr = min(key, S - 1);
-#pragma unroll
-        for (int v = 0; v < 16; ++v) lg[i][v] = 0.f;
-        if (kb < n_kb) {   // wave-uniform
-            const bf16_t* ksrc = kbase + (size_t)kr * ldk;
-#pragma unroll
-            for (int st = 0; st < STEPS; ++st) {
-                const uint4 kf = *reinterpret_cast<const uint4*>(ksrc + st * 16);
-                lg[i] = mfma32(qf[st], kf, lg[i]);
-            }
-        }
         const float kbias = (bias && key < S) ? bias[key] : 0.f;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {

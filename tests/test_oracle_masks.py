@@ -132,8 +132,8 @@ def test_kmeans_degenerate_inputs_and_tie_rule():
 # Candidate sets, fusion, masks: a rule table worked out by hand from Algorithm 1
 # ---------------------------------------------------------------------------------------------
 # columns: score, M3D^S1, M2D^S2, M3D^S2, u, expected sem, expected (mask2d, mask3d)
-# baselines from the table itself: mean M2D^S2 = 0.5375 (between 0.2 and 0.8),
-# mean M3D^S2 = 0.0804 (between 0.05 and 0.3).
+# baselines from the table itself: mean M2D^S2 = 0.538 (between 0.2 and 0.8),
+# mean M3D^S2 = 0.078 (between 0.05 and 0.3).
 _RULES = [
     # background (score ~ 0): dropped when u < 0.9, otherwise both modalities proposed
     (0.00, 0.15, 0.10, 0.10, 0.50, 0, (0, 0)),
