@@ -183,6 +183,11 @@ def main():
             rows = (wl.nt + 31) // 32 if otf else wl.nt     # on the fly: one row per 32-query tile
             b = 4.0 * wl.B * wl.H * rows * wl.n_vis + 4.0 * wl.B * wl.n_vis
             extra[sal_key[0]] = hbm_roofline(b, 1e-3 * sum(acc[sal_key]) / len(acc[sal_key]))
+    sc_key = ("score_probs", M_full)
+    if sc_key in acc:   # reads every key row once and the query rows, writes sums or probabilities
+        out_b = 4.0 * wl.B * wl.H * (((wl.nt + 31) // 32) * wl.n_vis if otf else wl.nt * wl.S)
+        b = 2.0 * wl.B * wl.S * wl.D + 2.0 * wl.B * wl.nt * wl.D + out_b
+        extra["score_probs"] = hbm_roofline(b, 1e-3 * sum(acc[sc_key]) / len(acc[sc_key]))
     cmp_key = ("compact", M_kept)
     if cmp_key in acc:
         b = 2.0 * M_kept * wl.D * 2 + 12.0 * M_kept

@@ -266,18 +266,29 @@ __global__ __launch_bounds__(SC_THREADS) void score_probs_kernel(
     __shared__ float sh_m[SC_THREADS / 64][32], sh_l[SC_THREADS / 64][32];
 
     for (int pass = 0; pass < 2; ++pass) {
+        // the key fragments of the wave's next block are requested before this block's products
+        // (rows past the end are clamped: loaded, never used)
+        uint4 kf[STEPS], kn[STEPS];
+        {
+            const bf16_t* ksrc = kbase + (size_t)min(wave * 32 + fr, S - 1) * ldk;
+#pragma unroll
+            for (int st = 0; st < STEPS; ++st) kn[st] = *reinterpret_cast<const uint4*>(ksrc + st * 16);
+        }
         for (int kb = wave; kb < n_kb; kb += SC_THREADS / 64) {
             const int key = kb * 32 + fr;  // this lane's key column
-            const int kr = min(key, S - 1);
+#pragma unroll
+            for (int st = 0; st < STEPS; ++st) kf[st] = kn[st];
+            {
+                const bf16_t* nsrc = kbase + (size_t)min(key + (SC_THREADS / 64) * 32, S - 1) * ldk;
+#pragma unroll
+                for (int st = 0; st < STEPS; ++st)
+                    kn[st] = *reinterpret_cast<const uint4*>(nsrc + st * 16);
+            }
             f32x16_t acc;
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[v] = 0.f;
-            const bf16_t* ksrc = kbase + (size_t)kr * ldk;
 #pragma unroll
-            for (int st = 0; st < STEPS; ++st) {
-                const uint4 kf = *reinterpret_cast<const uint4*>(ksrc + st * 16);
-                acc = mfma32(qf[st], kf, acc);
-            }
+            for (int st = 0; st < STEPS; ++st) acc = mfma32(qf[st], kf[st], acc);
             const float kbias = (bias && key < S) ? bias[key] : 0.f;
             float csum = 0.f;
 #pragma unroll
