@@ -29,7 +29,7 @@ if ROOT not in sys.path:
 # plain copy of known size (see profiles/single_view_gemm_gateup_hbm_traffic.txt).  Valid only
 # for the GEMM source the counters were taken with: keyed by kernel shape and a hash of gemm.hip.
 MEASURED_TRAFFIC = {
-    ("gemm_gateup", 544, 22016, 4096): (232.8e6, "fd3862c1a8a70ac1"),
+    ("gemm_gateup", 544, 22016, 4096): (232.8e6, "45b965ba7f30d12c"),
 }
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
@@ -59,8 +59,9 @@ def hbm_roofline(bytes_, seconds):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=None,
+                    help="timed steps (default: 200 for the 4-layer workloads, 5 for the 32-layer ones)")
+    ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="single_view")
     ap.add_argument("--keep", type=int, default=None, help="keep ratio in permille")
     ap.add_argument("--layers", type=int, default=None, help="override layer count (not the headline)")
@@ -102,7 +103,9 @@ def main():
         wl = W.with_keep(wl, args.keep)
     if args.layers is not None:
         wl = replace(wl, L=args.layers)
-    K, Wm = args.steps, args.warmup
+    small = wl.L * wl.B * wl.S < 20000
+    K = args.steps if args.steps is not None else (200 if small else 5)
+    Wm = args.warmup if args.warmup is not None else (20 if small else 2)
     M_full, M_kept = wl.B * wl.S, wl.B * wl.S_kept
 
     # ---- inputs, resident in HBM ------------------------------------------------------------
