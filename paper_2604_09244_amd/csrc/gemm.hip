@@ -24,8 +24,11 @@
 // Epilogues: plain bf16 store; residual add (bf16 residual in, fp32 out -- or
 // fp32 residual in, bf16 out: the residual stream between the two halves of a
 // layer stays in fp32, so it is rounded to bf16 once per layer); SiLU(gate)*up,
-// where gate and up columns alternate in blocks of 32 so that both sit in the
-// same lane.
+// where gate and up columns alternate in blocks of 32 (one 64-column group holds a
+// gate block and its up block).  Every epilogue lays the accumulator tile down in
+// LDS as fp32 rows first, so residual reads and result stores are 16 bytes per
+// lane on whole cache lines; K-split tiles take the same route after the pieces
+// are summed.
 #include "common.h"
 #include "mfma.h"
 
@@ -96,25 +99,6 @@ __device__ __forceinline__ void tile_of(int lin, int tiles_m, int tiles_n, int* 
     const int gm = min(GROUP_M, tiles_m - g * GROUP_M);
     *tm = g * GROUP_M + r % gm;
     *tn = r / gm;
-}
-
-// One output element through the epilogue.  For EPI_SILU_MUL, `val` is the gate and `up`
-// its partner; `col` is then the output column in the [M, N/2] result.
-template <int EPI>
-__device__ __forceinline__ void store_elem(void* Cv, int ldc, const void* Rv, int ldr, int row,
-                                           int col, float val, float up) {
-    if (EPI == EPI_SILU_MUL) {
-        const float s = val / (1.f + __expf(-val));
-        static_cast<bf16_t*>(Cv)[(size_t)row * ldc + col] = f32_to_bf16(s * up);
-    } else if (EPI == EPI_RES_BF16_TO_F32) {
-        static_cast<float*>(Cv)[(size_t)row * ldc + col] =
-            val + bf16_to_f32(static_cast<const bf16_t*>(Rv)[(size_t)row * ldr + col]);
-    } else if (EPI == EPI_RES_F32_TO_BF16) {
-        static_cast<bf16_t*>(Cv)[(size_t)row * ldc + col] =
-            f32_to_bf16(val + static_cast<const float*>(Rv)[(size_t)row * ldr + col]);
-    } else {
-        static_cast<bf16_t*>(Cv)[(size_t)row * ldc + col] = f32_to_bf16(val);
-    }
 }
 
 template <int BM, int BN, int BK, int WM, int WN, int NS, int EPI>
