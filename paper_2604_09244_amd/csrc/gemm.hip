@@ -101,6 +101,19 @@ __device__ __forceinline__ void tile_of(int lin, int tiles_m, int tiles_n, int* 
     *tn = r / gm;
 }
 
+// Epilogue staging: the output tile goes through LDS as fp32 rows of BN + 4 floats (the 4 keep
+// 16-byte accesses of 32 consecutive rows on different banks), RP rows per pass.  The whole tile
+// in one pass if the LDS a workgroup may use holds it, else one wave row per pass.
+template <int BM, int BN, int WM, int NS>
+struct EpiGeom {
+    static constexpr int LDT = BN + 4;
+    static constexpr int CAP = (NS == 2 && BM == 128 && BN == 128) ? 76 * 1024 : 156 * 1024;
+    static constexpr int PASSES = BM * LDT * 4 <= CAP ? 1 : WM;
+    static constexpr int RP = BM / PASSES;
+    static constexpr int BYTES = RP * LDT * 4;
+    static_assert(BM % PASSES == 0 && BYTES <= CAP, "epilogue tile does not fit the LDS");
+};
+
 template <int BM, int BN, int BK, int WM, int WN, int NS, int EPI>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ W, int M, int N, int K,
@@ -113,6 +126,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     constexpr int STAGE = (BM + BN) * CPR;  // 16-byte slots per stage
     constexpr int A_LD = BM * CPR / NT, B_LD = BN * CPR / NT;
     constexpr int P = A_LD + B_LD;          // direct loads per thread per slab
+    // the 96x96 wave tile has no registers to spare for fragment reads that linger
+    constexpr bool SPREAD = !(FM == 3 && FN == 3);
     static_assert(BM * CPR % NT == 0 && BN * CPR % NT == 0, "tile/thread mismatch");
     static_assert(KS % 2 == 0 && NS >= 2, "");
 
@@ -211,7 +226,45 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
 #define MVLA_MFMA(AF, BF)                                                                      \
     {                                                                                          \
         _Pragma("unroll") for (int i = 0; i < FM; ++i) _Pragma("unroll") for (int j = 0; j < FN; ++j) \
-            acc[i][j] = mfma32(AF[i], BF[j], acc[i][j]);                                       \
+            acc[i][j] = mfma32(BF[j], AF[i], acc[i][j]);                                       \
+    }
+
+// Scheduling of one k-step: the fragment reads of the next step are dealt out between this
+// step's MFMAs (MPR MFMAs, then one read, ...) instead of going out in one burst.
+#define MVLA_SPREAD_READS                                                                      \
+    {                                                                                          \
+        constexpr int MPR = (FM * FN) / (FM + FN) > 0 ? (FM * FN) / (FM + FN) : 1;             \
+        if (SPREAD) {                                                                          \
+            _Pragma("unroll") for (int r = 0; r < FM + FN; ++r) {                              \
+                __builtin_amdgcn_sched_group_barrier(0x008, MPR, 0);                           \
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                             \
+            }                                                                                  \
+            __builtin_amdgcn_sched_group_barrier(0x008, FM * FN, 0);                           \
+        } else { /* reads first, then the MFMAs */                                             \
+            __builtin_amdgcn_sched_group_barrier(0x100, FM + FN, 0);                           \
+            __builtin_amdgcn_sched_group_barrier(0x008, FM * FN, 0);                           \
+        }                                                                                      \
+        __builtin_amdgcn_sched_barrier(0);                                                     \
+    }
+// the MFMAs of one k-step with the direct loads of slab KT dealt out between them, one per MFMA
+// (a wave that is alone on its SIMD would otherwise issue nothing to the matrix core while it
+// sets up the loads)
+#define MVLA_MFMA_ISSUE(AF, BF, KT, STG)                                                       \
+    {                                                                                          \
+        const int koff = min((KT), k1 - 1) * BK;                                               \
+        const uint32_t soff = (uint32_t)(STG) * STAGE * 16u;                                   \
+        int n_ = 0;                                                                            \
+        _Pragma("unroll") for (int i = 0; i < FM; ++i) _Pragma("unroll") for (int j = 0; j < FN; ++j) { \
+            acc[i][j] = mfma32(BF[j], AF[i], acc[i][j]);                                       \
+            if (n_ < A_LD) dma16(a_src[n_ < A_LD ? n_ : 0] + koff, a_lds[n_ < A_LD ? n_ : 0] + soff); \
+            else if (n_ < P) dma16(b_src[n_ < P ? n_ - A_LD : 0] + koff, b_lds[n_ < P ? n_ - A_LD : 0] + soff); \
+            __builtin_amdgcn_sched_barrier(0);                                                 \
+            ++n_;                                                                              \
+        }                                                                                      \
+        _Pragma("unroll") for (int r = FM * FN; r < P; ++r) {                                  \
+            if (r < A_LD) dma16(a_src[r < A_LD ? r : 0] + koff, a_lds[r < A_LD ? r : 0] + soff);     \
+            else dma16(b_src[r - A_LD] + koff, b_lds[r - A_LD] + soff);                        \
+        }                                                                                      \
     }
 
         // every thread of the workgroup has left the previous segment's LDS reads behind
@@ -230,36 +283,36 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
 #pragma unroll
             for (int s = 0; s < KS - 2; s += 2) {
                 MVLA_READ_FRAGS(af1, bf1, stage, s + 1)
-                __builtin_amdgcn_sched_barrier(0);
                 MVLA_MFMA(af0, bf0)
-                __builtin_amdgcn_sched_barrier(0);
+                MVLA_SPREAD_READS
                 MVLA_READ_FRAGS(af0, bf0, stage, s + 2)
-                __builtin_amdgcn_sched_barrier(0);
                 MVLA_MFMA(af1, bf1)
-                __builtin_amdgcn_sched_barrier(0);
+                MVLA_SPREAD_READS
             }
             MVLA_READ_FRAGS(af1, bf1, stage, KS - 1)
-            __builtin_amdgcn_sched_barrier(0);
             MVLA_MFMA(af0, bf0)
-            __builtin_amdgcn_sched_barrier(0);
+            MVLA_SPREAD_READS
             // slab kt+1 has landed for every wave; slab kt's stage is free for slab kt+NS
             wait_vm<(NS - 2) * P>();
             __syncthreads();
-            MVLA_ISSUE(kt + NS, stage)
             MVLA_READ_FRAGS(af0, bf0, nstage, 0)
             __builtin_amdgcn_sched_barrier(0);
-            MVLA_MFMA(af1, bf1)
-            __builtin_amdgcn_sched_barrier(0);
+            MVLA_MFMA_ISSUE(af1, bf1, kt + NS, stage)
             stage = nstage;
         }
         wait_vm<0>();
 #undef MVLA_ISSUE
 #undef MVLA_READ_FRAGS
 #undef MVLA_MFMA
+#undef MVLA_MFMA_ISSUE
+#undef MVLA_SPREAD_READS
 
         // ---- K-split tiles: park the partial sums; the last piece to arrive finishes --------
-        const int n_pieces = is_dp ? 1 : last_blk - first_blk + 1;
-        if (n_pieces > 1) {
+        // (the four-wave 128x128-per-wave shape keeps its register budget for the main loop:
+        // whole tiles only, the host never plans a K-split for it)
+        constexpr bool HAS_SK = !(WM * WN == 4 && BM * BN == 256 * 256);
+        const int n_pieces = (!HAS_SK || is_dp) ? 1 : last_blk - first_blk + 1;
+        if (HAS_SK && n_pieces > 1) {
             // slot 0 of a workgroup holds the piece of the tile its range starts in, slot 1 the next
             const int my_slot = 2 * sk_id + (seg == 0 ? 0 : 1);
             float* mine = partial + (size_t)my_slot * (BM * BN);
@@ -376,16 +429,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
             }
         }
 
-        // ---- epilogue through LDS: the accumulator tile (lane = column, registers = rows) is
-        // laid down as fp32 rows, then every thread takes 8 consecutive columns of a row, so the
-        // residual is read and the result written with 16-byte accesses on whole cache lines.
-        // A pass covers as many tile rows as the pipeline's LDS holds (a whole number of wave
-        // rows); only the waves owning those rows write.
-        constexpr int LDS_FLOATS = NS * STAGE * 4;
-        constexpr int PASSES = BM * BN <= LDS_FLOATS ? 1 : WM;   // whole tile, or one wave row each
-        constexpr int RP = BM / PASSES;                  // tile rows per pass
-        static_assert(BM % PASSES == 0 && RP % TM == 0, "pass must hold whole wave rows");
-        static_assert(RP * BN <= LDS_FLOATS, "epilogue tile does not fit the stages");
+        // ---- epilogue through LDS: the MFMAs are issued with the weight fragment as the first
+        // operand, so a lane of an accumulator block holds one tile row and its registers four
+        // consecutive columns at a time: the tile is laid down as fp32 rows with 16-byte stores,
+        // then every thread takes 8 consecutive columns of a row, so the residual is read and the
+        // result written with 16-byte accesses on whole cache lines.  A pass covers as many tile
+        // rows as the LDS holds (a whole number of wave rows); only the waves owning them write.
+        using EG = EpiGeom<BM, BN, WM, NS>;
+        constexpr int LDT = EG::LDT, PASSES = EG::PASSES, RP = EG::RP;
+        static_assert(RP % TM == 0, "pass must hold whole wave rows");
         constexpr int OUT_COLS = EPI == EPI_SILU_MUL ? BN / 2 : BN;   // output columns per tile
         constexpr int ITEMS = RP * OUT_COLS / 8;                      // 8-column items per pass
         float* tile = reinterpret_cast<float*>(lds);
@@ -400,9 +452,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
 #pragma unroll
                     for (int j = 0; j < FN; ++j)
 #pragma unroll
-                        for (int v = 0; v < 16; ++v) {
-                            const int r = wm * TM - pass * RP + i * 32 + mfma32_row(v, lane);
-                            tile[r * BN + wn * TN + j * 32 + fr] = acc[i][j][v];
+                        for (int q = 0; q < 4; ++q) {
+                            const int r = wm * TM - pass * RP + i * 32 + fr;
+                            const int c = wn * TN + j * 32 + 8 * q + 4 * fg;
+                            *reinterpret_cast<float4*>(tile + r * LDT + c) =
+                                make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1],
+                                            acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
                         }
             }
             __syncthreads();
@@ -416,7 +471,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
                 if (EPI == EPI_SILU_MUL) {
                     // gate block [64q, 64q+32) and up block [64q+32, 64q+64) of the tile
                     const int oc = c8 * 8;                      // output column within the tile
-                    const float* g = tile + r * BN + (oc >> 5) * 64 + (oc & 31);
+                    const float* g = tile + r * LDT + (oc >> 5) * 64 + (oc & 31);
                     const float4 g0 = *reinterpret_cast<const float4*>(g);
                     const float4 g1 = *reinterpret_cast<const float4*>(g + 4);
                     const float4 u0 = *reinterpret_cast<const float4*>(g + 32);
@@ -426,7 +481,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
 #pragma unroll
                     for (int e = 0; e < 8; ++e) x[e] = gv[e] / (1.f + __expf(-gv[e])) * uv[e];
                 } else {
-                    const float* t = tile + r * BN + c8 * 8;
+                    const float* t = tile + r * LDT + c8 * 8;
                     const float4 t0 = *reinterpret_cast<const float4*>(t);
                     const float4 t1 = *reinterpret_cast<const float4*>(t + 4);
                     x[0] = t0.x; x[1] = t0.y; x[2] = t0.z; x[3] = t0.w;
@@ -499,8 +554,8 @@ static int launch_cfg(const bf16_t* A, int lda, const bf16_t* W, int M, int N, i
                       int ldc, const void* R, int ldr, int epi, int slots_per_cu, int sk_pct,
                       float* partial,
                       size_t partial_bytes, uint32_t* counters, int n_counters, hipStream_t st) {
-    GemmPlan plan = make_plan(M, N, K, BM, BN, BK, kNumCUs * slots_per_cu,
-                              sk_pct);
+    constexpr bool has_sk = !(WM * WN == 4 && BM * BN == 256 * 256);
+    GemmPlan plan = make_plan(M, N, K, BM, BN, BK, kNumCUs * slots_per_cu, has_sk ? sk_pct : 0);
     if (plan.sk_blocks > 0) {
         const size_t need = (size_t)2 * plan.sk_blocks * BM * BN * sizeof(float);
         if (need > partial_bytes || plan.sk_tiles > n_counters) {  // no room: whole tiles only
@@ -510,7 +565,9 @@ static int launch_cfg(const bf16_t* A, int lda, const bf16_t* W, int M, int N, i
         }
     }
     const int grid = plan.dp_grid + plan.sk_blocks;
-    const size_t lds = (size_t)NS * (BM + BN) * (BK / 8) * sizeof(uint4);
+    const size_t stage_bytes = (size_t)NS * (BM + BN) * (BK / 8) * sizeof(uint4);
+    const size_t epi_bytes = EpiGeom<BM, BN, WM, NS>::BYTES;
+    const size_t lds = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
     dim3 block(WM * WN * 64);
 #define MVLA_GEMM_LAUNCH(E)                                                                   \
     do {                                                                                      \
@@ -540,14 +597,17 @@ size_t gemm_partial_bytes() {
 struct TileCfg {
     int BM, BN, slots_per_cu;
     float round_us;
+    bool can_split;   // has the K-split path
 };
-constexpr int kNumCfgs = 5;
+constexpr int kNumCfgs = 6;
 static const TileCfg kCfgs[kNumCfgs] = {
-    {256, 256, 1, 110.f},  // K-slab 64, eight waves of 128x64, two stages
-    {256, 128, 1, 62.f},   // K-slab 64, eight waves of 64x64, three stages
-    {128, 128, 2, 67.f},   // K-slab 64, four waves of 64x64, two stages, two workgroups per CU
-    {128, 128, 1, 35.f},   // K-slab 64, eight waves of 32x64, three stages
-    {288, 192, 1, 128.f},  // K-slab 64, six waves of 96x96, two stages (row counts just over 2x256)
+    {256, 256, 1, 105.f, true},   // K-slab 64, eight waves of 128x64, two stages
+    {256, 128, 1, 62.f, true},    // K-slab 64, eight waves of 64x64, three stages
+    {128, 128, 2, 67.f, true},    // K-slab 64, four waves of 64x64, two stages, two workgroups per CU
+    {128, 128, 1, 35.f, true},    // K-slab 64, eight waves of 32x64, three stages
+    {288, 192, 1, 128.f, true},   // K-slab 64, six waves of 96x96, two stages (row counts just over 2x256)
+    {256, 256, 1, 98.f, false},   // K-slab 64, four waves of 128x128 (accumulators fill the second
+                                  // register file, a third less LDS traffic per MFMA), whole tiles only
 };
 constexpr int kSplitPct = 50;        // cut the last round along K only when it is under half full
 constexpr float kSplitOverhead = 0.3f;  // cost of the partial-sum exchange, in rounds
@@ -559,7 +619,9 @@ static float estimate_us(const TileCfg& c, int M, int N, int K) {
     const int slots = kNumCUs * c.slots_per_cu;
     const long full = tiles / slots, rem = tiles % slots;
     float rounds = (float)full;
-    if (rem) rounds += (rem * 100 < (long)slots * kSplitPct) ? (float)rem / slots + kSplitOverhead : 1.f;
+    if (rem)
+        rounds += (c.can_split && rem * 100 < (long)slots * kSplitPct)
+                      ? (float)rem / slots + kSplitOverhead : 1.f;
     return rounds * c.round_us * (float)K / 4096.f;
 }
 
@@ -596,7 +658,8 @@ int launch_gemm(const bf16_t* A, int lda, const bf16_t* W, int M, int N, int K, 
         case 1: return launch_cfg<256, 128, 64, 4, 2, 3>(MVLA_ARGS);
         case 2: return launch_cfg<128, 128, 64, 2, 2, 2>(MVLA_ARGS);
         case 3: return launch_cfg<128, 128, 64, 4, 2, 3>(MVLA_ARGS);
-        default: return launch_cfg<288, 192, 64, 3, 2, 2>(MVLA_ARGS);
+        case 4: return launch_cfg<288, 192, 64, 3, 2, 2>(MVLA_ARGS);
+        default: return launch_cfg<256, 256, 64, 2, 2, 2>(MVLA_ARGS);
     }
 #undef MVLA_ARGS
 }
