@@ -30,7 +30,7 @@ if ROOT not in sys.path:
 # plain copy of known size (see profiles/single_view_gemm_gateup_hbm_traffic.txt).  Valid only
 # for the GEMM source the counters were taken with: keyed by kernel shape and a hash of gemm.hip.
 MEASURED_TRAFFIC = {
-    ("gemm_gateup", 544, 22016, 4096): (232.8e6, "487c401d51ef7e22"),
+    ("gemm_gateup", 544, 22016, 4096): (232.8e6, "4399b47a2317efe8"),
 }
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
