@@ -540,20 +540,24 @@ int mvla_tune_layers(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_
         int best_cfg = -1, best_pct = 0;
         for (int c = 0; c < gemm_num_configs() && rc == MVLA_OK; ++c)
             for (int sp = 0; sp < 3 && rc == MVLA_OK; ++sp) {
-                for (int r = -1; r < reps; ++r) {   // r == -1: untimed first launch
-                    if (r == 0 && hipEventRecord(e0, st) != hipSuccess) rc = MVLA_EHIP;
-                    const mvla_layer_weights& w = layers[(r + n_layers) % n_layers];
-                    const void* wt = j.which == 0 ? w.wqkv : j.which == 1 ? w.wo
-                                     : j.which == 2 ? w.w_gateup : w.w_down;
-                    const int lrc = launch_gemm(j.A, j.lda, static_cast<const bf16_t*>(wt), M, j.N, j.K,
-                                                j.C, j.ldc, j.R, j.ldr, j.epi, GEMM_WS(ctx), c,
-                                                kSplitChoices[sp], st);
-                    if (lrc) rc = lrc;
-                }
                 float ms = 0.f;
-                if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
-                    hipEventElapsedTime(&ms, e0, e1) != hipSuccess)
-                    rc = MVLA_EHIP;
+                for (int pass = 0; pass < 2 && rc == MVLA_OK; ++pass) {   // the better of two timings
+                    for (int r = (pass == 0 ? -1 : 0); r < reps; ++r) {   // r == -1: untimed first launch
+                        if (r == 0 && hipEventRecord(e0, st) != hipSuccess) rc = MVLA_EHIP;
+                        const mvla_layer_weights& w = layers[(r + n_layers) % n_layers];
+                        const void* wt = j.which == 0 ? w.wqkv : j.which == 1 ? w.wo
+                                         : j.which == 2 ? w.w_gateup : w.w_down;
+                        const int lrc = launch_gemm(j.A, j.lda, static_cast<const bf16_t*>(wt), M, j.N,
+                                                    j.K, j.C, j.ldc, j.R, j.ldr, j.epi, GEMM_WS(ctx), c,
+                                                    kSplitChoices[sp], st);
+                        if (lrc) rc = lrc;
+                    }
+                    float t = 0.f;
+                    if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                        hipEventElapsedTime(&t, e0, e1) != hipSuccess)
+                        rc = MVLA_EHIP;
+                    if (pass == 0 || t < ms) ms = t;
+                }
                 if (rc == MVLA_OK && (best_cfg < 0 || ms < best_ms)) {
                     best_ms = ms;
                     best_cfg = c;
