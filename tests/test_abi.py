@@ -49,3 +49,13 @@ def test_pack_layer_layout():
     col = p["w_gateup"][:, 0].tolist()
     assert col[:32] == list(range(32)) and col[32:64] == [-float(i) for i in range(32)]
     assert col[64:96] == list(range(32, 64))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark measures one GPU; asking for more ends with a message, before any GPU work."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
