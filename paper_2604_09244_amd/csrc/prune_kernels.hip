@@ -56,7 +56,20 @@ __global__ __launch_bounds__(SAL_THREADS) void salience_kernel(
     if (VEC == 4) {
         if (col0 + 3 < n_vis) {
             int r = r_begin + group;
-            // two independent loads in flight per lane
+            // four, then two independent loads in flight per lane
+            for (; r + 3 * SAL_GROUPS < r_end; r += 4 * SAL_GROUPS) {
+                const float4 a = *reinterpret_cast<const float4*>(base + (size_t)r * S + col0);
+                const float4 c =
+                    *reinterpret_cast<const float4*>(base + (size_t)(r + SAL_GROUPS) * S + col0);
+                const float4 d =
+                    *reinterpret_cast<const float4*>(base + (size_t)(r + 2 * SAL_GROUPS) * S + col0);
+                const float4 e =
+                    *reinterpret_cast<const float4*>(base + (size_t)(r + 3 * SAL_GROUPS) * S + col0);
+                acc[0] += a.x; acc[1] += a.y; acc[2] += a.z; acc[3] += a.w;
+                acc[0] += c.x; acc[1] += c.y; acc[2] += c.z; acc[3] += c.w;
+                acc[0] += d.x; acc[1] += d.y; acc[2] += d.z; acc[3] += d.w;
+                acc[0] += e.x; acc[1] += e.y; acc[2] += e.z; acc[3] += e.w;
+            }
             for (; r + SAL_GROUPS < r_end; r += 2 * SAL_GROUPS) {
                 const float4 a = *reinterpret_cast<const float4*>(base + (size_t)r * S + col0);
                 const float4 c =
