@@ -143,26 +143,56 @@ __global__ __launch_bounds__(ROPE_THREADS) void rope_split_kernel(
     const int D = H * DH, ld = n_sections * D;
     const int tid = threadIdx.x;
 
-    // q (section 0) and k (section 1)
-    for (int item = tid; item < 2 * ROPE_TOK * CH; item += ROPE_THREADS) {
+    // v (section 2): the loads go out first so that their latency overlaps the q/k work
+    constexpr int V_IT = ROPE_TOK * (DH / 8) / ROPE_THREADS;
+    uint4 vreg[V_IT];
+    if (n_sections == 3) {
+#pragma unroll
+        for (int u = 0; u < V_IT; ++u) {
+            const int item = tid + u * ROPE_THREADS;
+            const int t = item / (DH / 8), c = item % (DH / 8);
+            const int s = s0 + t;
+            vreg[u] = make_uint4(0, 0, 0, 0);
+            if (s < S) vreg[u] = *reinterpret_cast<const uint4*>(qkv + ((size_t)b * S + s) * ld + 2 * D +
+                                                                 h * DH + c * 8);
+        }
+    }
+
+    // q (section 0) and k (section 1): all of a thread's items are loaded before the first is
+    // stored (the rotation is in place, so the compiler cannot move a load above a store)
+    constexpr int QK_IT = 2 * ROPE_TOK * CH / ROPE_THREADS;
+    static_assert(2 * ROPE_TOK * CH % ROPE_THREADS == 0, "");
+    uint4 va[QK_IT], vb[QK_IT];
+    float4 c0[QK_IT], c1[QK_IT], s0v[QK_IT], s1v[QK_IT];
+    bf16_t* basep[QK_IT];
+#pragma unroll
+    for (int u = 0; u < QK_IT; ++u) {
+        const int item = tid + u * ROPE_THREADS;
         const int sec = item / (ROPE_TOK * CH);
         const int rem = item % (ROPE_TOK * CH);
         const int t = rem / CH, c = rem % CH;
-        const int s = s0 + t;
-        if (s >= S) continue;
+        const int s = min(s0 + t, S - 1);   // rows past the end: loaded, not stored
         const size_t m = (size_t)b * S + s;
         int p = pos[m];
         p = min(max(p, 0), rope_len - 1);
-        bf16_t* base = qkv + m * ld + sec * D + h * DH;
-        uint4 va = *reinterpret_cast<uint4*>(base + c * 8);
-        uint4 vb = *reinterpret_cast<uint4*>(base + HALF + c * 8);
-        const float4 c0 = *reinterpret_cast<const float4*>(rc + (size_t)p * HALF + c * 8);
-        const float4 c1 = *reinterpret_cast<const float4*>(rc + (size_t)p * HALF + c * 8 + 4);
-        const float4 s0v = *reinterpret_cast<const float4*>(rs + (size_t)p * HALF + c * 8);
-        const float4 s1v = *reinterpret_cast<const float4*>(rs + (size_t)p * HALF + c * 8 + 4);
-        const float cs[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
-        const float sn[8] = {s0v.x, s0v.y, s0v.z, s0v.w, s1v.x, s1v.y, s1v.z, s1v.w};
-        uint32_t aw[4] = {va.x, va.y, va.z, va.w}, bw[4] = {vb.x, vb.y, vb.z, vb.w};
+        basep[u] = qkv + m * ld + sec * D + h * DH + c * 8;
+        va[u] = *reinterpret_cast<uint4*>(basep[u]);
+        vb[u] = *reinterpret_cast<uint4*>(basep[u] + HALF);
+        c0[u] = *reinterpret_cast<const float4*>(rc + (size_t)p * HALF + c * 8);
+        c1[u] = *reinterpret_cast<const float4*>(rc + (size_t)p * HALF + c * 8 + 4);
+        s0v[u] = *reinterpret_cast<const float4*>(rs + (size_t)p * HALF + c * 8);
+        s1v[u] = *reinterpret_cast<const float4*>(rs + (size_t)p * HALF + c * 8 + 4);
+    }
+#pragma unroll
+    for (int u = 0; u < QK_IT; ++u) {
+        const int item = tid + u * ROPE_THREADS;
+        const int t = (item % (ROPE_TOK * CH)) / CH;
+        if (s0 + t >= S) continue;
+        const float cs[8] = {c0[u].x, c0[u].y, c0[u].z, c0[u].w, c1[u].x, c1[u].y, c1[u].z, c1[u].w};
+        const float sn[8] = {s0v[u].x, s0v[u].y, s0v[u].z, s0v[u].w,
+                             s1v[u].x, s1v[u].y, s1v[u].z, s1v[u].w};
+        uint32_t aw[4] = {va[u].x, va[u].y, va[u].z, va[u].w};
+        uint32_t bw[4] = {vb[u].x, vb[u].y, vb[u].z, vb[u].w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const float a0 = __uint_as_float(aw[i] << 16), a1 = __uint_as_float(aw[i] & 0xFFFF0000u);
@@ -174,21 +204,19 @@ __global__ __launch_bounds__(ROPE_THREADS) void rope_split_kernel(
             aw[i] = pack_bf16x2(ra0, ra1);
             bw[i] = pack_bf16x2(rb0, rb1);
         }
-        *reinterpret_cast<uint4*>(base + c * 8) = make_uint4(aw[0], aw[1], aw[2], aw[3]);
-        *reinterpret_cast<uint4*>(base + HALF + c * 8) = make_uint4(bw[0], bw[1], bw[2], bw[3]);
+        *reinterpret_cast<uint4*>(basep[u]) = make_uint4(aw[0], aw[1], aw[2], aw[3]);
+        *reinterpret_cast<uint4*>(basep[u] + HALF) = make_uint4(bw[0], bw[1], bw[2], bw[3]);
     }
     if (n_sections < 3) return;
 
-    // v (section 2): [64 tokens x DH] -> LDS -> vt[d][s0 .. s0+63]
+    // [64 tokens x DH] -> LDS -> vt[d][s0 .. s0+63]
     __shared__ bf16_t tile[ROPE_TOK][DH + 2];  // +2: odd word stride, conflict-free column reads
-    for (int item = tid; item < ROPE_TOK * (DH / 8); item += ROPE_THREADS) {
+#pragma unroll
+    for (int u = 0; u < V_IT; ++u) {
+        const int item = tid + u * ROPE_THREADS;
         const int t = item / (DH / 8), c = item % (DH / 8);
-        const int s = s0 + t;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (s < S) v = *reinterpret_cast<const uint4*>(qkv + ((size_t)b * S + s) * ld + 2 * D +
-                                                       h * DH + c * 8);
         uint32_t* dst = reinterpret_cast<uint32_t*>(&tile[t][c * 8]);
-        dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
+        dst[0] = vreg[u].x; dst[1] = vreg[u].y; dst[2] = vreg[u].z; dst[3] = vreg[u].w;
     }
     __syncthreads();
     bf16_t* vrow = vt + ((size_t)(b * H + h) * DH) * S_pad + s0;
