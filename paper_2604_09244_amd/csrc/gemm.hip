@@ -146,7 +146,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     if (is_dp) {
         n_seg_work = xcd_chunked(blockIdx.x, plan.dp_tiles) < plan.dp_tiles ? 1 : 0;
     } else {
-        sk_id = blockIdx.x - plan.dp_grid;
+        // K-split workgroups in XCD-contiguous order too: the pieces of a tile, and the tiles that
+        // share a weight panel, then run on one XCD at the same time and share its L2
+        const int id = blockIdx.x - plan.dp_grid, x = id & 7;   // dp_grid is a multiple of 8
+        sk_id = x * (plan.sk_blocks >> 3) + min(x, plan.sk_blocks & 7) + (id >> 3);
         const long total = (long)plan.sk_tiles * k_tiles;
         it_begin = (int)(total * sk_id / plan.sk_blocks);
         it_end = (int)(total * (sk_id + 1) / plan.sk_blocks);
@@ -361,7 +364,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
             static_assert(NQ % CH == 0 && CH % 4 == 0, "");
             constexpr int PPR = (KEEP_OWN && 2 * NQ <= 16) ? 2 : 1;   // pieces per round trip
             f32x16_t own[KEEP_OWN ? FM : 1][KEEP_OWN ? FN : 1];
-            const int my_piece = KEEP_OWN ? (int)blockIdx.x - plan.dp_grid - first_blk : -1;
+            const int my_piece = KEEP_OWN ? sk_id - first_blk : -1;
 #pragma unroll
             for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -599,7 +602,7 @@ struct TileCfg {
     float round_us;
     bool can_split;   // has the K-split path
 };
-constexpr int kNumCfgs = 6;
+constexpr int kNumCfgs = 7;
 static const TileCfg kCfgs[kNumCfgs] = {
     {256, 256, 1, 105.f, true},   // K-slab 64, eight waves of 128x64, two stages
     {256, 128, 1, 62.f, true},    // K-slab 64, eight waves of 64x64, three stages
@@ -608,6 +611,8 @@ static const TileCfg kCfgs[kNumCfgs] = {
     {288, 192, 1, 128.f, true},   // K-slab 64, six waves of 96x96, two stages (row counts just over 2x256)
     {256, 256, 1, 98.f, false},   // K-slab 64, four waves of 128x128 (accumulators fill the second
                                   // register file, a third less LDS traffic per MFMA), whole tiles only
+    {192, 128, 1, 50.f, true},    // K-slab 64, eight waves of 96x32, three stages (row counts just over
+                                  // 2x256 with few column tiles: three row tiles, K-split over all CUs)
 };
 constexpr int kSplitPct = 50;        // cut the last round along K only when it is under half full
 constexpr float kSplitOverhead = 0.3f;  // cost of the partial-sum exchange, in rounds
@@ -659,7 +664,8 @@ int launch_gemm(const bf16_t* A, int lda, const bf16_t* W, int M, int N, int K, 
         case 2: return launch_cfg<128, 128, 64, 2, 2, 2>(MVLA_ARGS);
         case 3: return launch_cfg<128, 128, 64, 4, 2, 3>(MVLA_ARGS);
         case 4: return launch_cfg<288, 192, 64, 3, 2, 2>(MVLA_ARGS);
-        default: return launch_cfg<256, 256, 64, 2, 2, 2>(MVLA_ARGS);
+        case 5: return launch_cfg<256, 256, 64, 2, 2, 2>(MVLA_ARGS);
+        default: return launch_cfg<192, 128, 64, 2, 4, 3>(MVLA_ARGS);
     }
 #undef MVLA_ARGS
 }
