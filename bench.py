@@ -278,6 +278,13 @@ def main():
                    sample=f"sample 0 of {wl.B}, whole pruned prefill, {Lc} of {wl.L} layers timed "
                           f"({dt:.1f} s)" + ("" if scale == 1.0 else f", scaled x{scale:.2f} to {wl.L} layers"))
 
+    # the tile configuration / K-split threshold each projection shape runs with
+    choices = {}
+    if not args.no_tune:
+        for M in sorted({M_full, M_kept}, reverse=True):
+            for nm, (N_, K_, e_) in (("qkv", (3 * wl.D, wl.D, 0)), ("o", (wl.D, wl.D, 1)),
+                                     ("gateup", (2 * wl.F, wl.D, 3)), ("down", (wl.D, wl.F, 2))):
+                choices[f"{nm}@{M}"] = list(ctx.tuned_choice(M, N_, K_, e_))
     out = {
         "metric": "pruned-prefill tokens/s",
         "value": M_full / sec_pruned,
@@ -290,7 +297,8 @@ def main():
                    "n3": wl.n3, "n_text": wl.nt, "layers": wl.L, "full_layers_before_pruning": wl.p,
                    "keep_permille": wl.keep_permille, "hidden": wl.D, "heads": wl.H, "mlp": wl.F,
                    "fused_prune_call": fused, "scoring_reduced_on_the_fly": otf,
-                   "projection_kernels_measured_at_setup": not args.no_tune},
+                   "projection_kernels_measured_at_setup": not args.no_tune,
+                   "projection_kernel_choices": choices},
         "prune_step_us": prune_total_us,
         "prune_step_us_by_kernel": prune_us,
         "prune_pct_of_pruned_prefill": 100.0 * prune_total_us * 1e-6 / sec_instr,

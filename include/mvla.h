@@ -306,9 +306,10 @@ int mvla_prefill_layer_prune(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvl
 int mvla_tune_layers(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weights* layers,
                      int n_layers, int B, int S);
 /* Record a choice by hand (e.g. one measured in an earlier run, for identical
- * summation order across runs): configuration index 0 .. 6 (256x256 on eight waves,
+ * summation order across runs): configuration index 0 .. 7 (256x256 on eight waves,
  * 256x128, 128x128 two per CU, 128x128 on eight waves, 288x192, 256x256 on four
- * waves: whole tiles only, its K-split threshold is ignored, 192x128) and the K-split
+ * waves: whole tiles only, its K-split threshold is ignored, 192x128, 288x192 on
+ * four waves: whole tiles only) and the K-split
  * threshold in percent (0 never, 101 whenever the last round of tiles is not
  * full); cfg < 0 removes the record.  Host-side only, nothing is launched. */
 int mvla_set_gemm_choice(mvla_ctx* ctx, int M, int N, int K, int epilogue, int cfg, int split_pct);

@@ -108,10 +108,12 @@ template <int BM, int BN, int WM, int NS>
 struct EpiGeom {
     static constexpr int LDT = BN + 4;
     static constexpr int CAP = (NS == 2 && BM == 128 && BN == 128) ? 76 * 1024 : 156 * 1024;
+    static constexpr int TM = (BM / 32 + WM - 1) / WM * 32;   // rows of a wave row
     static constexpr int PASSES = BM * LDT * 4 <= CAP ? 1 : WM;
-    static constexpr int RP = BM / PASSES;
+    static constexpr int RP = PASSES == 1 ? BM : TM;
     static constexpr int BYTES = RP * LDT * 4;
-    static_assert(BM % PASSES == 0 && BYTES <= CAP, "epilogue tile does not fit the LDS");
+    static_assert(BYTES <= CAP, "epilogue tile does not fit the LDS");
+    static_assert(TM * WM == BM || PASSES == WM, "overlapping wave rows go one per pass");
 };
 
 template <int BM, int BN, int BK, int WM, int WN, int NS, int EPI>
@@ -122,7 +124,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     constexpr int NT = WM * WN * 64;
     constexpr int CPR = BK / 8;             // 16-byte chunks per LDS row
     constexpr int KS = BK / 16;             // MFMA k-steps per slab
-    constexpr int TM = BM / WM, TN = BN / WN, FM = TM / 32, FN = TN / 32;
+    // A wave owns FM x FN accumulator blocks of 32x32.  When the tile's 32-row blocks do not
+    // divide among the WM wave rows (288 rows on two wave rows), every wave row still takes
+    // FM = ceil blocks and the last one starts early: the rows both cover are computed twice
+    // (identical values) so that the main loop stays free of branches.
+    constexpr int FM = (BM / 32 + WM - 1) / WM, TM = FM * 32, TN = BN / WN, FN = TN / 32;
+    static_assert(BM % 32 == 0 && BN % (32 * WN) == 0 && TM <= BM, "");
     constexpr int STAGE = (BM + BN) * CPR;  // 16-byte slots per stage
     constexpr int A_LD = BM * CPR / NT, B_LD = BN * CPR / NT;
     constexpr int P = A_LD + B_LD;          // direct loads per thread per slab
@@ -136,6 +143,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     __shared__ int sh_slot[SK_MAX_PIECES];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
+    const int wrow0 = min(wm * TM, BM - TM);   // first tile row of this wave's blocks
     const int fr = lane & 31, fg = lane >> 5;
     const int k_tiles = plan.k_tiles;
 
@@ -198,7 +206,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
         }
         int a_row[FM], b_row[FN];
 #pragma unroll
-        for (int i = 0; i < FM; ++i) a_row[i] = wm * TM + i * 32 + fr;
+        for (int i = 0; i < FM; ++i) a_row[i] = wrow0 + i * 32 + fr;
 #pragma unroll
         for (int j = 0; j < FN; ++j) b_row[j] = wn * TN + j * 32 + fr;
 
@@ -313,7 +321,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
         // ---- K-split tiles: park the partial sums; the last piece to arrive finishes --------
         // (the four-wave 128x128-per-wave shape keeps its register budget for the main loop:
         // whole tiles only, the host never plans a K-split for it)
-        constexpr bool HAS_SK = !(WM * WN == 4 && BM * BN == 256 * 256);
+        constexpr bool HAS_SK = !(WM * WN == 4 && FM * FN >= 15);
         const int n_pieces = (!HAS_SK || is_dp) ? 1 : last_blk - first_blk + 1;
         if (HAS_SK && n_pieces > 1) {
             // slot 0 of a workgroup holds the piece of the tile its range starts in, slot 1 the next
@@ -440,7 +448,6 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
         // rows as the LDS holds (a whole number of wave rows); only the waves owning them write.
         using EG = EpiGeom<BM, BN, WM, NS>;
         constexpr int LDT = EG::LDT, PASSES = EG::PASSES, RP = EG::RP;
-        static_assert(RP % TM == 0, "pass must hold whole wave rows");
         constexpr int OUT_COLS = EPI == EPI_SILU_MUL ? BN / 2 : BN;   // output columns per tile
         constexpr int ITEMS = RP * OUT_COLS / 8;                      // 8-column items per pass
         float* tile = reinterpret_cast<float*>(lds);
@@ -449,14 +456,16 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
 #pragma unroll 1
         for (int pass = 0; pass < PASSES; ++pass) {
             __syncthreads();   // previous readers of the LDS (fragments or the last pass) are done
-            if (wm * TM >= pass * RP && wm * TM < (pass + 1) * RP) {
+            // first tile row of the pass (with overlapping wave rows the last pass starts early)
+            const int prow0 = PASSES == 1 ? 0 : min(pass * TM, BM - TM);
+            if (PASSES == 1 || wm == pass) {
 #pragma unroll
                 for (int i = 0; i < FM; ++i)
 #pragma unroll
                     for (int j = 0; j < FN; ++j)
 #pragma unroll
                         for (int q = 0; q < 4; ++q) {
-                            const int r = wm * TM - pass * RP + i * 32 + fr;
+                            const int r = wrow0 - prow0 + i * 32 + fr;
                             const int c = wn * TN + j * 32 + 8 * q + 4 * fg;
                             *reinterpret_cast<float4*>(tile + r * LDT + c) =
                                 make_float4(acc[i][j][4 * q], acc[i][j][4 * q + 1],
@@ -467,9 +476,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
 #pragma unroll 1
             for (int it = tid; it < ITEMS; it += NT) {
                 const int r = it / (OUT_COLS / 8), c8 = it % (OUT_COLS / 8);
-                const int row = m0 + pass * RP + r;
+                const int row = m0 + prow0 + r;
                 const int ocol = out_n0 + c8 * 8;
                 if (row >= M || ocol >= out_N) continue;
+                if (PASSES > 1 && prow0 + r < pass * TM) continue;   // written by the pass before
                 float x[8];
                 if (EPI == EPI_SILU_MUL) {
                     // gate block [64q, 64q+32) and up block [64q+32, 64q+64) of the tile
@@ -557,7 +567,7 @@ static int launch_cfg(const bf16_t* A, int lda, const bf16_t* W, int M, int N, i
                       int ldc, const void* R, int ldr, int epi, int slots_per_cu, int sk_pct,
                       float* partial,
                       size_t partial_bytes, uint32_t* counters, int n_counters, hipStream_t st) {
-    constexpr bool has_sk = !(WM * WN == 4 && BM * BN == 256 * 256);
+    constexpr bool has_sk = !(WM * WN == 4 && ((BM / 32 + WM - 1) / WM) * (BN / WN / 32) >= 15);
     GemmPlan plan = make_plan(M, N, K, BM, BN, BK, kNumCUs * slots_per_cu, has_sk ? sk_pct : 0);
     if (plan.sk_blocks > 0) {
         const size_t need = (size_t)2 * plan.sk_blocks * BM * BN * sizeof(float);
@@ -602,7 +612,7 @@ struct TileCfg {
     float round_us;
     bool can_split;   // has the K-split path
 };
-constexpr int kNumCfgs = 7;
+constexpr int kNumCfgs = 8;
 static const TileCfg kCfgs[kNumCfgs] = {
     {256, 256, 1, 105.f, true},   // K-slab 64, eight waves of 128x64, two stages
     {256, 128, 1, 62.f, true},    // K-slab 64, eight waves of 64x64, three stages
@@ -613,6 +623,9 @@ static const TileCfg kCfgs[kNumCfgs] = {
                                   // register file, a third less LDS traffic per MFMA), whole tiles only
     {192, 128, 1, 50.f, true},    // K-slab 64, eight waves of 96x32, three stages (row counts just over
                                   // 2x256 with few column tiles: three row tiles, K-split over all CUs)
+    {288, 192, 1, 92.f, false},   // K-slab 64, four waves of 160x96 (the two wave rows overlap by one
+                                  // 32-row block), accumulators in the second register file, whole
+                                  // tiles only
 };
 constexpr int kSplitPct = 50;        // cut the last round along K only when it is under half full
 constexpr float kSplitOverhead = 0.3f;  // cost of the partial-sum exchange, in rounds
@@ -665,7 +678,8 @@ int launch_gemm(const bf16_t* A, int lda, const bf16_t* W, int M, int N, int K, 
         case 3: return launch_cfg<128, 128, 64, 4, 2, 3>(MVLA_ARGS);
         case 4: return launch_cfg<288, 192, 64, 3, 2, 2>(MVLA_ARGS);
         case 5: return launch_cfg<256, 256, 64, 2, 2, 2>(MVLA_ARGS);
-        default: return launch_cfg<192, 128, 64, 2, 4, 3>(MVLA_ARGS);
+        case 6: return launch_cfg<192, 128, 64, 2, 4, 3>(MVLA_ARGS);
+        default: return launch_cfg<288, 192, 64, 2, 2, 2>(MVLA_ARGS);
     }
 #undef MVLA_ARGS
 }

@@ -36,13 +36,14 @@ def _resource_usage(src):
 def test_projection_kernels_fit_their_launch_shapes():
     k = _resource_usage("gemm.hip")
     gemm = {n: v for n, v in k.items() if "gemm_kernel" in n}
-    assert len(gemm) == 28                                   # 7 tile shapes x 4 epilogues
+    assert len(gemm) == 32                                   # 8 tile shapes x 4 epilogues
     for name, v in gemm.items():
         assert v["ScratchSize"] == 0, (name, v)              # (a spill reload in the main loop
-        four_wave_big = "ILi256ELi256ELi64ELi2ELi2ELi2E" in name   # would also wait on the loads)
+        four_wave_big = ("ILi256ELi256ELi64ELi2ELi2ELi2E" in name    # would also wait on the loads)
+                         or "ILi288ELi192ELi64ELi2ELi2ELi2E" in name)
         assert v["Occupancy"] >= (1 if four_wave_big else 2), (name, v)
         if four_wave_big:                                    # accumulators in the second file
-            assert v["AGPRs"] == 256 and v["VGPRs"] <= 256, (name, v)
+            assert v["AGPRs"] >= 240 and v["VGPRs"] <= 256, (name, v)
     # 128x128 on four waves with two stages is launched two workgroups per CU
     two_per_cu = [v for n, v in gemm.items() if "ILi128ELi128ELi64ELi2ELi2ELi2E" in n]
     assert len(two_per_cu) == 4
