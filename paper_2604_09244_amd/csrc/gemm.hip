@@ -131,11 +131,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     constexpr int FM = (BM / 32 + WM - 1) / WM, TM = FM * 32, TN = BN / WN, FN = TN / 32;
     static_assert(BM % 32 == 0 && BN % (32 * WN) == 0 && TM <= BM, "");
     constexpr int STAGE = (BM + BN) * CPR;  // 16-byte slots per stage
-    constexpr int A_LD = BM * CPR / NT, B_LD = BN * CPR / NT;
+    constexpr int A_SLOTS = BM * CPR, B_SLOTS = BN * CPR;   // 16-byte slots of the A and W tiles
+    constexpr int A_LD = A_SLOTS / NT, B_LD = B_SLOTS / NT;
     constexpr int P = A_LD + B_LD;          // direct loads per thread per slab
     // the 96x96 wave tile has no registers to spare for fragment reads that linger
     constexpr bool SPREAD = !(FM == 3 && FN == 3);
-    static_assert(BM * CPR % NT == 0 && BN * CPR % NT == 0, "tile/thread mismatch");
+    static_assert(A_SLOTS % NT == 0 && B_SLOTS % NT == 0, "tile/thread mismatch");
     static_assert(KS % 2 == 0 && NS >= 2, "");
 
     extern __shared__ uint4 lds[];
@@ -195,14 +196,15 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
         for (int i = 0; i < A_LD; ++i) {
             const int sl = i * NT + tid, row = sl / CPR, ch = (sl % CPR) ^ swz<CPR>(row);
             a_src[i] = A + (size_t)min(m0 + row, M - 1) * lda + ch * 8;
-            a_lds[i] = __builtin_amdgcn_readfirstlane(lds_base + (uint32_t)(i * NT + wave * 64) * 16u);
+            a_lds[i] = __builtin_amdgcn_readfirstlane(
+                lds_base + (uint32_t)(i * NT + wave * 64) * 16u);
         }
 #pragma unroll
         for (int i = 0; i < B_LD; ++i) {
             const int sl = i * NT + tid, row = sl / CPR, ch = (sl % CPR) ^ swz<CPR>(row);
             b_src[i] = W + (size_t)min(n0 + row, N - 1) * K + ch * 8;
             b_lds[i] = __builtin_amdgcn_readfirstlane(
-                lds_base + (uint32_t)(BM * CPR + i * NT + wave * 64) * 16u);
+                lds_base + (uint32_t)(A_SLOTS + i * NT + wave * 64) * 16u);
         }
         int a_row[FM], b_row[FN];
 #pragma unroll
