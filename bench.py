@@ -28,9 +28,10 @@ if ROOT not in sys.path:
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a
 # plain copy of known size (see profiles/single_view_gemm_gateup_hbm_traffic.txt).  Valid only
-# for the GEMM source the counters were taken with: keyed by kernel shape and a hash of gemm.hip.
+# for the GEMM source and tile configuration the counters were taken with: keyed by kernel shape,
+# with a hash of gemm.hip and the configuration index the set-up measurement must have chosen.
 MEASURED_TRAFFIC = {
-    ("gemm_gateup", 544, 22016, 4096): (232.8e6, "4399b47a2317efe8"),
+    ("gemm_gateup", 544, 22016, 4096): (232.8e6, "6ccd7f30cc2b2c42", 7),
 }
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
@@ -165,7 +166,8 @@ def main():
     code = re.sub(r"//[^\n]*", "", open(src).read())
     src_hash = hashlib.sha256("".join(code.split()).encode()).hexdigest()[:16]
     meas = MEASURED_TRAFFIC.get(("gemm_gateup", dom_tag, 2 * wl.F, wl.D))
-    roofline["traffic"] = meas[0] if meas and meas[1] == src_hash else None
+    dom_cfg = None if args.no_tune else ctx.tuned_choice(dom_tag, 2 * wl.F, wl.D, 3)[0]
+    roofline["traffic"] = meas[0] if meas and meas[1] == src_hash and meas[2] == dom_cfg else None
     roofline["avg_us"] = dom_ms * 1e3
     roofline["launches"] = len(by_tag[dom_tag])
 
