@@ -31,7 +31,7 @@ if ROOT not in sys.path:
 # for the GEMM source and tile configuration the counters were taken with: keyed by kernel shape,
 # with a hash of gemm.hip and the configuration index the set-up measurement must have chosen.
 MEASURED_TRAFFIC = {
-    ("gemm_gateup", 544, 22016, 4096): (232.8e6, "6ccd7f30cc2b2c42", 7),
+    ("gemm_gateup", 544, 22016, 4096): (232.8e6, "6ccd7f30cc2b2c42", 6),
 }
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
@@ -144,7 +144,7 @@ def main():
 
     # ---- the timed region: K pruned prefills, nothing bracketed (an event pair around a launch
     # costs ~11 us of stream time, so per-kernel timing runs in regions of its own below) --------
-    GATEUP = 7
+    GATEUP = next(i for i in range(32) if mv.load().mvla_kernel_name(i) == b"gemm_gateup")
     for _ in range(Wm):
         run_pruned()
     ctx.profile_enable([], 0)

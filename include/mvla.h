@@ -306,10 +306,11 @@ int mvla_prefill_layer_prune(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvl
 int mvla_tune_layers(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weights* layers,
                      int n_layers, int B, int S);
 /* Record a choice by hand (e.g. one measured in an earlier run, for identical
- * summation order across runs): configuration index 0 .. 7 (256x256 on eight waves,
- * 256x128, 128x128 two per CU, 128x128 on eight waves, 288x192, 256x256 on four
- * waves: whole tiles only, its K-split threshold is ignored, 192x128, 288x192 on
- * four waves: whole tiles only) and the K-split
+ * summation order across runs): configuration index 0 .. 6 (256x256 on eight waves,
+ * 256x128, 128x128 two per CU, 128x128 on eight waves, 256x256 on four waves, 192x128,
+ * 288x192 on four waves; the two four-wave shapes run whole tiles only and ignore the
+ * K-split threshold; a shape whose tiles do not hold whole heads is not used for the
+ * q/k/v projection, whatever is recorded) and the K-split
  * threshold in percent (0 never, 101 whenever the last round of tiles is not
  * full); cfg < 0 removes the record.  Host-side only, nothing is launched. */
 int mvla_set_gemm_choice(mvla_ctx* ctx, int M, int N, int K, int epilogue, int cfg, int split_pct);
@@ -344,7 +345,7 @@ int mvla_profile_enable(mvla_ctx* ctx, uint32_t kernel_mask, int max_records);
  * Clears the record list. */
 int mvla_profile_read(mvla_ctx* ctx, int capacity, int32_t* ids, int32_t* tags, float* ms,
                       int32_t* n_out);
-/* Name of kernel id 0..19 ("rmsnorm", "gemm_qkv", "rope_split", "score_probs",
+/* Name of kernel id 0..18 ("rmsnorm", "gemm_qkv", "score_probs",
  * "attention", "gemm_o", "rmsnorm_mlp", "gemm_gateup", "gemm_down", "salience",
  * "budget", "select", "compact", "rope_table", "prune_fused", "smooth",
  * "decompose", "feature_share", "candidate_masks", "mask_indices"), "?"

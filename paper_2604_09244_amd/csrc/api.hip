@@ -101,7 +101,7 @@ struct Timed {
     if (rc) return rc
 
 const char* const kKernelNames[KID_COUNT] = {
-    "rmsnorm", "gemm_qkv", "rope_split", "score_probs", "attention", "gemm_o", "rmsnorm_mlp",
+    "rmsnorm", "gemm_qkv", "score_probs", "attention", "gemm_o", "rmsnorm_mlp",
     "gemm_gateup", "gemm_down", "salience", "budget", "select", "compact", "rope_table",
     "prune_fused", "smooth", "decompose", "feature_share", "candidate_masks", "mask_indices"};
 
@@ -399,12 +399,11 @@ static int run_layer(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_
 
     TIMED(ctx, KID_RMSNORM, M,
           launch_rmsnorm(xin, static_cast<const bf16_t*>(w->g_attn), M, D, cfg->rms_eps, lb.u, st));
+    // q and k leave the projection rotated, v transposed (no separate pass over q/k/v)
+    const RopeEpilogue rope = {pos, w->rope_cos, w->rope_sin, lb.vt, w->rope_len, S, lb.S_pad, D, dh};
     TIMED(ctx, KID_GEMM_QKV, M,
-          launch_gemm(lb.u, D, wqkv, M, 3 * D, D, lb.qkv, 3 * D, nullptr, 0, EPI_STORE, GEMM_WS(ctx),
-                      GEMM_PICK(ctx, M, 3 * D, D, EPI_STORE), st));
-    TIMED(ctx, KID_ROPE_SPLIT, M,
-          launch_rope_split(lb.qkv, pos, w->rope_cos, w->rope_sin, w->rope_len, B, S, H, dh,
-                            lb.S_pad, lb.vt, st));
+          launch_gemm(lb.u, D, wqkv, M, 3 * D, D, lb.qkv, 3 * D, nullptr, 0, EPI_QKV_ROPE,
+                      GEMM_WS(ctx), GEMM_PICK(ctx, M, 3 * D, D, EPI_QKV_ROPE), &rope, st));
     if (n_query_tail > 0 && !red) {
         TIMED(ctx, KID_SCORE_PROBS, M,
               launch_score_probs(lb.qkv, 3 * D, lb.qkv + D, 3 * D, key_bias, B, S, H, dh,
@@ -438,18 +437,18 @@ static int run_layer(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_
     TIMED(ctx, KID_GEMM_O, M,
           launch_gemm(lb.attn, D, static_cast<const bf16_t*>(w->wo), M, D, D, lb.x1, D, xin, D,
                       EPI_RES_BF16_TO_F32, GEMM_WS(ctx), GEMM_PICK(ctx, M, D, D, EPI_RES_BF16_TO_F32),
-                      st));
+                      nullptr, st));
     TIMED(ctx, KID_RMSNORM_MLP, M,
           launch_rmsnorm_f32(lb.x1, static_cast<const bf16_t*>(w->g_mlp), M, D, cfg->rms_eps, lb.u,
                              st));
     TIMED(ctx, KID_GEMM_GATEUP, M,
           launch_gemm(lb.u, D, static_cast<const bf16_t*>(w->w_gateup), M, 2 * F, D, lb.act, F,
                       nullptr, 0, EPI_SILU_MUL, GEMM_WS(ctx), GEMM_PICK(ctx, M, 2 * F, D, EPI_SILU_MUL),
-                      st));
+                      nullptr, st));
     TIMED(ctx, KID_GEMM_DOWN, M,
           launch_gemm(lb.act, F, static_cast<const bf16_t*>(w->w_down), M, D, F, y, D, lb.x1, D,
                       EPI_RES_F32_TO_BF16, GEMM_WS(ctx), GEMM_PICK(ctx, M, D, F, EPI_RES_F32_TO_BF16),
-                      st));
+                      nullptr, st));
     return MVLA_OK;
 }
 
@@ -527,7 +526,7 @@ int mvla_tune_layers(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_
     };
     // the down projection writes into the (unused) q/k/v buffer instead of a layer output
     const Job jobs[4] = {
-        {lb.u, D, 3 * D, D, lb.qkv, 3 * D, nullptr, 0, EPI_STORE, 0},
+        {lb.u, D, 3 * D, D, lb.qkv, 3 * D, nullptr, 0, EPI_QKV_ROPE, 0},
         {lb.attn, D, D, D, lb.x1, D, lb.u, D, EPI_RES_BF16_TO_F32, 1},
         {lb.u, D, 2 * F, D, lb.act, F, nullptr, 0, EPI_SILU_MUL, 2},
         {lb.act, F, D, F, lb.qkv, D, lb.x1, D, EPI_RES_F32_TO_BF16, 3},
@@ -540,6 +539,11 @@ int mvla_tune_layers(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_
         int best_cfg = -1, best_pct = 0;
         for (int c = 0; c < gemm_num_configs() && rc == MVLA_OK; ++c)
             for (int sp = 0; sp < 3 && rc == MVLA_OK; ++sp) {
+                // position ids of the timed q/k/v launches: the zeros of the attention buffer
+                const RopeEpilogue rope = {reinterpret_cast<const int32_t*>(lb.attn), layers[0].rope_cos,
+                                           layers[0].rope_sin, lb.vt, layers[0].rope_len, S, lb.S_pad,
+                                           D, cfg->dh};
+                if (!gemm_config_runs(c, j.epi, &rope)) continue;
                 float ms = 0.f;
                 for (int pass = 0; pass < 2 && rc == MVLA_OK; ++pass) {   // the better of two timings
                     for (int r = (pass == 0 ? -1 : 0); r < reps; ++r) {   // r == -1: untimed first launch
@@ -549,7 +553,8 @@ int mvla_tune_layers(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_
                                          : j.which == 2 ? w.w_gateup : w.w_down;
                         const int lrc = launch_gemm(j.A, j.lda, static_cast<const bf16_t*>(wt), M, j.N,
                                                     j.K, j.C, j.ldc, j.R, j.ldr, j.epi, GEMM_WS(ctx), c,
-                                                    kSplitChoices[sp], st);
+                                                    kSplitChoices[sp],
+                                                    j.epi == EPI_QKV_ROPE ? &rope : nullptr, st);
                         if (lrc) rc = lrc;
                     }
                     float t = 0.f;
@@ -623,12 +628,11 @@ int mvla_score_only(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_w
           launch_rmsnorm(static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(w->g_attn), M, D,
                          cfg->rms_eps, lb.u, st));
     // query and key projections only (first 2D rows of wqkv), stored with row stride 2D
+    const RopeEpilogue rope = {pos, w->rope_cos, w->rope_sin, nullptr, w->rope_len, S, lb.S_pad, D, dh};
     TIMED(ctx, KID_GEMM_QKV, M,
           launch_gemm(lb.u, D, static_cast<const bf16_t*>(w->wqkv), M, 2 * D, D, lb.qkv, 2 * D,
-                      nullptr, 0, EPI_STORE, GEMM_WS(ctx), GEMM_PICK(ctx, M, 2 * D, D, EPI_STORE), st));
-    TIMED(ctx, KID_ROPE_SPLIT, M,
-          launch_rope_split(lb.qkv, pos, w->rope_cos, w->rope_sin, w->rope_len, B, S, H, dh,
-                            lb.S_pad, nullptr, st));
+                      nullptr, 0, EPI_QKV_ROPE, GEMM_WS(ctx),
+                      GEMM_PICK(ctx, M, 2 * D, D, EPI_QKV_ROPE), &rope, st));
     TIMED(ctx, KID_SCORE_PROBS, M,
           launch_score_probs(lb.qkv, 2 * D, lb.qkv + D, 2 * D, key_bias, B, S, H, dh,
                              n_query_tail, probs_out, 0, st));

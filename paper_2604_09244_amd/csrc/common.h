@@ -12,7 +12,7 @@ typedef uint16_t bf16_t;  // raw bf16 storage
 
 // per-kernel timing records (HIP events on the context's stream)
 enum KernelId {
-    KID_RMSNORM = 0, KID_GEMM_QKV, KID_ROPE_SPLIT, KID_SCORE_PROBS, KID_ATTENTION, KID_GEMM_O,
+    KID_RMSNORM = 0, KID_GEMM_QKV, KID_SCORE_PROBS, KID_ATTENTION, KID_GEMM_O,
     KID_RMSNORM_MLP, KID_GEMM_GATEUP, KID_GEMM_DOWN, KID_SALIENCE, KID_BUDGET, KID_SELECT,
     KID_COMPACT, KID_ROPE_TABLE, KID_PRUNE_FUSED, KID_SMOOTH, KID_DECOMPOSE, KID_FEATURE_SHARE,
     KID_CANDIDATE, KID_MASK_INDEX, KID_COUNT
@@ -96,28 +96,38 @@ int launch_rmsnorm(const bf16_t* x, const bf16_t* gain, int M, int D, float eps,
 int launch_rmsnorm_f32(const float* x, const bf16_t* gain, int M, int D, float eps, bf16_t* out,
                        hipStream_t st);
 int launch_rope_table(double base, int rope_len, int dh, float* c, float* s, hipStream_t st);
-// q,k rotated in place inside qkv [B*S, 3D]; v transposed to vt [B, H, dh, S_pad]
-int launch_rope_split(bf16_t* qkv, const int32_t* pos, const float* rc, const float* rs,
-                      int rope_len, int B, int S, int H, int dh, int S_pad, bf16_t* vt,
-                      hipStream_t st);
 // scoring probabilities of the last nq rows: probs [B,H,nq,S] fp32
 int launch_score_probs(const bf16_t* q, int q_row_stride, const bf16_t* k, int k_row_stride,
                        const float* key_bias, int B, int S, int H, int dh, int nq, float* out,
                        int colsum_n, hipStream_t st);
 
 // gemm.hip:  C[M,N] = A[M,K] * W[N,K]^T  (bf16 in, fp32 accumulate)
-// EPI_STORE: C bf16.  EPI_RES_BF16_TO_F32: C fp32 = acc + R(bf16).  EPI_RES_F32_TO_BF16:
-// C bf16 = acc + R(fp32).  EPI_SILU_MUL: C bf16 [M, N/2] = SiLU(gate) * up.
-enum GemmEpilogue { EPI_STORE = 0, EPI_RES_BF16_TO_F32 = 1, EPI_RES_F32_TO_BF16 = 2,
+// EPI_QKV_ROPE: the q/k/v projection (N = 3D, or 2D for q and k alone).  Columns [0, 2D) are
+// rotated by the position of their row (pairs (d, d + dh/2) of every head, cos/sin from the
+// tables, in fp32 on the accumulators) and stored as bf16 into C [M, ldc]; columns [2D, 3D) are
+// stored transposed into vt [B, H, dh, S_pad] (zeros in [S, S_pad)) and not into C.
+// EPI_RES_BF16_TO_F32: C fp32 = acc + R(bf16).  EPI_RES_F32_TO_BF16: C bf16 = acc + R(fp32).
+// EPI_SILU_MUL: C bf16 [M, N/2] = SiLU(gate) * up.
+enum GemmEpilogue { EPI_QKV_ROPE = 0, EPI_RES_BF16_TO_F32 = 1, EPI_RES_F32_TO_BF16 = 2,
                     EPI_SILU_MUL = 3 };
+// What EPI_QKV_ROPE needs beyond C: rows are tokens b*S + s.
+struct RopeEpilogue {
+    const int32_t* pos;   // [M] position ids (clamped to the table)
+    const float* rc;      // [rope_len, dh/2] cos
+    const float* rs;      // [rope_len, dh/2] sin
+    bf16_t* vt;           // [B, H, dh, S_pad], null when N = 2D
+    int rope_len, S, S_pad, D, dh;
+};
 // partial: fp32 scratch of gemm_partial_bytes() for K-split tiles; counters: n_counters zeroed
 // arrival counters (left at zero again when the kernel ends).
 size_t gemm_partial_bytes();
 int launch_gemm(const bf16_t* A, int lda, const bf16_t* W, int M, int N, int K, void* C, int ldc,
                 const void* R, int ldr, int epilogue, float* partial, size_t partial_bytes,
                 uint32_t* counters, int n_counters, int force_cfg, int force_split_pct,
-                hipStream_t st);
+                const RopeEpilogue* rope, hipStream_t st);
 int gemm_num_configs();
+// whether tile configuration cfg can run this epilogue (the rotating one needs whole heads per tile)
+bool gemm_config_runs(int cfg, int epilogue, const RopeEpilogue* rope);
 
 // attention.hip: causal flash attention; q,k rows inside qkv (row stride ldqkv), vt [B,H,dh,S_pad]
 int launch_attention(const bf16_t* q, const bf16_t* k, int ldqkv, const bf16_t* vt, int S_pad,

@@ -120,7 +120,7 @@ template <int BM, int BN, int BK, int WM, int WN, int NS, int EPI>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ W, int M, int N, int K,
     void* __restrict__ Cv, int ldc, const void* __restrict__ Rv, int ldr, GemmPlan plan,
-    float* __restrict__ partial, uint32_t* __restrict__ counters) {
+    float* __restrict__ partial, uint32_t* __restrict__ counters, RopeEpilogue rope) {
     constexpr int NT = WM * WN * 64;
     constexpr int CPR = BK / 8;             // 16-byte chunks per LDS row
     constexpr int KS = BK / 16;             // MFMA k-steps per slab
@@ -134,8 +134,6 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     constexpr int A_SLOTS = BM * CPR, B_SLOTS = BN * CPR;   // 16-byte slots of the A and W tiles
     constexpr int A_LD = A_SLOTS / NT, B_LD = B_SLOTS / NT;
     constexpr int P = A_LD + B_LD;          // direct loads per thread per slab
-    // the 96x96 wave tile has no registers to spare for fragment reads that linger
-    constexpr bool SPREAD = !(FM == 3 && FN == 3);
     static_assert(A_SLOTS % NT == 0 && B_SLOTS % NT == 0, "tile/thread mismatch");
     static_assert(KS % 2 == 0 && NS >= 2, "");
 
@@ -247,16 +245,11 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
 #define MVLA_SPREAD_READS                                                                      \
     {                                                                                          \
         constexpr int MPR = (FM * FN) / (FM + FN) > 0 ? (FM * FN) / (FM + FN) : 1;             \
-        if (SPREAD) {                                                                          \
-            _Pragma("unroll") for (int r = 0; r < FM + FN; ++r) {                              \
-                __builtin_amdgcn_sched_group_barrier(0x008, MPR, 0);                           \
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                             \
-            }                                                                                  \
-            __builtin_amdgcn_sched_group_barrier(0x008, FM * FN, 0);                           \
-        } else { /* reads first, then the MFMAs */                                             \
-            __builtin_amdgcn_sched_group_barrier(0x100, FM + FN, 0);                           \
-            __builtin_amdgcn_sched_group_barrier(0x008, FM * FN, 0);                           \
+        _Pragma("unroll") for (int r = 0; r < FM + FN; ++r) {                                  \
+            __builtin_amdgcn_sched_group_barrier(0x008, MPR, 0);                               \
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                 \
         }                                                                                      \
+        __builtin_amdgcn_sched_group_barrier(0x008, FM * FN, 0);                               \
         __builtin_amdgcn_sched_barrier(0);                                                     \
     }
 // the MFMAs of one k-step with the direct loads of slab KT dealt out between them, one per MFMA
@@ -451,6 +444,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
         using EG = EpiGeom<BM, BN, WM, NS>;
         constexpr int LDT = EG::LDT, PASSES = EG::PASSES, RP = EG::RP;
         constexpr int OUT_COLS = EPI == EPI_SILU_MUL ? BN / 2 : BN;   // output columns per tile
+        static_assert(RP % 16 == 0, "row groups of 8 come in pairs");
         constexpr int ITEMS = RP * OUT_COLS / 8;                      // 8-column items per pass
         float* tile = reinterpret_cast<float*>(lds);
         const int out_n0 = EPI == EPI_SILU_MUL ? n0 / 2 : n0;
@@ -475,6 +469,85 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
                         }
             }
             __syncthreads();
+            if (EPI == EPI_QKV_ROPE) {
+                const int DH = rope.dh, HALF = DH >> 1, CPH = HALF >> 3;   // 16-byte chunks per half head
+                if (n0 < 2 * rope.D) {
+                    // q or k columns: every item is 8 columns of the first half of a head and
+                    // their partners dh/2 further on (tiles hold whole heads: BN % dh == 0)
+                    bf16_t* Cb = static_cast<bf16_t*>(Cv);
+                    const int per_row = (BN / DH) * CPH;
+#pragma unroll 1
+                    for (int it = tid; it < RP * per_row; it += NT) {
+                        const int r = it / per_row, rest = it - r * per_row;
+                        const int col = (rest / CPH) * DH + (rest % CPH) * 8;   // column in the tile
+                        const int row = m0 + prow0 + r;
+                        if (row >= M || n0 + col >= N) continue;
+                        if (PASSES > 1 && prow0 + r < pass * TM) continue;
+                        const int p = min(max(rope.pos[row], 0), rope.rope_len - 1);
+                        const float* ta = tile + r * LDT + col;
+                        const float4 a0 = *reinterpret_cast<const float4*>(ta);
+                        const float4 a1 = *reinterpret_cast<const float4*>(ta + 4);
+                        const float4 b0 = *reinterpret_cast<const float4*>(ta + HALF);
+                        const float4 b1 = *reinterpret_cast<const float4*>(ta + HALF + 4);
+                        const size_t toff = (size_t)p * HALF + (rest % CPH) * 8;
+                        const float4 c0 = *reinterpret_cast<const float4*>(rope.rc + toff);
+                        const float4 c1 = *reinterpret_cast<const float4*>(rope.rc + toff + 4);
+                        const float4 s0 = *reinterpret_cast<const float4*>(rope.rs + toff);
+                        const float4 s1 = *reinterpret_cast<const float4*>(rope.rs + toff + 4);
+                        const float a[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+                        const float b[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+                        const float cs[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+                        const float sn[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+                        uint32_t wa[4], wb[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            wa[e] = pack_bf16x2(a[2 * e] * cs[2 * e] - b[2 * e] * sn[2 * e],
+                                                a[2 * e + 1] * cs[2 * e + 1] - b[2 * e + 1] * sn[2 * e + 1]);
+                            wb[e] = pack_bf16x2(b[2 * e] * cs[2 * e] + a[2 * e] * sn[2 * e],
+                                                b[2 * e + 1] * cs[2 * e + 1] + a[2 * e + 1] * sn[2 * e + 1]);
+                        }
+                        bf16_t* dst = Cb + (size_t)row * ldc + n0 + col;
+                        *reinterpret_cast<uint4*>(dst) = make_uint4(wa[0], wa[1], wa[2], wa[3]);
+                        *reinterpret_cast<uint4*>(dst + HALF) = make_uint4(wb[0], wb[1], wb[2], wb[3]);
+                    }
+                } else {
+                    // v columns, transposed: an item is one column and 8 consecutive rows (tokens).
+                    // Lanes run over 32 columns x 2 row groups: LDS reads without bank conflicts,
+                    // 32 bytes of a vt row per column and instruction.
+                    const int H = rope.D / DH;
+#pragma unroll 1
+                    for (int it = tid; it < BN * (RP / 8); it += NT) {
+                        const int d = (it >> 1) % BN, g = ((it >> 1) / BN) * 2 + (it & 1);
+                        const int r0 = g * 8, row0 = m0 + prow0 + r0;
+                        if (row0 >= M || n0 + d >= N) continue;
+                        if (PASSES > 1 && prow0 + r0 < pass * TM) continue;
+                        float v[8];
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) v[i] = tile[(r0 + i) * LDT + d];
+                        const int vcol = n0 - 2 * rope.D + d, hd = vcol / DH, dd = vcol - hd * DH;
+                        const int bs = row0 / rope.S, s_first = row0 - bs * rope.S;
+                        if ((s_first & 7) == 0 && s_first + 8 < rope.S) {
+                            // 8 tokens of one sample, its last token not among them
+                            bf16_t* dst = rope.vt + ((size_t)(bs * H + hd) * DH + dd) * rope.S_pad + s_first;
+                            *reinterpret_cast<uint4*>(dst) =
+                                make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]),
+                                           pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
+                        } else {
+#pragma unroll 1
+                            for (int i = 0; i < 8; ++i) {
+                                const int row = row0 + i;
+                                if (row >= M) break;
+                                const int b2 = row / rope.S, s2 = row - b2 * rope.S;
+                                bf16_t* dst = rope.vt + ((size_t)(b2 * H + hd) * DH + dd) * rope.S_pad;
+                                dst[s2] = (bf16_t)(pack_bf16x2(v[i], 0.f) & 0xFFFFu);
+                                if (s2 == rope.S - 1)   // the sample's last token also clears the padding
+                                    for (int z = rope.S; z < rope.S_pad; ++z) dst[z] = 0;
+                            }
+                        }
+                    }
+                }
+                continue;
+            }
 #pragma unroll 1
             for (int it = tid; it < ITEMS; it += NT) {
                 const int r = it / (OUT_COLS / 8), c8 = it % (OUT_COLS / 8);
@@ -567,8 +640,8 @@ static GemmPlan make_plan(int M, int N, int K, int BM, int BN, int BK, int slots
 template <int BM, int BN, int BK, int WM, int WN, int NS>
 static int launch_cfg(const bf16_t* A, int lda, const bf16_t* W, int M, int N, int K, void* C,
                       int ldc, const void* R, int ldr, int epi, int slots_per_cu, int sk_pct,
-                      float* partial,
-                      size_t partial_bytes, uint32_t* counters, int n_counters, hipStream_t st) {
+                      float* partial, size_t partial_bytes, uint32_t* counters, int n_counters,
+                      const RopeEpilogue& rope, hipStream_t st) {
     constexpr bool has_sk = !(WM * WN == 4 && ((BM / 32 + WM - 1) / WM) * (BN / WN / 32) >= 15);
     GemmPlan plan = make_plan(M, N, K, BM, BN, BK, kNumCUs * slots_per_cu, has_sk ? sk_pct : 0);
     if (plan.sk_blocks > 0) {
@@ -591,9 +664,9 @@ static int launch_cfg(const bf16_t* A, int lda, const bf16_t* W, int M, int N, i
                                            hipFuncAttributeMaxDynamicSharedMemorySize,        \
                                            (int)lds));                                        \
         hipLaunchKernelGGL(kern, dim3(grid), block, lds, st, A, lda, W, M, N, K, C, ldc, R,   \
-                           ldr, plan, partial, counters);                                     \
+                           ldr, plan, partial, counters, rope);                               \
     } while (0)
-    if (epi == EPI_STORE) MVLA_GEMM_LAUNCH(EPI_STORE);
+    if (epi == EPI_QKV_ROPE) MVLA_GEMM_LAUNCH(EPI_QKV_ROPE);
     else if (epi == EPI_RES_BF16_TO_F32) MVLA_GEMM_LAUNCH(EPI_RES_BF16_TO_F32);
     else if (epi == EPI_RES_F32_TO_BF16) MVLA_GEMM_LAUNCH(EPI_RES_F32_TO_BF16);
     else MVLA_GEMM_LAUNCH(EPI_SILU_MUL);
@@ -614,13 +687,12 @@ struct TileCfg {
     float round_us;
     bool can_split;   // has the K-split path
 };
-constexpr int kNumCfgs = 8;
+constexpr int kNumCfgs = 7;
 static const TileCfg kCfgs[kNumCfgs] = {
     {256, 256, 1, 105.f, true},   // K-slab 64, eight waves of 128x64, two stages
     {256, 128, 1, 62.f, true},    // K-slab 64, eight waves of 64x64, three stages
     {128, 128, 2, 67.f, true},    // K-slab 64, four waves of 64x64, two stages, two workgroups per CU
     {128, 128, 1, 35.f, true},    // K-slab 64, eight waves of 32x64, three stages
-    {288, 192, 1, 128.f, true},   // K-slab 64, six waves of 96x96, two stages (row counts just over 2x256)
     {256, 256, 1, 98.f, false},   // K-slab 64, four waves of 128x128 (accumulators fill the second
                                   // register file, a third less LDS traffic per MFMA), whole tiles only
     {192, 128, 1, 50.f, true},    // K-slab 64, eight waves of 96x32, three stages (row counts just over
@@ -647,40 +719,62 @@ static float estimate_us(const TileCfg& c, int M, int N, int K) {
 
 int gemm_num_configs() { return kNumCfgs; }
 
+// The rotating q/k/v epilogue works on tiles that hold whole heads and lie inside one of the
+// q, k, v column sections.
+static bool cfg_runs(const TileCfg& c, int epilogue, const RopeEpilogue* rope) {
+    return epilogue != EPI_QKV_ROPE || (c.BN % rope->dh == 0 && rope->D % c.BN == 0);
+}
+
+bool gemm_config_runs(int cfg, int epilogue, const RopeEpilogue* rope) {
+    return cfg >= 0 && cfg < kNumCfgs && (epilogue != EPI_QKV_ROPE || rope) &&
+           cfg_runs(kCfgs[cfg], epilogue, rope);
+}
+
 // force_cfg >= 0 picks that tile configuration and force_split_pct the K-split threshold
-// (0 = never, 101 = whenever the last round is not full); force_cfg < 0 uses the cost model.
+// (0 = never, 101 = whenever the last round is not full); force_cfg < 0, or a configuration
+// that cannot run this epilogue, leaves the choice to the cost model.
 int launch_gemm(const bf16_t* A, int lda, const bf16_t* W, int M, int N, int K, void* C, int ldc,
                 const void* R, int ldr, int epilogue, float* partial, size_t partial_bytes,
                 uint32_t* counters, int n_counters, int force_cfg, int force_split_pct,
-                hipStream_t st) {
+                const RopeEpilogue* rope, hipStream_t st) {
     if (M <= 0 || N <= 0) return MVLA_OK;
     if (K < 64 || K % 64 != 0 || lda % 8 != 0) return MVLA_EUNSUPPORTED;
     if (epilogue == EPI_SILU_MUL && N % 64 != 0) return MVLA_EUNSUPPORTED;
     if (N % 8 != 0 || ldc % 8 != 0 || (R && ldr % 8 != 0)) return MVLA_EUNSUPPORTED;
-    int best = 0, split_pct = kSplitPct;
-    if (force_cfg >= 0 && force_cfg < kNumCfgs) {
+    if (epilogue == EPI_QKV_ROPE) {
+        if (!rope || !rope->pos || !rope->rc || !rope->rs || rope->S <= 0 || rope->rope_len <= 0)
+            return MVLA_EINVAL;
+        if ((rope->dh != 64 && rope->dh != 128) || rope->D % rope->dh != 0) return MVLA_EUNSUPPORTED;
+        if (N != 3 * rope->D && N != 2 * rope->D) return MVLA_EINVAL;
+        if ((N == 3 * rope->D) != (rope->vt != nullptr)) return MVLA_EINVAL;
+        if (M % rope->S != 0 || rope->S_pad < rope->S || rope->S_pad % 8 != 0) return MVLA_EINVAL;
+    }
+    int best = -1, split_pct = kSplitPct;
+    if (force_cfg >= 0 && force_cfg < kNumCfgs && cfg_runs(kCfgs[force_cfg], epilogue, rope)) {
         best = force_cfg;
         split_pct = force_split_pct;
     } else {
-        float best_us = estimate_us(kCfgs[0], M, N, K);
-        for (int i = 1; i < kNumCfgs; ++i) {
+        float best_us = 0.f;
+        for (int i = 0; i < kNumCfgs; ++i) {
+            if (!cfg_runs(kCfgs[i], epilogue, rope)) continue;
             const float t = estimate_us(kCfgs[i], M, N, K);
-            if (t < best_us) {
+            if (best < 0 || t < best_us) {
                 best_us = t;
                 best = i;
             }
         }
+        if (best < 0) return MVLA_EUNSUPPORTED;
     }
+    const RopeEpilogue rope_args = rope ? *rope : RopeEpilogue{};
 #define MVLA_ARGS A, lda, W, M, N, K, C, ldc, R, ldr, epilogue, kCfgs[best].slots_per_cu, split_pct, \
-                  partial, partial_bytes, counters, n_counters, st
+                  partial, partial_bytes, counters, n_counters, rope_args, st
     switch (best) {
         case 0: return launch_cfg<256, 256, 64, 2, 4, 2>(MVLA_ARGS);
         case 1: return launch_cfg<256, 128, 64, 4, 2, 3>(MVLA_ARGS);
         case 2: return launch_cfg<128, 128, 64, 2, 2, 2>(MVLA_ARGS);
         case 3: return launch_cfg<128, 128, 64, 4, 2, 3>(MVLA_ARGS);
-        case 4: return launch_cfg<288, 192, 64, 3, 2, 2>(MVLA_ARGS);
-        case 5: return launch_cfg<256, 256, 64, 2, 2, 2>(MVLA_ARGS);
-        case 6: return launch_cfg<192, 128, 64, 2, 4, 3>(MVLA_ARGS);
+        case 4: return launch_cfg<256, 256, 64, 2, 2, 2>(MVLA_ARGS);
+        case 5: return launch_cfg<192, 128, 64, 2, 4, 3>(MVLA_ARGS);
         default: return launch_cfg<288, 192, 64, 2, 2, 2>(MVLA_ARGS);
     }
 #undef MVLA_ARGS

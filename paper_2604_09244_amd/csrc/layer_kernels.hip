@@ -1,5 +1,6 @@
 // Element-wise and small kernels of the decoder layer on gfx950: RMSNorm,
-// rotary table, rotary embedding + V transpose, and the language-query scoring
+// rotary table (the rotation itself and the V transpose happen in the q/k/v
+// projection's epilogue, gemm.hip), and the language-query scoring
 // probabilities (paper Sec. 3.2: the attention rows that salience is read from).
 #include "common.h"
 #include "mfma.h"
@@ -119,132 +120,6 @@ int launch_rope_table(double base, int rope_len, int dh, float* c, float* s, hip
     if (n <= 0) return MVLA_OK;
     hipLaunchKernelGGL(rope_table_kernel, dim3((n + 255) / 256), dim3(256), 0, st, base, rope_len,
                        dh / 2, c, s);
-    MVLA_HIP_CHECK(hipGetLastError());
-    return MVLA_OK;
-}
-
-// ---------------------------------------------------------------------------
-// Rotary embedding of q and k in place (rotate-half pairing: element i with
-// i + dh/2) and transposition of v into vt[b, h, d, s] (row length S_pad,
-// zero beyond S), which makes the keys the contiguous axis of the P*V operand.
-// One workgroup handles 64 tokens of one head.
-// ---------------------------------------------------------------------------
-constexpr int ROPE_THREADS = 256;
-constexpr int ROPE_TOK = 64;
-
-template <int DH>
-__global__ __launch_bounds__(ROPE_THREADS) void rope_split_kernel(
-    bf16_t* __restrict__ qkv, const int32_t* __restrict__ pos, const float* __restrict__ rc,
-    const float* __restrict__ rs, int rope_len, int S, int H, int S_pad, int n_sections,
-    bf16_t* __restrict__ vt) {
-    constexpr int HALF = DH / 2;
-    constexpr int CH = HALF / 8;  // 16-byte chunks per half row
-    const int s0 = blockIdx.x * ROPE_TOK, h = blockIdx.y, b = blockIdx.z;
-    const int D = H * DH, ld = n_sections * D;
-    const int tid = threadIdx.x;
-
-    // v (section 2): the loads go out first so that their latency overlaps the q/k work
-    constexpr int V_IT = ROPE_TOK * (DH / 8) / ROPE_THREADS;
-    uint4 vreg[V_IT];
-    if (n_sections == 3) {
-#pragma unroll
-        for (int u = 0; u < V_IT; ++u) {
-            const int item = tid + u * ROPE_THREADS;
-            const int t = item / (DH / 8), c = item % (DH / 8);
-            const int s = s0 + t;
-            vreg[u] = make_uint4(0, 0, 0, 0);
-            if (s < S) vreg[u] = *reinterpret_cast<const uint4*>(qkv + ((size_t)b * S + s) * ld + 2 * D +
-                                                                 h * DH + c * 8);
-        }
-    }
-
-    // q (section 0) and k (section 1): all of a thread's items are loaded before the first is
-    // stored (the rotation is in place, so the compiler cannot move a load above a store)
-    constexpr int QK_IT = 2 * ROPE_TOK * CH / ROPE_THREADS;
-    static_assert(2 * ROPE_TOK * CH % ROPE_THREADS == 0, "");
-    uint4 va[QK_IT], vb[QK_IT];
-    float4 c0[QK_IT], c1[QK_IT], s0v[QK_IT], s1v[QK_IT];
-    bf16_t* basep[QK_IT];
-#pragma unroll
-    for (int u = 0; u < QK_IT; ++u) {
-        const int item = tid + u * ROPE_THREADS;
-        const int sec = item / (ROPE_TOK * CH);
-        const int rem = item % (ROPE_TOK * CH);
-        const int t = rem / CH, c = rem % CH;
-        const int s = min(s0 + t, S - 1);   // rows past the end: loaded, not stored
-        const size_t m = (size_t)b * S + s;
-        int p = pos[m];
-        p = min(max(p, 0), rope_len - 1);
-        basep[u] = qkv + m * ld + sec * D + h * DH + c * 8;
-        va[u] = *reinterpret_cast<uint4*>(basep[u]);
-        vb[u] = *reinterpret_cast<uint4*>(basep[u] + HALF);
-        c0[u] = *reinterpret_cast<const float4*>(rc + (size_t)p * HALF + c * 8);
-        c1[u] = *reinterpret_cast<const float4*>(rc + (size_t)p * HALF + c * 8 + 4);
-        s0v[u] = *reinterpret_cast<const float4*>(rs + (size_t)p * HALF + c * 8);
-        s1v[u] = *reinterpret_cast<const float4*>(rs + (size_t)p * HALF + c * 8 + 4);
-    }
-#pragma unroll
-    for (int u = 0; u < QK_IT; ++u) {
-        const int item = tid + u * ROPE_THREADS;
-        const int t = (item % (ROPE_TOK * CH)) / CH;
-        if (s0 + t >= S) continue;
-        const float cs[8] = {c0[u].x, c0[u].y, c0[u].z, c0[u].w, c1[u].x, c1[u].y, c1[u].z, c1[u].w};
-        const float sn[8] = {s0v[u].x, s0v[u].y, s0v[u].z, s0v[u].w,
-                             s1v[u].x, s1v[u].y, s1v[u].z, s1v[u].w};
-        uint32_t aw[4] = {va[u].x, va[u].y, va[u].z, va[u].w};
-        uint32_t bw[4] = {vb[u].x, vb[u].y, vb[u].z, vb[u].w};
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float a0 = __uint_as_float(aw[i] << 16), a1 = __uint_as_float(aw[i] & 0xFFFF0000u);
-            const float b0 = __uint_as_float(bw[i] << 16), b1 = __uint_as_float(bw[i] & 0xFFFF0000u);
-            const float ra0 = a0 * cs[2 * i] - b0 * sn[2 * i];
-            const float rb0 = b0 * cs[2 * i] + a0 * sn[2 * i];
-            const float ra1 = a1 * cs[2 * i + 1] - b1 * sn[2 * i + 1];
-            const float rb1 = b1 * cs[2 * i + 1] + a1 * sn[2 * i + 1];
-            aw[i] = pack_bf16x2(ra0, ra1);
-            bw[i] = pack_bf16x2(rb0, rb1);
-        }
-        *reinterpret_cast<uint4*>(basep[u]) = make_uint4(aw[0], aw[1], aw[2], aw[3]);
-        *reinterpret_cast<uint4*>(basep[u] + HALF) = make_uint4(bw[0], bw[1], bw[2], bw[3]);
-    }
-    if (n_sections < 3) return;
-
-    // [64 tokens x DH] -> LDS -> vt[d][s0 .. s0+63]
-    __shared__ bf16_t tile[ROPE_TOK][DH + 2];  // +2: odd word stride, conflict-free column reads
-#pragma unroll
-    for (int u = 0; u < V_IT; ++u) {
-        const int item = tid + u * ROPE_THREADS;
-        const int t = item / (DH / 8), c = item % (DH / 8);
-        uint32_t* dst = reinterpret_cast<uint32_t*>(&tile[t][c * 8]);
-        dst[0] = vreg[u].x; dst[1] = vreg[u].y; dst[2] = vreg[u].z; dst[3] = vreg[u].w;
-    }
-    __syncthreads();
-    bf16_t* vrow = vt + ((size_t)(b * H + h) * DH) * S_pad + s0;
-    for (int item = tid; item < DH * (ROPE_TOK / 8); item += ROPE_THREADS) {
-        const int d = item / (ROPE_TOK / 8), c = item % (ROPE_TOK / 8);
-        uint32_t w[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            w[i] = (uint32_t)tile[c * 8 + 2 * i][d] | ((uint32_t)tile[c * 8 + 2 * i + 1][d] << 16);
-        *reinterpret_cast<uint4*>(vrow + (size_t)d * S_pad + c * 8) =
-            make_uint4(w[0], w[1], w[2], w[3]);
-    }
-}
-
-int launch_rope_split(bf16_t* qkv, const int32_t* pos, const float* rc, const float* rs,
-                      int rope_len, int B, int S, int H, int dh, int S_pad, bf16_t* vt,
-                      hipStream_t st) {
-    if (B <= 0 || S <= 0) return MVLA_OK;
-    const int n_sections = vt ? 3 : 2;
-    dim3 grid((S + ROPE_TOK - 1) / ROPE_TOK, H, B);
-    if (dh == 128)
-        hipLaunchKernelGGL(rope_split_kernel<128>, grid, dim3(ROPE_THREADS), 0, st, qkv, pos, rc,
-                           rs, rope_len, S, H, S_pad, n_sections, vt);
-    else if (dh == 64)
-        hipLaunchKernelGGL(rope_split_kernel<64>, grid, dim3(ROPE_THREADS), 0, st, qkv, pos, rc,
-                           rs, rope_len, S, H, S_pad, n_sections, vt);
-    else
-        return MVLA_EUNSUPPORTED;
     MVLA_HIP_CHECK(hipGetLastError());
     return MVLA_OK;
 }

@@ -283,7 +283,7 @@ def test_action_iteration_sequence(ctx):
     assert min(overlaps) > 0.9, overlaps
 
 
-@pytest.mark.parametrize("cfg_id", range(8))
+@pytest.mark.parametrize("cfg_id", range(7))
 @pytest.mark.parametrize("split_pct", [0, 101])
 def test_every_projection_kernel_configuration(ctx, cfg_id, split_pct):
     """Each tile configuration, with and without the K-split, forced for all four projections of
