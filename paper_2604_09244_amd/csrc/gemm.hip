@@ -120,7 +120,7 @@ template <int BM, int BN, int BK, int WM, int WN, int NS, int EPI>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ W, int M, int N, int K,
     void* __restrict__ Cv, int ldc, const void* __restrict__ Rv, int ldr, GemmPlan plan,
-    float* __restrict__ partial, uint32_t* __restrict__ counters, RopeEpilogue rope) {
+    float* __restrict__ partial, uint32_t* __restrict__ counters, RopeEpilogue ea_rope) {
     constexpr int NT = WM * WN * 64;
     constexpr int CPR = BK / 8;             // 16-byte chunks per LDS row
     constexpr int KS = BK / 16;             // MFMA k-steps per slab
@@ -447,13 +447,29 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
         static_assert(RP % 16 == 0, "row groups of 8 come in pairs");
         constexpr int ITEMS = RP * OUT_COLS / 8;                      // 8-column items per pass
         float* tile = reinterpret_cast<float*>(lds);
+        const RopeEpilogue& rope = ea_rope;
+        const int ea_rope_D = EPI == EPI_QKV_ROPE ? rope.D : 0;
         const int out_n0 = EPI == EPI_SILU_MUL ? n0 / 2 : n0;
         const int out_N = EPI == EPI_SILU_MUL ? N / 2 : N;
 #pragma unroll 1
         for (int pass = 0; pass < PASSES; ++pass) {
-            __syncthreads();   // previous readers of the LDS (fragments or the last pass) are done
             // first tile row of the pass (with overlapping wave rows the last pass starts early)
             const int prow0 = PASSES == 1 ? 0 : min(pass * TM, BM - TM);
+            // q/k rotation: the position ids of this thread's items of the pass, fetched while
+            // the tile is laid down (items: 8 columns of a half head, BN/16 per row)
+            constexpr int PER_ROW = BN / 16;
+            constexpr int QB = (FM * FN >= 8 && WM * WN >= 8) ? 2 : 4;   // items whose table rows fly together
+            constexpr int NB = (RP * PER_ROW + QB * NT - 1) / (QB * NT);
+            constexpr bool PREFETCH = EPI == EPI_QKV_ROPE && QB == 4;   // (registers to spare)
+            int pos_pre[PREFETCH ? NB * QB : 1];
+            if (PREFETCH && n0 < 2 * ea_rope_D) {
+#pragma unroll
+                for (int q = 0; q < NB * QB; ++q) {
+                    const int row = m0 + prow0 + min((tid + q * NT) / PER_ROW, RP - 1);
+                    pos_pre[q] = rope.pos[min(row, M - 1)];
+                }
+            }
+            __syncthreads();   // previous readers of the LDS (fragments or the last pass) are done
             if (PASSES == 1 || wm == pass) {
 #pragma unroll
                 for (int i = 0; i < FM; ++i)
@@ -473,75 +489,118 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
                 const int DH = rope.dh, HALF = DH >> 1, CPH = HALF >> 3;   // 16-byte chunks per half head
                 if (n0 < 2 * rope.D) {
                     // q or k columns: every item is 8 columns of the first half of a head and
-                    // their partners dh/2 further on (tiles hold whole heads: BN % dh == 0)
+                    // their partners dh/2 further on (tiles hold whole heads: BN % dh == 0; a row
+                    // has BN/16 items whatever dh is).  Items are taken a few at a time so that the
+                    // table rows of a batch are in flight together.
                     bf16_t* Cb = static_cast<bf16_t*>(Cv);
-                    const int per_row = (BN / DH) * CPH;
-#pragma unroll 1
-                    for (int it = tid; it < RP * per_row; it += NT) {
-                        const int r = it / per_row, rest = it - r * per_row;
-                        const int col = (rest / CPH) * DH + (rest % CPH) * 8;   // column in the tile
-                        const int row = m0 + prow0 + r;
-                        if (row >= M || n0 + col >= N) continue;
-                        if (PASSES > 1 && prow0 + r < pass * TM) continue;
-                        const int p = min(max(rope.pos[row], 0), rope.rope_len - 1);
-                        const float* ta = tile + r * LDT + col;
-                        const float4 a0 = *reinterpret_cast<const float4*>(ta);
-                        const float4 a1 = *reinterpret_cast<const float4*>(ta + 4);
-                        const float4 b0 = *reinterpret_cast<const float4*>(ta + HALF);
-                        const float4 b1 = *reinterpret_cast<const float4*>(ta + HALF + 4);
-                        const size_t toff = (size_t)p * HALF + (rest % CPH) * 8;
-                        const float4 c0 = *reinterpret_cast<const float4*>(rope.rc + toff);
-                        const float4 c1 = *reinterpret_cast<const float4*>(rope.rc + toff + 4);
-                        const float4 s0 = *reinterpret_cast<const float4*>(rope.rs + toff);
-                        const float4 s1 = *reinterpret_cast<const float4*>(rope.rs + toff + 4);
-                        const float a[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
-                        const float b[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
-                        const float cs[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
-                        const float sn[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
-                        uint32_t wa[4], wb[4];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            wa[e] = pack_bf16x2(a[2 * e] * cs[2 * e] - b[2 * e] * sn[2 * e],
-                                                a[2 * e + 1] * cs[2 * e + 1] - b[2 * e + 1] * sn[2 * e + 1]);
-                            wb[e] = pack_bf16x2(b[2 * e] * cs[2 * e] + a[2 * e] * sn[2 * e],
-                                                b[2 * e + 1] * cs[2 * e + 1] + a[2 * e + 1] * sn[2 * e + 1]);
+                    for (int jb = 0; jb < NB; ++jb) {
+                        const int it0 = tid + jb * QB * NT;
+                        int r[QB], col[QB], c8[QB], p[QB];
+                        bool ok[QB];
+#pragma unroll
+                        for (int u = 0; u < QB; ++u) {
+                            const int it = it0 + u * NT;
+                            r[u] = min(it / PER_ROW, RP - 1);
+                            const int rest = it % PER_ROW;
+                            c8[u] = (rest % CPH) * 8;
+                            col[u] = (rest / CPH) * DH + c8[u];   // column in the tile
+                            const int row = m0 + prow0 + r[u];
+                            ok[u] = it < RP * PER_ROW && row < M && n0 + col[u] < N &&
+                                    !(PASSES > 1 && prow0 + r[u] < pass * TM);
+                            p[u] = PREFETCH ? pos_pre[PREFETCH ? jb * QB + u : 0] : rope.pos[min(row, M - 1)];
                         }
-                        bf16_t* dst = Cb + (size_t)row * ldc + n0 + col;
-                        *reinterpret_cast<uint4*>(dst) = make_uint4(wa[0], wa[1], wa[2], wa[3]);
-                        *reinterpret_cast<uint4*>(dst + HALF) = make_uint4(wb[0], wb[1], wb[2], wb[3]);
+                        float4 cs[QB][2], sn[QB][2];
+#pragma unroll
+                        for (int u = 0; u < QB; ++u) {
+                            const size_t toff = (size_t)min(max(p[u], 0), rope.rope_len - 1) * HALF + c8[u];
+                            cs[u][0] = *reinterpret_cast<const float4*>(rope.rc + toff);
+                            cs[u][1] = *reinterpret_cast<const float4*>(rope.rc + toff + 4);
+                            sn[u][0] = *reinterpret_cast<const float4*>(rope.rs + toff);
+                            sn[u][1] = *reinterpret_cast<const float4*>(rope.rs + toff + 4);
+                        }
+#pragma unroll
+                        for (int u = 0; u < QB; ++u) {
+                            if (!ok[u]) continue;
+                            const float* ta = tile + r[u] * LDT + col[u];
+                            const float4 a0 = *reinterpret_cast<const float4*>(ta);
+                            const float4 a1 = *reinterpret_cast<const float4*>(ta + 4);
+                            const float4 b0 = *reinterpret_cast<const float4*>(ta + HALF);
+                            const float4 b1 = *reinterpret_cast<const float4*>(ta + HALF + 4);
+                            const float a[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+                            const float b[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+                            const float c[8] = {cs[u][0].x, cs[u][0].y, cs[u][0].z, cs[u][0].w,
+                                                cs[u][1].x, cs[u][1].y, cs[u][1].z, cs[u][1].w};
+                            const float sv[8] = {sn[u][0].x, sn[u][0].y, sn[u][0].z, sn[u][0].w,
+                                                 sn[u][1].x, sn[u][1].y, sn[u][1].z, sn[u][1].w};
+                            uint32_t wa[4], wb[4];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                wa[e] = pack_bf16x2(a[2 * e] * c[2 * e] - b[2 * e] * sv[2 * e],
+                                                    a[2 * e + 1] * c[2 * e + 1] - b[2 * e + 1] * sv[2 * e + 1]);
+                                wb[e] = pack_bf16x2(b[2 * e] * c[2 * e] + a[2 * e] * sv[2 * e],
+                                                    b[2 * e + 1] * c[2 * e + 1] + a[2 * e + 1] * sv[2 * e + 1]);
+                            }
+                            bf16_t* dst = Cb + (size_t)(m0 + prow0 + r[u]) * ldc + n0 + col[u];
+                            *reinterpret_cast<uint4*>(dst) = make_uint4(wa[0], wa[1], wa[2], wa[3]);
+                            *reinterpret_cast<uint4*>(dst + HALF) = make_uint4(wb[0], wb[1], wb[2], wb[3]);
+                        }
                     }
                 } else {
-                    // v columns, transposed: an item is one column and 8 consecutive rows (tokens).
-                    // Lanes run over 32 columns x 2 row groups: LDS reads without bank conflicts,
-                    // 32 bytes of a vt row per column and instruction.
-                    const int H = rope.D / DH;
+                    // v columns, transposed into vt[b, h, d, s]: an item is one column and one
+                    // group of 8 tokens aligned in s (one 16-byte store).  Groups are found from
+                    // candidate rows 8 apart; where a sample does not start on a multiple of 8 rows
+                    // they straddle the candidates, and the groups cut by the ends of the pass are
+                    // stored token by token by the two passes (or tiles) that hold their rows.
+                    // Lanes run over 32 columns x 2 groups: LDS reads without bank conflicts.
+                    const int H = rope.D / DH, S = rope.S;
+                    const int g_base = m0 + prow0;                                  // global row of LDS row 0
+                    const int g_lo = m0 + (PASSES > 1 ? max(prow0, pass * TM) : 0);  // rows this pass owns
+                    const int g_hi = min(g_base + RP, M);
+                    const int step = min(8, S);           // samples shorter than 8 tokens: one candidate each
+                    const int k_items = ((RP + step - 1) / step + 2) & ~1;   // + the clamped tail, kept even
 #pragma unroll 1
-                    for (int it = tid; it < BN * (RP / 8); it += NT) {
-                        const int d = (it >> 1) % BN, g = ((it >> 1) / BN) * 2 + (it & 1);
-                        const int r0 = g * 8, row0 = m0 + prow0 + r0;
-                        if (row0 >= M || n0 + d >= N) continue;
-                        if (PASSES > 1 && prow0 + r0 < pass * TM) continue;
-                        float v[8];
-#pragma unroll
-                        for (int i = 0; i < 8; ++i) v[i] = tile[(r0 + i) * LDT + d];
+                    for (int it = tid; it < BN * k_items; it += NT) {
+                        const int d = (it >> 1) % BN, k = ((it >> 1) / BN) * 2 + (it & 1);
+                        if (g_lo >= g_hi || n0 + d >= N) continue;
+                        const int cand = min(g_lo + step * k, g_hi - 1);
+                        const int bs = cand / S;
+                        int s_al = (cand - bs * S) & ~7;
+                        if (k > 0) {   // the same group as the candidate before (only at the clamped tail)?
+                            const int prev = min(g_lo + step * (k - 1), g_hi - 1) - bs * S;
+                            if (prev >= 0 && (prev & ~7) == s_al) continue;
+                        }
                         const int vcol = n0 - 2 * rope.D + d, hd = vcol / DH, dd = vcol - hd * DH;
-                        const int bs = row0 / rope.S, s_first = row0 - bs * rope.S;
-                        if ((s_first & 7) == 0 && s_first + 8 < rope.S) {
-                            // 8 tokens of one sample, its last token not among them
-                            bf16_t* dst = rope.vt + ((size_t)(bs * H + hd) * DH + dd) * rope.S_pad + s_first;
-                            *reinterpret_cast<uint4*>(dst) =
-                                make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]),
-                                           pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
-                        } else {
+                        bf16_t* dst = rope.vt + ((size_t)(bs * H + hd) * DH + dd) * rope.S_pad;
+                        // A sample's short last group can lie between two candidates: the item of
+                        // the group before it takes it along.
+                        const int n_groups = (s_al + 8 < S && cand + 8 >= (bs + 1) * S) ? 2 : 1;
 #pragma unroll 1
+                        for (int rep = 0; rep < n_groups; ++rep, s_al += 8) {
+                            const int g0 = bs * S + s_al;        // global row of the group's first token
+                            const int n_tok = min(8, S - s_al);  // tokens of the group that exist
+                            float v[8];
+#pragma unroll
                             for (int i = 0; i < 8; ++i) {
-                                const int row = row0 + i;
-                                if (row >= M) break;
-                                const int b2 = row / rope.S, s2 = row - b2 * rope.S;
-                                bf16_t* dst = rope.vt + ((size_t)(b2 * H + hd) * DH + dd) * rope.S_pad;
-                                dst[s2] = (bf16_t)(pack_bf16x2(v[i], 0.f) & 0xFFFFu);
-                                if (s2 == rope.S - 1)   // the sample's last token also clears the padding
-                                    for (int z = rope.S; z < rope.S_pad; ++z) dst[z] = 0;
+                                const int g = g0 + i;
+                                v[i] = (i < n_tok && g >= g_lo && g < g_hi) ? tile[(g - g_base) * LDT + d] : 0.f;
+                            }
+                            if (g0 >= g_lo && g0 + n_tok <= g_hi) {
+                                *reinterpret_cast<uint4*>(dst + s_al) =
+                                    make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]),
+                                               pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
+                                if (s_al + 8 >= S)   // the sample's last token: clear the rest of the padding
+                                    for (int z = s_al + 8; z < rope.S_pad; z += 8)
+                                        *reinterpret_cast<uint4*>(dst + z) = make_uint4(0, 0, 0, 0);
+                            } else {
+#pragma unroll 1
+                                for (int i = 0; i < n_tok; ++i) {
+                                    const int g = g0 + i;
+                                    if (g < g_lo || g >= g_hi) continue;
+                                    dst[s_al + i] = (bf16_t)(pack_bf16x2(v[i], 0.f) & 0xFFFFu);
+                                    if (s_al + i == S - 1)
+                                        for (int z = S; z < rope.S_pad; ++z) dst[z] = 0;
+                                }
                             }
                         }
                     }
