@@ -13,7 +13,8 @@
 // of step s.
 //
 // Work split.  A workgroup owns a BM x BN tile; its waves own (BM/WM) x (BN/WN)
-// sub-tiles of 32x32 MFMA blocks.  Tiles that fill whole rounds of the chip
+// sub-tiles of 32x32 MFMA blocks (wave rows overlap by a block where the 32-row
+// blocks do not divide).  Tiles that fill whole rounds of the chip
 // are computed start to finish by one workgroup.  The tiles of the last,
 // partial round are cut along K into equal ranges of k-iterations handed out
 // contiguously to the otherwise idle CUs; the pieces of a tile meet in an fp32
@@ -21,7 +22,9 @@
 // adds them up in fixed piece order and runs the epilogue, so results do not
 // depend on timing.
 //
-// Epilogues: plain bf16 store; residual add (bf16 residual in, fp32 out -- or
+// Epilogues: the q/k/v projection (q and k columns rotated by the row's position
+// on the fp32 accumulators and stored as bf16, v columns stored transposed for
+// the attention kernel); residual add (bf16 residual in, fp32 out -- or
 // fp32 residual in, bf16 out: the residual stream between the two halves of a
 // layer stays in fp32, so it is rounded to bf16 once per layer); SiLU(gate)*up,
 // where gate and up columns alternate in blocks of 32 (one 64-column group holds a
