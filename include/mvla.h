@@ -263,7 +263,10 @@ int mvla_rope_table(mvla_ctx* ctx, double base, int rope_len, int dh, float* cos
  * last n_query_tail rows (the language-token queries, Sec. 3.2) to
  * probs_out (device, fp32 [B, H, n_query_tail, S]); key_bias (device, fp32
  * [B, S] or NULL) is added to those scoring logits only, never to the layer's
- * own attention.  n_query_tail == 0: key_bias/probs_out ignored. */
+ * own attention.  n_query_tail == 0: key_bias/probs_out ignored.
+ * This call and the other layer and pruning calls only enqueue kernels on the
+ * context's stream (no memset, no synchronisation, no allocation): with the
+ * per-kernel timing off they may be recorded into a HIP graph and replayed. */
 int mvla_prefill_layer(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weights* w,
                        const void* x, const int32_t* pos, int B, int S, void* y, int n_query_tail,
                        const float* key_bias, float* probs_out);
