@@ -123,7 +123,7 @@ template <int BM, int BN, int BK, int WM, int WN, int NS, int EPI>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
     const bf16_t* __restrict__ A, int lda, const bf16_t* __restrict__ W, int M, int N, int K,
     void* __restrict__ Cv, int ldc, const void* __restrict__ Rv, int ldr, GemmPlan plan,
-    float* __restrict__ partial, uint32_t* __restrict__ counters, RopeEpilogue ea_rope) {
+    float* __restrict__ partial, uint32_t* __restrict__ counters, RopeEpilogue rope) {
     constexpr int NT = WM * WN * 64;
     constexpr int CPR = BK / 8;             // 16-byte chunks per LDS row
     constexpr int KS = BK / 16;             // MFMA k-steps per slab
@@ -450,8 +450,6 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
         static_assert(RP % 16 == 0, "row groups of 8 come in pairs");
         constexpr int ITEMS = RP * OUT_COLS / 8;                      // 8-column items per pass
         float* tile = reinterpret_cast<float*>(lds);
-        const RopeEpilogue& rope = ea_rope;
-        const int ea_rope_D = EPI == EPI_QKV_ROPE ? rope.D : 0;
         const int out_n0 = EPI == EPI_SILU_MUL ? n0 / 2 : n0;
         const int out_N = EPI == EPI_SILU_MUL ? N / 2 : N;
 #pragma unroll 1
@@ -465,7 +463,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
             constexpr int NB = (RP * PER_ROW + QB * NT - 1) / (QB * NT);
             constexpr bool PREFETCH = EPI == EPI_QKV_ROPE && QB == 4;   // (registers to spare)
             int pos_pre[PREFETCH ? NB * QB : 1];
-            if (PREFETCH && n0 < 2 * ea_rope_D) {
+            if (PREFETCH && n0 < 2 * rope.D) {
 #pragma unroll
                 for (int q = 0; q < NB * QB; ++q) {
                     const int row = m0 + prow0 + min((tid + q * NT) / PER_ROW, RP - 1);
