@@ -25,9 +25,10 @@ constexpr int ATT_QT = 128;  // queries per workgroup (32 per wave)
 constexpr int ATT_KT = 64;   // keys per tile
 
 // untracked direct global -> LDS copy (see gemm.hip): order consumers behind att_wait_vm + barrier
-__device__ __forceinline__ void att_dma16(const void* g, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr),
-                 "v"(g)
+// (address = wave-uniform base + per-lane unsigned 32-bit byte offset)
+__device__ __forceinline__ void att_dma16(const void* base, uint32_t off, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr),
+                 "v"(off), "s"(base)
                  : "memory");
 }
 template <int N>
@@ -68,6 +69,12 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_kernel(
         const bf16_t* src = q + ((size_t)b * S + min(my_q, S - 1)) * ld + h * DH + fg * 8;
 #pragma unroll
         for (int st = 0; st < STEPS; ++st) qf[st] = *reinterpret_cast<const uint4*>(src + st * 16);
+        // The fragments are pinned here, before any direct load is in flight: otherwise the
+        // compiler's waits for these loads sit inside the key loop, where they would also wait
+        // for the (untracked) direct loads of the next tile.
+#pragma unroll
+        for (int st = 0; st < STEPS; ++st)
+            asm volatile("" : "+v"(qf[st].x), "+v"(qf[st].y), "+v"(qf[st].z), "+v"(qf[st].w));
     }
 
     const int last_row = min(q0 + ATT_QT, S) - 1;
@@ -75,22 +82,24 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_kernel(
 
     // direct-load mapping: op i of this thread covers slot i*256 + tid of the K (or V^T) tile
     const uint32_t lds_base = (uint32_t)(uintptr_t)lds;
-    const bf16_t* k_src[K_LD];
+    // (bases are wave-uniform, the per-lane parts 32-bit byte offsets within one sample's keys
+    // or one head's V^T: fewer address registers than one pointer per op)
+    const bf16_t* k_base = k + (size_t)b * S * ld + h * DH;
+    const bf16_t* v_base = vt + (size_t)(b * H + h) * DH * S_pad;
     int k_row[K_LD];
-    uint32_t k_lds[K_LD];
+    uint32_t k_off[K_LD], k_lds[K_LD];
 #pragma unroll
     for (int i = 0; i < K_LD; ++i) {
         const int sl = i * ATT_THREADS + tid, row = sl / CPR, ch = (sl % CPR) ^ att_swz<CPR>(row);
         k_row[i] = row;
-        k_src[i] = k + (size_t)b * S * ld + h * DH + ch * 8;
+        k_off[i] = (uint32_t)ch * 16u;
         k_lds[i] = __builtin_amdgcn_readfirstlane(lds_base + (uint32_t)(i * ATT_THREADS + wave * 64) * 16u);
     }
-    const bf16_t* v_src[V_LD];
-    uint32_t v_lds[V_LD];
+    uint32_t v_off[V_LD], v_lds[V_LD];
 #pragma unroll
     for (int i = 0; i < V_LD; ++i) {
         const int sl = i * ATT_THREADS + tid, row = sl >> 3, ch = (sl & 7) ^ att_swz<8>(row);
-        v_src[i] = vt + ((size_t)(b * H + h) * DH + row) * S_pad + ch * 8;
+        v_off[i] = ((uint32_t)row * (uint32_t)S_pad + (uint32_t)ch * 8u) * 2u;
         v_lds[i] = __builtin_amdgcn_readfirstlane(
             lds_base + (uint32_t)(K_SLOTS + i * ATT_THREADS + wave * 64) * 16u);
     }
@@ -100,10 +109,10 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_kernel(
         const uint32_t soff = (uint32_t)(STG) * STAGE * 16u;                                \
         _Pragma("unroll") for (int i = 0; i < K_LD; ++i) {                                  \
             const int key = min(kt_ * ATT_KT + k_row[i], S - 1);                            \
-            att_dma16(k_src[i] + (size_t)key * ld, k_lds[i] + soff);                        \
+            att_dma16(k_base, k_off[i] + (uint32_t)key * (uint32_t)ld * 2u, k_lds[i] + soff); \
         }                                                                                   \
         _Pragma("unroll") for (int i = 0; i < V_LD; ++i)                                    \
-            att_dma16(v_src[i] + kt_ * ATT_KT, v_lds[i] + soff);                            \
+            att_dma16(v_base + kt_ * ATT_KT, v_off[i], v_lds[i] + soff);                    \
     }
 
     f32x16_t o_acc[DB];
@@ -132,16 +141,38 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_kernel(
             const uint4* Kc = lds + stage * STAGE;
             const uint2* Vc = reinterpret_cast<const uint2*>(Kc + K_SLOTS);
             // ---- S^T for the two 32-key halves of the tile
+            // (all key fragments are read first, then the two independent accumulator chains
+            // alternate, so the matrix core waits neither on LDS latency nor on its own results)
             f32x16_t s_acc[2];
+            uint4 kf[2][STEPS];
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
+            for (int st = 0; st < STEPS; ++st)
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const int row = t * 32 + fr;
+                    kf[t][st] = Kc[row * CPR + ((st * 2 + fg) ^ att_swz<CPR>(row))];
+                }
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) s_acc[t][v] = 0.f;
-                const int row = t * 32 + fr;
 #pragma unroll
-                for (int st = 0; st < STEPS; ++st) {
-                    const uint4 kf = Kc[row * CPR + ((st * 2 + fg) ^ att_swz<CPR>(row))];
-                    s_acc[t] = mfma32(kf, qf[st], s_acc[t]);
+            for (int st = 0; st < STEPS; ++st)
+#pragma unroll
+                for (int t = 0; t < 2; ++t) s_acc[t] = mfma32(kf[t][st], qf[st], s_acc[t]);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2 * STEPS, 0);   // the LDS reads ...
+            __builtin_amdgcn_sched_group_barrier(0x008, 2 * STEPS, 0);   // ... then the MFMAs
+            // V^T fragments of the first two head-dim blocks: in flight during the softmax arithmetic
+            uint4 vfrag[2][4];
+#pragma unroll
+            for (int d = 0; d < 2; ++d) {
+                const int row = min(d, DB - 1) * 32 + fr;
+                const int sw = att_swz<8>(row);
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {
+                    const uint2 lo = Vc[(row * 8 + ((ks * 2) ^ sw)) * 2 + fg];
+                    const uint2 hi = Vc[(row * 8 + ((ks * 2 + 1) ^ sw)) * 2 + fg];
+                    vfrag[d][ks] = make_uint4(lo.x, lo.y, hi.x, hi.y);
                 }
             }
             // ---- scale, (mask,) row max; only tiles that reach the diagonal or the end of the
@@ -192,17 +223,34 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_kernel(
 #pragma unroll
                 for (int v = 0; v < 16; ++v) o_acc[d][v] *= corr;
             // ---- O^T += V^T * P^T ; the A fragment takes keys {4g..4g+3, 8+4g..8+4g+3} of each
-            // 16-key step, matching the key order of the P^T registers
+            // 16-key step, matching the key order of the P^T registers.  The fragments of a pair
+            // of head-dim blocks are read ahead of their MFMAs (the first pair before the softmax
+            // arithmetic above, see vfrag), so the matrix core does not wait on LDS latency.
 #pragma unroll
-            for (int d = 0; d < DB; ++d) {
-                const int row = d * 32 + fr;
-                const int sw = att_swz<8>(row);
+            for (int dp = 0; dp < DB; dp += 2) {
+                uint4 vnext[2][4];
+                if (dp + 2 < DB) {
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks) {
-                    const uint2 lo = Vc[(row * 8 + ((ks * 2) ^ sw)) * 2 + fg];
-                    const uint2 hi = Vc[(row * 8 + ((ks * 2 + 1) ^ sw)) * 2 + fg];
-                    o_acc[d] = mfma32(make_uint4(lo.x, lo.y, hi.x, hi.y), pf[ks], o_acc[d]);
+                    for (int d = 0; d < 2; ++d) {
+                        const int row = (dp + 2 + d) * 32 + fr;
+                        const int sw = att_swz<8>(row);
+#pragma unroll
+                        for (int ks = 0; ks < 4; ++ks) {
+                            const uint2 lo = Vc[(row * 8 + ((ks * 2) ^ sw)) * 2 + fg];
+                            const uint2 hi = Vc[(row * 8 + ((ks * 2 + 1) ^ sw)) * 2 + fg];
+                            vnext[d][ks] = make_uint4(lo.x, lo.y, hi.x, hi.y);
+                        }
+                    }
                 }
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                    for (int d = 0; d < 2; ++d)
+                        if (dp + d < DB) o_acc[dp + d] = mfma32(vfrag[d][ks], pf[ks], o_acc[dp + d]);
+#pragma unroll
+                for (int d = 0; d < 2; ++d)
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks) vfrag[d][ks] = vnext[d][ks];
             }
         }
         stage = stage + 1 == NS ? 0 : stage + 1;
@@ -247,6 +295,9 @@ int launch_attention(const bf16_t* q, const bf16_t* k, int ldqkv, const bf16_t* 
                      int B, int S, int H, int dh, bf16_t* out, int ldo, hipStream_t st) {
     if (B <= 0 || S <= 0) return MVLA_OK;
     if (S_pad % ATT_KT != 0 || S_pad < S) return MVLA_EINVAL;
+    // per-lane byte offsets inside one sample's keys / one head's V^T are 32-bit
+    if ((size_t)S * ldqkv * 2 >= ((size_t)1 << 32) || (size_t)dh * S_pad * 2 >= ((size_t)1 << 32))
+        return MVLA_EUNSUPPORTED;
     // two stages of 32 KiB each: two workgroups per CU, whose waves overlap softmax and MFMA
     if (dh == 128) return launch_att<128, 2>(q, k, ldqkv, vt, S_pad, B, S, H, out, ldo, st);
     if (dh == 64) return launch_att<64, 2>(q, k, ldqkv, vt, S_pad, B, S, H, out, ldo, st);
