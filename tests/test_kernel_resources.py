@@ -57,3 +57,53 @@ def test_attention_kernel_keeps_two_workgroups_per_cu():
     assert att
     for name, v in att.items():
         assert v["ScratchSize"] == 0 and v["Occupancy"] >= 2, (name, v)
+
+
+def _device_assembly(src, tmp_path):
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    if not os.path.exists(hipcc):
+        pytest.skip("hipcc not available")
+    out_s = os.path.join(str(tmp_path), src + ".s")
+    cmd = [hipcc, "-O3", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "-S",
+           "--cuda-device-only", os.path.join(CSRC, src), "-o", out_s]
+    out = subprocess.run(cmd, capture_output=True, text=True, timeout=900)
+    assert out.returncode == 0, out.stderr[-2000:]
+    return open(out_s).read().split("\n")
+
+
+def _waits_among_mfmas(lines, kernel_prefix):
+    """Per kernel: the compiler's own `s_waitcnt vmcnt` (not those written in inline asm) that
+    stand between the first and the last MFMA instruction."""
+    starts = [i for i, l in enumerate(lines) if re.match(r"^%s.*:\s*(;.*)?$" % kernel_prefix, l)]
+    found = {}
+    for a, b in zip(starts, starts[1:] + [len(lines)]):
+        seg = lines[a:b]
+        end = next((i for i, l in enumerate(seg) if "s_endpgm" in l), len(seg))
+        seg = seg[:end]
+        mf = [i for i, l in enumerate(seg) if "v_mfma" in l]
+        if not mf:
+            continue
+        in_asm, waits = False, []
+        for i, l in enumerate(seg):
+            if "ASMSTART" in l:
+                in_asm = True
+            elif "ASMEND" in l:
+                in_asm = False
+            elif not in_asm and "s_waitcnt" in l and "vmcnt" in l and mf[0] <= i <= mf[-1]:
+                waits.append(l.strip())
+        found[lines[a].rstrip(":")] = waits
+    return found
+
+
+@pytest.mark.parametrize("src,prefix,n_kernels", [("gemm.hip", "_ZN4mvla11gemm_kernelI", 28),
+                                                  ("attention.hip", "_ZN4mvla16attention_kernelI", 2)])
+def test_no_compiler_wait_catches_the_direct_loads(src, prefix, n_kernels, tmp_path):
+    """The global->LDS loads are issued from inline asm and waited for explicitly.  A wait the
+    compiler adds for one of ITS loads (a spill reload, an operand fetched before the loop) counts
+    every outstanding load, so inside the MFMA loops it would also wait for the direct loads of
+    the next tile: there must be none between the first and the last MFMA of a kernel."""
+    found = _waits_among_mfmas(_device_assembly(src, tmp_path), prefix)
+    assert len(found) == n_kernels, sorted(found)
+    for name, waits in found.items():
+        assert not waits, (name, waits)
