@@ -141,8 +141,8 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_kernel(
             const uint4* Kc = lds + stage * STAGE;
             const uint2* Vc = reinterpret_cast<const uint2*>(Kc + K_SLOTS);
             // ---- S^T for the two 32-key halves of the tile
-            // (all key fragments are read first, then the two independent accumulator chains
-            // alternate, so the matrix core waits neither on LDS latency nor on its own results)
+            // (the two independent accumulator chains alternate, so the matrix core does not
+            // wait on its own results)
             f32x16_t s_acc[2];
             uint4 kf[2][STEPS];
 #pragma unroll
@@ -160,8 +160,6 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_kernel(
             for (int st = 0; st < STEPS; ++st)
 #pragma unroll
                 for (int t = 0; t < 2; ++t) s_acc[t] = mfma32(kf[t][st], qf[st], s_acc[t]);
-            __builtin_amdgcn_sched_group_barrier(0x100, 2 * STEPS, 0);   // the LDS reads ...
-            __builtin_amdgcn_sched_group_barrier(0x008, 2 * STEPS, 0);   // ... then the MFMAs
             // V^T fragments of the first two head-dim blocks: in flight during the softmax arithmetic
             uint4 vfrag[2][4];
 #pragma unroll
@@ -175,33 +173,30 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_kernel(
                     vfrag[d][ks] = make_uint4(lo.x, lo.y, hi.x, hi.y);
                 }
             }
-            // ---- scale, (mask,) row max; only tiles that reach the diagonal or the end of the
-            // sequence need the mask (wave-uniform test)
+            // ---- (mask,) row max on the raw logits; only tiles that reach the diagonal or the end
+            // of the sequence need the mask (wave-uniform test).  The softmax scale is positive, so
+            // the max commutes with it, and scale and subtraction fuse into one FMA per logit (the
+            // kernel is bound by vector-ALU issue, not by the matrix core).
             float tile_m = -INFINITY;
             if (key0 + ATT_KT - 1 <= qw0 && key0 + ATT_KT <= S) {
 #pragma unroll
                 for (int t = 0; t < 2; ++t)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        s_acc[t][v] *= scale_log2e;
-                        tile_m = fmaxf(tile_m, s_acc[t][v]);
-                    }
+                    for (int v = 0; v < 16; ++v) tile_m = fmaxf(tile_m, s_acc[t][v]);
             } else {
 #pragma unroll
                 for (int t = 0; t < 2; ++t)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const int key = key0 + t * 32 + mfma32_row(v, lane);
-                        const float x =
-                            (key <= my_q && key < S) ? s_acc[t][v] * scale_log2e : -INFINITY;
+                        const float x = (key <= my_q && key < S) ? s_acc[t][v] : -INFINITY;
                         s_acc[t][v] = x;
                         tile_m = fmaxf(tile_m, x);
                     }
             }
             tile_m = fmaxf(tile_m, __shfl_xor(tile_m, 32));
-            const float new_m = fmaxf(run_m, tile_m);   // finite from the first tile on (key 0)
-            const float corr = __builtin_amdgcn_exp2f(run_m - new_m);
-            run_m = new_m;
+            const float new_m = fmaxf(run_m, tile_m);   // (raw logits) finite from the first tile on (key 0)
+            const float neg_m = -new_m * scale_log2e;
             float psum = 0.f;
             uint4 pf[4];  // P^T B-operand fragments: one per 16-key step
 #pragma unroll
@@ -211,17 +206,24 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_kernel(
                     float e[8];
 #pragma unroll
                     for (int i = 0; i < 8; ++i) {
-                        e[i] = __builtin_amdgcn_exp2f(s_acc[t][hh * 8 + i] - new_m);
+                        e[i] = __builtin_amdgcn_exp2f(fmaf(s_acc[t][hh * 8 + i], scale_log2e, neg_m));
                         psum += e[i];
                     }
                     pf[t * 2 + hh] = make_uint4(pack_bf16x2(e[0], e[1]), pack_bf16x2(e[2], e[3]),
                                                 pack_bf16x2(e[4], e[5]), pack_bf16x2(e[6], e[7]));
                 }
-            run_l = run_l * corr + psum;
+            // the running max rarely moves after the first tiles: rescale only when it did for
+            // some query of the wave (a factor of exactly 1 otherwise)
+            if (__any(new_m != run_m)) {
+                const float corr = __builtin_amdgcn_exp2f((run_m - new_m) * scale_log2e);
+                run_l *= corr;
 #pragma unroll
-            for (int d = 0; d < DB; ++d)
+                for (int d = 0; d < DB; ++d)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) o_acc[d][v] *= corr;
+                    for (int v = 0; v < 16; ++v) o_acc[d][v] *= corr;
+                run_m = new_m;
+            }
+            run_l += psum;
             // ---- O^T += V^T * P^T ; the A fragment takes keys {4g..4g+3, 8+4g..8+4g+3} of each
             // 16-key step, matching the key order of the P^T registers.  The fragments of a pair
             // of head-dim blocks are read ahead of their MFMAs (the first pair before the softmax
