@@ -297,8 +297,8 @@ int launch_attention(const bf16_t* q, const bf16_t* k, int ldqkv, const bf16_t* 
                      int B, int S, int H, int dh, bf16_t* out, int ldo, hipStream_t st) {
     if (B <= 0 || S <= 0) return MVLA_OK;
     if (S_pad % ATT_KT != 0 || S_pad < S) return MVLA_EINVAL;
-    // per-lane byte offsets inside one sample's keys / one head's V^T are 32-bit
-    if ((size_t)S * ldqkv * 2 >= ((size_t)1 << 32) || (size_t)dh * S_pad * 2 >= ((size_t)1 << 32))
+    // per-lane byte offsets inside one sample's keys / one head's V^T are 32-bit (kept below 2^31)
+    if ((size_t)S * ldqkv * 2 >= ((size_t)1 << 31) || (size_t)dh * S_pad * 2 >= ((size_t)1 << 31))
         return MVLA_EUNSUPPORTED;
     // two stages of 32 KiB each: two workgroups per CU, whose waves overlap softmax and MFMA
     if (dh == 128) return launch_att<128, 2>(q, k, ldqkv, vt, S_pad, B, S, H, out, ldo, st);
