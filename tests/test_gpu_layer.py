@@ -74,6 +74,15 @@ def test_layer_tiny_ragged_lengths(ctx, S):
     _run_layer_case(ctx, wl, 2, S, min(S, 5))
 
 
+@pytest.mark.parametrize("B,S", [(3, 3), (3, 9), (5, 13), (3, 77)])
+def test_layer_tiny_short_and_misaligned_samples(ctx, B, S):
+    """Samples shorter than, or not a multiple of, the 8-token groups in which V is stored
+    transposed: groups straddle tile rows, end early at a sample's last token, or are all there
+    is of a sample."""
+    wl = W.WORKLOADS["tiny"]
+    _run_layer_case(ctx, wl, B, S, min(S, 3))
+
+
 def test_layer_tiny_gathered_positions(ctx):
     wl = W.WORKLOADS["tiny"]
     r = np.random.default_rng(0)
