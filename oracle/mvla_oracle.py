@@ -419,8 +419,11 @@ def candidate_masks(x_hat, score, u, tau_2d=0.08, tau_3d=0.20, bg_drop=0.9,
            (M2D^S1, M3D^S1, M2D^S2, M3D^S2).
     score: float32 [B, P], the patch's attention score that is clustered.
     u    : float32 [B, P], uniform draws in [0, 1) for the background drop.
-    Decisions compare float32 values with float32 thresholds; the two
-    baselines are float64 means over the sample's patches.
+    The indicators and the rule constants are float32 data (that is how they
+    are handed over: Algorithm 1's tau = 0.08 / 0.20 and the other constants
+    reach either side as the float32 nearest to the decimal), so a threshold
+    decision compares the float32 indicator with that float32 constant; the
+    two baselines are float64 means over the sample's patches.
     Readings where the text gives no number: clusters are named by the order
     of their centres (lowest = background, middle = robot, highest = object);
     "2D far above 0 and 3D near 0" for an object patch is
@@ -504,9 +507,11 @@ def mask_indices(mask2d, mask3d, n_text):
 
 def patch_score(sal, n_patch):
     """Attention score of a patch: its 2D token's salience plus its 3D token's
-    (the summand of Eq. 3), added in float32 as the kernel does."""
-    s = np.asarray(sal, np.float32)
-    return s[:, :n_patch] + s[:, n_patch:2 * n_patch]
+    (the summand of Eq. 3).  Scores cross the library boundary as float32, so
+    the sum of the two float32 inputs is formed exactly (float64 holds it) and
+    rounded once to float32."""
+    s = np.asarray(sal, np.float32).astype(F64)
+    return (s[:, :n_patch] + s[:, n_patch:2 * n_patch]).astype(np.float32)
 
 
 def masked_prefill(x, pos, layers, H, n_patch, n_text, p, t, x_hat_prev, u,

@@ -243,9 +243,15 @@ def test_mask_indices_hand_case_and_structure():
         assert np.array_equal(sel[:33], m2[b] == 1) and np.array_equal(sel[33:66], m3[b] == 1)
 
 
-def test_patch_score_is_the_float32_sum():
-    sal = np.array([[0.1, 0.2, 0.3, 0.4, 9.0]], np.float32)
-    assert np.array_equal(O.patch_score(sal, 2), np.array([[f32(0.1) + f32(0.3), f32(0.2) + f32(0.4)]]))
+def test_patch_score_hand_values_layout_and_single_rounding():
+    """Hand values (all exactly representable): patch p adds column p and column n_patch + p;
+    language columns are ignored.  The second sample pins the rounding: 1 + 2^-24 is a tie
+    between two float32 neighbours and goes to the even one (1.0), 1 + 3 * 2^-25 goes up."""
+    sal = np.array([[0.5, 0.25, 0.125, 2.0, 9.0],
+                    [1.0, 1.0, 2.0 ** -24, 3 * 2.0 ** -25, 7.0]], np.float32)
+    got = O.patch_score(sal, 2)
+    assert got.dtype == np.float32
+    assert got.tolist() == [[0.625, 2.25], [1.0, 1.0 + 2.0 ** -23]]
 
 
 # ---------------------------------------------------------------------------------------------

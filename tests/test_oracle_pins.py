@@ -408,33 +408,40 @@ def test_modality_decompose_special_cases():
     assert np.all(m3 >= 0) and np.all(m3 <= 1 - m2 + 1e-12)
 
 
+def test_compact_hand_case():
+    """Gather of kept rows and their position ids, by hand: row i of the output is row
+    kept_idx[i] of the input, per sample, and position ids travel with their rows."""
+    h = np.arange(2 * 4 * 3, dtype=np.float64).reshape(2, 4, 3)     # h[b, s, :] = 12 b + 3 s + (0, 1, 2)
+    pos = np.array([[10, 11, 12, 13], [20, 21, 22, 23]])
+    kept = np.array([[0, 3], [1, 2]], np.int32)
+    ho, po = O.compact(h, pos, kept)
+    assert ho.tolist() == [[[0, 1, 2], [9, 10, 11]], [[15, 16, 17], [18, 19, 20]]]
+    assert po.tolist() == [[10, 13], [21, 22]]
+    # keeping everything is the identity; an empty keep list gives empty outputs
+    all_idx = np.tile(np.arange(4, dtype=np.int32), (2, 1))
+    ho, po = O.compact(h, pos, all_idx)
+    assert np.array_equal(ho, h) and np.array_equal(po, pos)
+    ho, po = O.compact(h, pos, np.zeros((2, 0), np.int32))
+    assert ho.shape == (2, 0, 3) and po.shape == (2, 0)
+
+
 # ---------------------------------------------------------------- bf16 operand floor
 def test_bf16_operand_rounding_floor():
-    """An fp64 layer whose only inexact steps are bf16 roundings of the eight
-    matrix-core operands and of the output already misses 2e-2 * RMS on the
-    worst element at the 7B shape; this is the floor the GPU tolerance for
-    D = 4096 is derived from (the planted roundings live here, on the CPU)."""
+    """An fp64 layer whose only inexact steps are the bf16 roundings of the eight matrix-core
+    operands and of the output (helpers.bf16_floor_layer) already misses 2e-2 * RMS on the
+    worst element at the 7B shape, while its RMS error is a few 1e-3: the stated bar sits
+    inside the noise of bf16 operands there.  The GPU bar for D = 4096 is this floor, computed
+    per sample and shape, times a stated margin; at D = 256 the same floor is well inside the
+    stated bar, which is why it is asserted as stated there."""
+    from helpers import bf16_floor_layer, layer_errors
     from paper_2604_09244_amd import workloads as W
-    wl = W.WORKLOADS["single_view"]
-    w = {k: v.to(torch.float64).numpy() for k, v in W.layer_weights(wl, 0).items()}
-    x, pos = W.hidden_states(wl, B=1)
-    x, pos = x[0].to(torch.float64).numpy(), pos[0].numpy()
-    S, D = x.shape
-    H, dh = wl.H, wl.dh
-    bf = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(torch.bfloat16).to(torch.float64).numpy()
-    y_ref, _ = O.decoder_layer(x, pos, w, H)
-    u = bf(O.rmsnorm(x, w["g_attn"], 1e-5))
-    q = bf(O.rope_rotate_half((u @ w["wq"].T).reshape(S, H, dh), pos))
-    k = bf(O.rope_rotate_half((u @ w["wk"].T).reshape(S, H, dh), pos))
-    v = bf(u @ w["wv"].T).reshape(S, H, dh)
-    A = bf(O.attention_probs(q, k, True))
-    o = bf(np.matmul(A, v.transpose(1, 0, 2)).transpose(1, 0, 2).reshape(S, D))
-    x1 = x + o @ w["wo"].T
-    t = bf(O.rmsnorm(x1, w["g_mlp"], 1e-5))
-    g, up = t @ w["w_gate"].T, t @ w["w_up"].T
-    y = bf(x1 + bf(g / (1 + np.exp(-g)) * up) @ w["w_down"].T)
-    r = np.sqrt(np.mean(y_ref ** 2))
-    d = np.abs(y - y_ref) / r
-    assert 2e-2 < d.max() < 3e-2
-    assert np.mean(d > 2e-2) < 1e-5
-    assert np.sqrt(np.mean(d * d)) < 5e-3
+    for name, lo, hi in (("single_view", 2e-2, 3e-2), ("tiny", 0.0, 1.2e-2)):
+        wl = W.WORKLOADS[name]
+        w = {k: v.to(torch.float64).numpy() for k, v in W.layer_weights(wl, 0).items()}
+        x, pos = W.hidden_states(wl, B=1)
+        x, pos = x[0].to(torch.float64).numpy(), pos[0].numpy()
+        y_ref, _ = O.decoder_layer(x, pos, w, wl.H)
+        worst, rms_err, over = layer_errors(bf16_floor_layer(x, pos, w, wl.H), y_ref)
+        print(f"[floor] {name}: worst {worst:.4f} x RMS, rms err {rms_err:.5f}, frac > 2e-2 {over:.2e}")
+        assert lo < worst < hi
+        assert over < 1e-5 and rms_err < 5e-3
