@@ -2,22 +2,29 @@
 """Benchmark of the pruned prefill on one MI355X.
 
 One "step" = one whole pruned prefill of a batch: p decoder layers on all S
-tokens (the last one also emits the language-query attention rows), the pruning
+tokens (the last one also scores the language-query attention rows), the pruning
 step (salience, 2D:3D budget, top-k, compaction), L-p layers on the kept tokens.
 Inputs are synthetic, seeded and resident in HBM before timing starts.
 
+Default workload: the largest one a single GPU runs, the keep-ratio sweep
+(32 layers of the 7B shape, B = 16, S = 2624) at keep = 50 %; the other keep
+ratios are timed after the headline and reported under "keep_curve".
+
 Prints ONE JSON line: pruned-prefill tokens/s (input tokens B*S per second of
-whole-path time), ms per step, the pruning step's own cost, the speed-up over
-the unpruned prefill of the same shape, a roofline object for the dominant
-kernel (timed with HIP events on the library's stream), and the CPU oracle
-timed on a bounded sample of the same workload.
+whole-path time), ms per step, the pruning step's own cost against the cost of
+an empty launch, the speed-up over the unpruned prefill of the same shape, a
+roofline object for the dominant kernel (timed with HIP events on the
+library's stream; datasheet peak and the rate a bare matrix-core loop sustains
+on this device), and the CPU oracle timed on a bounded sample of the same
+workload.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
-import re
 import os
+import re
 import sys
 import time
 from collections import defaultdict
@@ -26,36 +33,50 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a
-# plain copy of known size (see profiles/single_view_gemm_gateup_hbm_traffic.txt).  Valid only
-# for the GEMM source and tile configuration the counters were taken with: keyed by kernel shape,
-# with a hash of gemm.hip and the configuration index the set-up measurement must have chosen.
+# HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled
+# by what the same counter shows for a plain copy of known size (see the *_hbm_traffic.txt files
+# under profiles/).  Valid only for the GEMM source and tile configuration the counters were
+# taken with: keyed by kernel shape, with a hash of gemm.hip and the configuration index the
+# set-up measurement must have chosen; anything else reports null.
 MEASURED_TRAFFIC = {
-    ("gemm_gateup", 544, 22016, 4096): (232.8e6, "2b1d4d053cd5a123", 6),
 }
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
 
-def gemm_roofline(M, N, K, out_cols, seconds):
+def gemm_roofline(M, N, K, out_cols, seconds, measured=None):
     """C[M,N] = A[M,K] W[N,K]^T in bf16: algorithmic flops and bytes of one launch."""
     flops = 2.0 * M * N * K
     bytes_ = 2.0 * (N * K + M * K + M * out_cols)
     t_mfma, t_hbm = flops / (PEAK_BF16_TFLOPS * 1e12), bytes_ / (PEAK_HBM_GBS * 1e9)
     if t_mfma >= t_hbm:
         ach = flops / seconds / 1e12
-        return dict(bound="mfma", achieved=ach, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                    frac=ach / PEAK_BF16_TFLOPS, traffic=None)
-    ach = bytes_ / seconds / 1e9
-    return dict(bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s",
-                frac=ach / PEAK_HBM_GBS, traffic=None)
+        r = dict(bound="mfma", achieved=ach, peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                 frac=ach / PEAK_BF16_TFLOPS, traffic=None)
+        if measured:
+            r["peak_measured"] = measured["mfma_tflops_random"]
+            r["frac_of_measured"] = ach / measured["mfma_tflops_random"]
+        return r
+    return hbm_roofline(bytes_, seconds, measured)
 
 
-def hbm_roofline(bytes_, seconds):
+def hbm_roofline(bytes_, seconds, measured=None):
     ach = bytes_ / seconds / 1e9
-    return dict(bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS,
-                traffic=None)
+    r = dict(bound="hbm", achieved=ach, peak=PEAK_HBM_GBS, unit="GB/s", frac=ach / PEAK_HBM_GBS,
+             traffic=None)
+    if measured:
+        r["peak_measured"] = measured["copy_gbs"]
+        r["frac_of_measured"] = ach / measured["copy_gbs"]
+    return r
+
+
+def gemm_source_hash():
+    """Hash of the GEMM source without comments and layout, so that only code changes void a
+    stored traffic figure."""
+    src = os.path.join(ROOT, "paper_2604_09244_amd", "csrc", "gemm.hip")
+    code = re.sub(r"//[^\n]*", "", open(src).read())
+    return hashlib.sha256("".join(code.split()).encode()).hexdigest()[:16]
 
 
 def main():
@@ -64,22 +85,30 @@ def main():
     ap.add_argument("--steps", type=int, default=None,
                     help="timed steps (default: 200 for the 4-layer workloads, 5 for the 32-layer ones)")
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="single_view")
+    ap.add_argument("--workload", default="ratio_sweep")
     ap.add_argument("--keep", type=int, default=None, help="keep ratio in permille")
     ap.add_argument("--layers", type=int, default=None, help="override layer count (not the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-curve", action="store_true",
+                    help="ratio_sweep: skip the other keep ratios after the headline one")
+    ap.add_argument("--no-peaks", action="store_true",
+                    help="skip the probes of what the device sustains (stream read / copy, "
+                         "matrix-core loop, empty launch)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 128 MiB row copy (compact kernel, identity indices) so "
                          "that hardware byte counters can be scaled against a known size")
     ap.add_argument("--separate-prune-calls", action="store_true",
-                    help="issue the four pruning calls one by one instead of mvla_prune_step")
+                    help="issue the four pruning calls one by one instead of the fused ones")
     ap.add_argument("--materialise-probs", action="store_true",
                     help="write the scoring probabilities to memory and reduce them in a second "
-                         "kernel (mvla_prefill_layer + mvla_prune_step) instead of the single call "
-                         "that reduces them on the fly")
+                         "kernel instead of reducing them inside the scoring kernel")
     ap.add_argument("--no-tune", action="store_true",
                     help="let the built-in cost model choose the projection kernels' tile "
                          "configurations instead of measuring them once at set-up")
+    ap.add_argument("--choices", default=None,
+                    help="JSON object {\"qkv@M\": [config, split_pct], ...} as printed under "
+                         "config.projection_kernel_choices by an earlier run: replay exactly those "
+                         "kernel choices (same summation order, bit-identical outputs run to run)")
     ap.add_argument("--masks", action="store_true",
                     help="also time an action-iteration episode that prunes with the masks of "
                          "Algorithm 1 (needs n2 == n3 and p >= 1); reported as 'masked_episode'")
@@ -116,8 +145,17 @@ def main():
     kb = W.scoring_bias(wl, device=dev)
     ctx = mv.Context(wl.B, wl.S, wl.D, wl.H, wl.F, wl.nt)
     cfg = mv.LayerCfg(wl.D, wl.H, wl.dh, wl.F, wl.rms_eps)
+    shapes = {"qkv": (3 * wl.D, wl.D, 0), "o": (wl.D, wl.D, 1), "gateup": (2 * wl.F, wl.D, 3),
+              "down": (wl.D, wl.F, 2)}
+    replay = json.loads(args.choices) if args.choices else None
+    if replay:
+        for key, (c, pct) in replay.items():
+            nm, M = key.split("@")
+            N_, K_, e_ = shapes[nm]
+            ctx.set_gemm_choice(int(M), N_, K_, e_, int(c), int(pct))
+    tune = not args.no_tune and not replay
     plan = mv.PrefillPlan(ctx, cfg, layers, wl.B, wl.n2, wl.n3, wl.nt, wl.k_total, wl.p,
-                          rope_base=wl.rope_base, tune=not args.no_tune)
+                          rope_base=wl.rope_base, tune=tune)
     fused = not args.separate_prune_calls
     torch.cuda.synchronize()
     if args.calibrate_copy:
@@ -129,6 +167,24 @@ def main():
         torch.cuda.synchronize()
         cal_ctx.close()
         del src
+
+    # ---- what this device sustains on the simplest kernels -----------------------------------
+    measured = None
+    if not args.no_peaks:
+        big = torch.empty(2 << 30, dtype=torch.uint8, device=dev)       # 2 GiB, beyond every cache
+        big.view(torch.int32).random_(0, 1 << 30)
+        zeros = torch.zeros(8192, dtype=torch.uint8, device=dev)
+        rnd = (torch.randn(4096, device=dev) * 0.5).to(torch.bfloat16)
+        measured = dict(
+            read_gbs=ctx.peak_probe(mv.PROBE_READ, big, 10),
+            copy_gbs=ctx.peak_probe(mv.PROBE_COPY, big, 10),
+            mfma_tflops_zeros=ctx.peak_probe(mv.PROBE_MFMA, zeros, 5),
+            mfma_tflops_random=ctx.peak_probe(mv.PROBE_MFMA, rnd, 5),
+            empty_launch_us=ctx.peak_probe(mv.PROBE_LAUNCH, None, 200),
+            note="stream read of 2 GiB; copy of 1 GiB to 1 GiB (bytes read + written); loop of "
+                 "32x32x16 bf16 matrix-core products on register operands, four waves per "
+                 "compute unit, all-zero and N(0, 0.25) operands; empty kernels back to back")
+        del big
 
     def timed(fn, steps):
         torch.cuda.synchronize()
@@ -145,6 +201,8 @@ def main():
     # ---- the timed region: K pruned prefills, nothing bracketed (an event pair around a launch
     # costs ~11 us of stream time, so per-kernel timing runs in regions of its own below) --------
     GATEUP = next(i for i in range(32) if mv.load().mvla_kernel_name(i) == b"gemm_gateup")
+    PRUNE_IDS = [i for i in range(32) if mv.load().mvla_kernel_name(i) in
+                 (b"prune_fused", b"compact", b"salience", b"budget", b"select")]
     for _ in range(Wm):
         run_pruned()
     ctx.profile_enable([], 0)
@@ -158,18 +216,15 @@ def main():
         by_tag[tag].append(ms)
     dom_tag = max(by_tag, key=lambda t: sum(by_tag[t]))
     dom_ms = sum(by_tag[dom_tag]) / len(by_tag[dom_tag])
-    roofline = gemm_roofline(dom_tag, 2 * wl.F, wl.D, wl.F, dom_ms * 1e-3)
+    roofline = gemm_roofline(dom_tag, 2 * wl.F, wl.D, wl.F, dom_ms * 1e-3, measured)
     roofline["kernel"] = f"gemm_gateup M={dom_tag} N={2 * wl.F} K={wl.D}"
-    import hashlib
-    src = os.path.join(ROOT, "paper_2604_09244_amd", "csrc", "gemm.hip")
-    # hash of the kernel source without comments and layout, so that only code changes void it
-    code = re.sub(r"//[^\n]*", "", open(src).read())
-    src_hash = hashlib.sha256("".join(code.split()).encode()).hexdigest()[:16]
     meas = MEASURED_TRAFFIC.get(("gemm_gateup", dom_tag, 2 * wl.F, wl.D))
-    dom_cfg = None if args.no_tune else ctx.tuned_choice(dom_tag, 2 * wl.F, wl.D, 3)[0]
-    roofline["traffic"] = meas[0] if meas and meas[1] == src_hash and meas[2] == dom_cfg else None
+    dom_cfg = ctx.tuned_choice(dom_tag, 2 * wl.F, wl.D, 3)[0]
+    roofline["traffic"] = (meas[0] if meas and meas[1] == gemm_source_hash() and meas[2] == dom_cfg
+                           else None)
     roofline["avg_us"] = dom_ms * 1e3
     roofline["launches"] = len(by_tag[dom_tag])
+    roofline["share_of_step"] = sum(by_tag[dom_tag]) * 1e-3 / (K * sec_dom)
 
     # ---- second pass with every kernel bracketed: per-kernel table, pruning-step cost --------
     ctx.profile_enable(None, max_records=K * (wl.L * 10 + 8))
@@ -183,40 +238,96 @@ def main():
     prune_us = {n: 1e3 * sum(sum(v) for (nn, t), v in acc.items() if nn == n) / K for n in prune_names}
     prune_us = {n: v for n, v in prune_us.items() if v > 0}
     prune_total_us = sum(prune_us.values())
+    prune_launches = sum(len(v) for (nn, t), v in acc.items() if nn in prune_names) / K
 
-    # roofline of the bandwidth-bound pruning kernels (algorithmic bytes per launch)
+    # the pruning kernels are reported against what bounds them: the bandwidth-bound ones
+    # (at least 32 MB per launch) against HBM, the others against the cost of an empty launch
     extra = {}
+
+    def by_size(avg_s, bytes_):
+        if bytes_ >= 32e6:
+            return hbm_roofline(bytes_, avg_s, measured)
+        return dict(bound="latency", avg_us=avg_s * 1e6, algorithmic_bytes=bytes_,
+                    empty_launch_us=None if not measured else measured["empty_launch_us"])
+
     for sal_key in (("salience", wl.B), ("prune_fused", wl.B)):   # fused: + budget and selection
         if sal_key in acc:
             rows = (wl.nt + 31) // 32 if otf else wl.nt     # on the fly: one row per 32-query tile
             b = 4.0 * wl.B * wl.H * rows * wl.n_vis + 4.0 * wl.B * wl.n_vis
-            extra[sal_key[0]] = hbm_roofline(b, 1e-3 * sum(acc[sal_key]) / len(acc[sal_key]))
+            extra[sal_key[0]] = by_size(1e-3 * sum(acc[sal_key]) / len(acc[sal_key]), b)
     sc_key = ("score_probs", M_full)
     if sc_key in acc:   # reads every key row once and the query rows, writes sums or probabilities
         out_b = 4.0 * wl.B * wl.H * (((wl.nt + 31) // 32) * wl.n_vis if otf else wl.nt * wl.S)
         b = 2.0 * wl.B * wl.S * wl.D + 2.0 * wl.B * wl.nt * wl.D + out_b
-        extra["score_probs"] = hbm_roofline(b, 1e-3 * sum(acc[sc_key]) / len(acc[sc_key]))
+        extra["score_probs"] = by_size(1e-3 * sum(acc[sc_key]) / len(acc[sc_key]), b)
     cmp_key = ("compact", M_kept)
     if cmp_key in acc:
         b = 2.0 * M_kept * wl.D * 2 + 12.0 * M_kept
-        extra["compact"] = hbm_roofline(b, 1e-3 * sum(acc[cmp_key]) / len(acc[cmp_key]))
+        extra["compact"] = by_size(1e-3 * sum(acc[cmp_key]) / len(acc[cmp_key]), b)
     for (n, t), v in acc.items():
         if n.startswith("gemm_"):
             N_, K_, oc = {"gemm_qkv": (3 * wl.D, wl.D, 3 * wl.D), "gemm_o": (wl.D, wl.D, 2 * wl.D),
                           "gemm_gateup": (2 * wl.F, wl.D, wl.F), "gemm_down": (wl.D, wl.F, wl.D)}[n]
-            extra[f"{n}@{t}"] = gemm_roofline(t, N_, K_, oc, 1e-3 * sum(v) / len(v))
+            extra[f"{n}@{t}"] = gemm_roofline(t, N_, K_, oc, 1e-3 * sum(v) / len(v), measured)
         if n == "attention":
             S_ = t // wl.B
             fl = 4.0 * wl.dh * wl.H * S_ * (S_ + 1) / 2 * wl.B
             s_ = 1e-3 * sum(v) / len(v)
-            extra[f"attention@{t}"] = dict(bound="mfma", achieved=fl / s_ / 1e12, peak=PEAK_BF16_TFLOPS,
-                                           unit="TFLOP/s", frac=fl / s_ / 1e12 / PEAK_BF16_TFLOPS,
-                                           traffic=None)
+            r = dict(bound="mfma", achieved=fl / s_ / 1e12, peak=PEAK_BF16_TFLOPS,
+                     unit="TFLOP/s", frac=fl / s_ / 1e12 / PEAK_BF16_TFLOPS, traffic=None)
+            if measured:
+                r["peak_measured"] = measured["mfma_tflops_random"]
+                r["frac_of_measured"] = r["achieved"] / measured["mfma_tflops_random"]
+            extra[f"attention@{t}"] = r
 
     # ---- unpruned prefill of the same shape ----------------------------------------------------
     for _ in range(max(1, Wm // 2)):
         run_full()
     sec_full = timed(run_full, K)
+
+    # ---- pruning before any layer (masks returned to the encoder output, last line of
+    # Algorithm 1): a scoring pass, the pruning step, then every layer on kept tokens -----------
+    encoder_variant = None
+    if small or wl.name == "action_iter":
+        plan0 = mv.PrefillPlan(ctx, cfg, layers, wl.B, wl.n2, wl.n3, wl.nt, wl.k_total, 0,
+                               rope_base=wl.rope_base, tune=False)
+        run0 = lambda: plan0.run(x, pos, kb, fused_prune=fused)
+        for _ in range(Wm):
+            run0()
+        sec0 = timed(run0, K)
+        encoder_variant = dict(ms_per_step=sec0 * 1e3, tokens_per_s=M_full / sec0,
+                               speedup_vs_unpruned=sec_full / sec0,
+                               gemm_linear_ceiling=wl.S / wl.S_kept,
+                               note="p = 0: mvla_score_only + pruning step + all layers on the "
+                                    "kept tokens")
+        del plan0
+
+    # ---- the other keep ratios of the sweep ---------------------------------------------------
+    curve = None
+    if wl.name == "ratio_sweep" and not args.no_curve and args.layers is None:
+        curve = {str(wl.keep_permille): dict(ms_per_step=sec_pruned * 1e3, S_kept=wl.S_kept,
+                                             speedup_vs_unpruned=sec_full / sec_pruned,
+                                             prune_step_us=prune_total_us, steps=K)}
+        for permille in W.RATIO_SWEEP_PERMILLE:
+            if permille == wl.keep_permille:
+                continue
+            w2 = W.with_keep(wl, permille)
+            pl2 = mv.PrefillPlan(ctx, cfg, layers, w2.B, w2.n2, w2.n3, w2.nt, w2.k_total, w2.p,
+                                 rope_base=w2.rope_base, tune=tune)
+            r2 = lambda: pl2.run(x, pos, kb, fused_prune=fused, on_the_fly=otf)
+            r2()
+            n2 = max(2, K // 2)
+            s2 = timed(r2, n2)
+            ctx.profile_enable(PRUNE_IDS, max_records=64)
+            r2()
+            torch.cuda.synchronize()
+            p_us = 1e3 * sum(ms for _, _, ms in ctx.profile_read())
+            ctx.profile_enable([], 0)
+            curve[str(permille)] = dict(ms_per_step=s2 * 1e3, S_kept=w2.S_kept,
+                                        speedup_vs_unpruned=sec_full / s2, prune_step_us=p_us,
+                                        gemm_linear_ceiling=w2.L * w2.S / (w2.p * w2.S + (w2.L - w2.p) * w2.S_kept),
+                                        steps=n2)
+            del pl2
 
     # ---- optional: episode with Algorithm 1's masks (ragged kept lengths, padded per step) -----
     masked = None
@@ -271,22 +382,19 @@ def main():
                          wl.rope_base, kb0)
         dt = time.perf_counter() - t0
         # scale layer count linearly if the workload has more layers than the sample ran
-        per_full = dt  # seconds for Lc layers on one sample
         scale = 1.0
         if wl.L > Lc:
             # kept-token layers dominate the remainder: extrapolate with the kept/full cost ratio
             scale = (wl.p * wl.S + (wl.L - wl.p) * wl.S_kept) / (pc * wl.S + (Lc - pc) * wl.S_kept)
-        cpu = dict(value=wl.S / (per_full * scale), unit="tokens/s", cores=int(cores), kind="oracle",
+        cpu = dict(value=wl.S / (dt * scale), unit="tokens/s", cores=int(cores), kind="oracle",
                    sample=f"sample 0 of {wl.B}, whole pruned prefill, {Lc} of {wl.L} layers timed "
                           f"({dt:.1f} s)" + ("" if scale == 1.0 else f", scaled x{scale:.2f} to {wl.L} layers"))
 
-    # the tile configuration / K-split threshold each projection shape runs with
+    # the tile configuration / K-split threshold each projection shape runs with (-1: cost model)
     choices = {}
-    if not args.no_tune:
-        for M in sorted({M_full, M_kept}, reverse=True):
-            for nm, (N_, K_, e_) in (("qkv", (3 * wl.D, wl.D, 0)), ("o", (wl.D, wl.D, 1)),
-                                     ("gateup", (2 * wl.F, wl.D, 3)), ("down", (wl.D, wl.F, 2))):
-                choices[f"{nm}@{M}"] = list(ctx.tuned_choice(M, N_, K_, e_))
+    for M in sorted({M_full, M_kept}, reverse=True):
+        for nm, (N_, K_, e_) in shapes.items():
+            choices[f"{nm}@{M}"] = list(ctx.tuned_choice(M, N_, K_, e_))
     out = {
         "metric": "pruned-prefill tokens/s",
         "value": M_full / sec_pruned,
@@ -295,21 +403,29 @@ def main():
         "ms_per_step": sec_pruned * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": wl.name, "B": wl.B, "S": wl.S, "S_kept": wl.S_kept, "n2": wl.n2,
+        "config": {"workload": wl.name, "keep_permille": wl.keep_permille, "B": wl.B, "S": wl.S,
+                   "S_kept": wl.S_kept, "n2": wl.n2,
                    "n3": wl.n3, "n_text": wl.nt, "layers": wl.L, "full_layers_before_pruning": wl.p,
-                   "keep_permille": wl.keep_permille, "hidden": wl.D, "heads": wl.H, "mlp": wl.F,
+                   "hidden": wl.D, "heads": wl.H, "mlp": wl.F,
                    "fused_prune_call": fused, "scoring_reduced_on_the_fly": otf,
-                   "projection_kernels_measured_at_setup": not args.no_tune,
+                   "projection_kernels_measured_at_setup": tune,
                    "projection_kernel_choices": choices},
         "prune_step_us": prune_total_us,
         "prune_step_us_by_kernel": prune_us,
+        "prune_step_launches": prune_launches,
+        "prune_step_vs_empty_launches": (None if not measured else
+                                         prune_total_us / (prune_launches * measured["empty_launch_us"])),
         "prune_pct_of_pruned_prefill": 100.0 * prune_total_us * 1e-6 / sec_instr,
         "unpruned_ms_per_step": sec_full * 1e3,
         "speedup_vs_unpruned": sec_full / sec_pruned,
+        "gemm_linear_speedup_ceiling": wl.L * wl.S / (wl.p * wl.S + (wl.L - wl.p) * wl.S_kept),
         "instrumented_ms_per_step": {"dominant_kernel_only": sec_dom * 1e3, "all_kernels": sec_instr * 1e3},
         "roofline": roofline,
         "roofline_other": extra,
+        "peaks_measured": measured,
         "kernels": kernels,
+        "keep_curve": curve,
+        "encoder_mask_variant": encoder_variant,
         "cpu_baseline": cpu,
         "masked_episode": masked,
         "paper_context": {"speedup": 2.55, "overhead_pct": 5.8,

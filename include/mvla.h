@@ -323,12 +323,74 @@ int mvla_set_gemm_choice(mvla_ctx* ctx, int M, int N, int K, int epilogue, int c
 int mvla_tuned_choice(mvla_ctx* ctx, int M, int N, int K, int epilogue, int* cfg_out,
                       int* split_pct_out);
 
-/* Scoring pass alone, for pruning before any layer has run: RMSNorm, query
- * projection of the last n_query_tail rows, key projection of all rows, RoPE,
- * causal softmax (+ key_bias).  Writes probs_out as above. */
+/* Scoring pass alone, for pruning before any layer has run -- the variant in
+ * which the masks go back to the encoder output and every layer sees kept tokens
+ * only (Algorithm 1, last line: "return Mask_2D, Mask_3D to network encoder"):
+ * RMSNorm, key projection of all rows, query projection of the last
+ * n_query_tail rows only, RoPE, causal softmax (+ key_bias).  Uses the norm
+ * gain and the q, k rows of w->wqkv.  Writes probs_out as above. */
 int mvla_score_only(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weights* w,
                     const void* x, const int32_t* pos, int B, int S, int n_query_tail,
                     const float* key_bias, float* probs_out);
+
+/* ------------------------------------------------------------------------ */
+/* Whole path                                                               */
+/* ------------------------------------------------------------------------ */
+
+/* What one pruned prefill runs (Sec. 4.4 and Algorithm 1 for the order of the
+ * steps; App. C for the backbone): p layers on all S = n2 + n3 + n_text tokens,
+ * the pruning step on the language-query attention of layer p-1, then the
+ * remaining n_layers - p layers on the k_total + n_text kept tokens.  p = 0:
+ * a scoring pass with layer 0's weights (mvla_score_only), the pruning step
+ * on the input itself, then every layer on kept tokens.
+ * smooth_step = t > 0 makes the call timestep t of an action-iteration episode
+ * (Algorithm 1, "Action Iteration Stage"; Eqs. 8-9): the salience of the step
+ * updates the smoothed state sal_hat (mvla_temporal_smooth with smooth_k,
+ * smooth_beta), budget and selection read sal_hat; at t = 1 (cold start) nothing
+ * is pruned: all layers run on all tokens and the state is seeded. */
+typedef struct {
+    int B, n2, n3, n_text;
+    int k_total, min2, min3;      /* as mvla_modality_budget                            */
+    int n_layers, p;
+    int smooth_step, smooth_k;    /* 0 = no smoothing; paper: k = 7                     */
+    double smooth_beta;           /* paper: 0.85                                        */
+    int materialise_probs;        /* != 0: write the probabilities and reduce them in a
+                                     second kernel; 0: reduce them inside the scoring
+                                     kernel (p >= 1; p = 0 always materialises)        */
+    int separate_prune_calls;     /* != 0: salience, budget, selection, gather as four
+                                     launches instead of the fused ones                 */
+} mvla_prefill_desc;
+
+/* Device buffers of mvla_prefill, caller-owned, pairwise disjoint and disjoint
+ * from x.  Outputs of the pruning step land in sal, k2k3, kept_idx, pos_kept
+ * as the single calls define them. */
+typedef struct {
+    void* h_full[2];     /* bf16 [B, S, D] each: layer outputs on all tokens             */
+    void* h_kept[2];     /* bf16 [B, k_total + n_text, D] each: gathered tokens, outputs  */
+    float* probs;        /* fp32 [B, H, n_text, S]; may be NULL unless materialise_probs
+                            or p == 0                                                     */
+    float* sal;          /* fp32 [B, n2 + n3]: salience of this call                      */
+    float* sal_hat;      /* fp32 [B, n2 + n3]: smoothed state (read and updated), or NULL
+                            when smooth_step == 0                                         */
+    int32_t* k2k3;       /* int32 [B, 2]                                                  */
+    int32_t* kept_idx;   /* int32 [B, k_total + n_text]                                   */
+    int32_t* pos_kept;   /* int32 [B, k_total + n_text]                                   */
+} mvla_prefill_buffers;
+
+/* Enqueue one whole pruned prefill: exactly the sequence of the calls above
+ * that the description selects (no arithmetic of its own, same results as
+ * issuing them one by one).  layers: HOST array of n_layers descriptors;
+ * x: device bf16 [B, S, D]; pos: device int32 [B, S]; key_bias: device fp32
+ * [B, S] or NULL (added to the scoring logits only).
+ * *y_out (host) receives the device pointer of the final hidden states -- one
+ * of the h_kept buffers, or one of the h_full buffers at a cold start -- and
+ * *rows_out their rows per sample (k_total + n_text, or S).
+ * Everything (description, every layer descriptor, workspace size) is checked
+ * before the first launch. */
+int mvla_prefill(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weights* layers,
+                 const mvla_prefill_desc* desc, const void* x, const int32_t* pos,
+                 const float* key_bias, const mvla_prefill_buffers* buffers, void** y_out,
+                 int* rows_out);
 
 /* ------------------------------------------------------------------------ */
 /* Measurement (the paper's overhead study, Table 4, reports the pruning    */
@@ -354,6 +416,23 @@ int mvla_profile_read(mvla_ctx* ctx, int capacity, int32_t* ids, int32_t* tags, 
  * "decompose", "feature_share", "candidate_masks", "mask_indices"), "?"
  * otherwise. */
 const char* mvla_kernel_name(int id);
+
+/* Rates the device sustains on the simplest kernels, so that a kernel's time
+ * can be quoted against what the part delivers as well as against its
+ * datasheet.  Runs one untimed and `reps` timed launches on the context's
+ * stream between two HIP events and SYNCHRONISES the stream.
+ *   MVLA_PROBE_READ   streams `bytes` of buf once per launch        -> GB/s
+ *   MVLA_PROBE_COPY   copies the first half of buf to the second    -> GB/s (bytes read + written)
+ *   MVLA_PROBE_MFMA   every wave (four per compute unit) runs a loop of the sixteen
+ *                     independent 32x32x16 bf16 products of a 128x128 register tile on
+ *                     operands taken from the first 8 KiB of buf (all zeros, or random
+ *                     values: the part's clock under matrix load depends on the data)
+ *                                                                   -> TFLOP/s
+ *   MVLA_PROBE_LAUNCH empty kernels back to back (buf unused)       -> microseconds per launch
+ * buf: device, 16-byte aligned; bytes >= 1 MiB for READ/COPY, >= 8 KiB for MFMA.
+ * result: HOST. */
+enum { MVLA_PROBE_READ = 0, MVLA_PROBE_COPY = 1, MVLA_PROBE_MFMA = 2, MVLA_PROBE_LAUNCH = 3 };
+int mvla_peak_probe(mvla_ctx* ctx, int kind, void* buf, size_t bytes, int reps, double* result);
 
 #ifdef __cplusplus
 }

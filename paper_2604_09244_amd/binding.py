@@ -26,7 +26,7 @@ EXPORTS = [
     "mvla_modality_decompose", "mvla_feature_share", "mvla_mask_rules_default",
     "mvla_candidate_masks", "mvla_mask_indices", "mvla_prefill_layer_salience",
     "mvla_prefill_layer_prune", "mvla_tune_layers", "mvla_tuned_choice",
-    "mvla_set_gemm_choice",
+    "mvla_set_gemm_choice", "mvla_prefill", "mvla_peak_probe",
 ]
 
 
@@ -64,6 +64,25 @@ class MaskRules(C.Structure):
         return r
 
 
+class PrefillDesc(C.Structure):
+    """mvla_prefill_desc."""
+    _fields_ = [("B", C.c_int), ("n2", C.c_int), ("n3", C.c_int), ("n_text", C.c_int),
+                ("k_total", C.c_int), ("min2", C.c_int), ("min3", C.c_int),
+                ("n_layers", C.c_int), ("p", C.c_int), ("smooth_step", C.c_int),
+                ("smooth_k", C.c_int), ("smooth_beta", C.c_double),
+                ("materialise_probs", C.c_int), ("separate_prune_calls", C.c_int)]
+
+
+class PrefillBuffers(C.Structure):
+    """mvla_prefill_buffers."""
+    _fields_ = [("h_full", C.c_void_p * 2), ("h_kept", C.c_void_p * 2), ("probs", C.c_void_p),
+                ("sal", C.c_void_p), ("sal_hat", C.c_void_p), ("k2k3", C.c_void_p),
+                ("kept_idx", C.c_void_p), ("pos_kept", C.c_void_p)]
+
+
+PROBE_READ, PROBE_COPY, PROBE_MFMA, PROBE_LAUNCH = 0, 1, 2, 3
+
+
 def load() -> C.CDLL:
     """Load the HIP library; raise if it has not been built."""
     global _lib
@@ -99,6 +118,10 @@ def load() -> C.CDLL:
     lib.mvla_tune_layers.argtypes = [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeightsC), i, i, i]
     lib.mvla_set_gemm_choice.argtypes = [vp, i, i, i, i, i, i]
     lib.mvla_tuned_choice.argtypes = [vp, i, i, i, i, C.POINTER(C.c_int), C.POINTER(C.c_int)]
+    lib.mvla_prefill.argtypes = [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeightsC),
+                                 C.POINTER(PrefillDesc), vp, vp, vp, C.POINTER(PrefillBuffers),
+                                 C.POINTER(vp), C.POINTER(i)]
+    lib.mvla_peak_probe.argtypes = [vp, i, vp, sz, i, C.POINTER(C.c_double)]
     lib.mvla_score_only.argtypes = [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeightsC), vp, vp,
                                     i, i, i, vp, vp]
     lib.mvla_modality_decompose.argtypes = [vp, vp, i, i, i, i, i, vp, vp]
@@ -419,6 +442,16 @@ class Context:
                "mvla_tuned_choice")
         return c.value, p.value
 
+    def peak_probe(self, kind: int, buf: Optional[torch.Tensor], reps: int = 10) -> float:
+        """Measured rate of a probe kernel (synchronises): GB/s for PROBE_READ / PROBE_COPY,
+        TFLOP/s for PROBE_MFMA (operands: the first 8 KiB of buf), microseconds per launch for
+        PROBE_LAUNCH."""
+        out = C.c_double(0.0)
+        nbytes = 0 if buf is None else buf.numel() * buf.element_size()
+        _check(load().mvla_peak_probe(self._h, kind, _ptr(buf), nbytes, reps, C.byref(out)),
+               "mvla_peak_probe")
+        return out.value
+
     def score_only(self, cfg: LayerCfg, w: LayerWeightsC, x, pos, n_query_tail, key_bias=None,
                    probs_out=None):
         B, S, D = _dev(x, torch.bfloat16).shape
@@ -431,8 +464,8 @@ class Context:
 
 
 class PrefillPlan:
-    """Pre-allocated buffers and packed weights for one workload; ``run`` only
-    enqueues library calls (no allocation, no host synchronisation)."""
+    """Pre-allocated buffers and packed weights for one workload; ``run`` hands them to
+    mvla_prefill (no allocation, no host synchronisation, no torch operation)."""
 
     def __init__(self, ctx: Context, cfg: LayerCfg, layers: List[Dict[str, torch.Tensor]],
                  B: int, n2: int, n3: int, nt: int, k_total: int, p: int,
@@ -458,83 +491,42 @@ class PrefillPlan:
                           kept_idx=torch.empty(B, self.S_kept, dtype=i32, device=dev),
                           h=self.h_kept[0],
                           pos=torch.empty(B, self.S_kept, dtype=i32, device=dev))
+        self._layer_array = (LayerWeightsC * len(self.structs))(*self.structs)
+        hf, hk = (C.c_void_p * 2), (C.c_void_p * 2)
+        self._buffers = PrefillBuffers(hf(*[t.data_ptr() for t in self.h_full]),
+                                       hk(*[t.data_ptr() for t in self.h_kept]),
+                                       self.probs.data_ptr(), self.prune["sal"].data_ptr(),
+                                       self.sal_hat.data_ptr(), self.prune["k2k3"].data_ptr(),
+                                       self.prune["kept_idx"].data_ptr(),
+                                       self.prune["pos"].data_ptr())
 
     def run(self, x: torch.Tensor, pos: torch.Tensor, key_bias: Optional[torch.Tensor] = None,
             fused_prune: bool = True, smooth_step: int = 0, smooth_k: int = 7,
             smooth_beta: float = 0.85, on_the_fly: bool = False):
-        """Pruned prefill: p full layers, pruning step, L-p layers on kept tokens.
+        """Pruned prefill: p full layers, pruning step, L-p layers on kept tokens -- one call
+        of mvla_prefill, which does the sequencing.
 
         smooth_step > 0 turns on the action-iteration smoothing of the salience: the call is
         timestep ``smooth_step`` (1-based) of an episode; step 1 is the cold start and returns
-        the unpruned prefill, later steps select on the smoothed salience."""
-        ctx, cfg = self.ctx, self.cfg
-        if smooth_step == 1:
-            return self._cold_start(x, pos, key_bias, smooth_k, smooth_beta)
-        if on_the_fly:
-            # the pruning step rides on the last full-sequence layer; no probability tensor
-            assert self.p >= 1 and smooth_step == 0
-            h = x
-            for li in range(self.p - 1):
-                y = self.h_full[li & 1]
-                ctx.prefill_layer(cfg, self.structs[li], h, pos, y)
-                h = y
-            y = self.h_full[(self.p - 1) & 1]
-            ctx.prefill_layer_prune(cfg, self.structs[self.p - 1], h, pos, y, self.n2, self.n3,
-                                    self.nt, self.k_total, key_bias, out=self.prune)
-            h, pk = self.prune["h"], self.prune["pos"]
-            for li in range(self.p, self.L):
-                y = self.h_kept[(li - self.p + 1) & 1]
-                ctx.prefill_layer(cfg, self.structs[li], h, pk, y)
-                h = y
-            return h
-        h = x
-        for li in range(self.p):
-            tail = self.nt if li == self.p - 1 else 0
-            y = self.h_full[li & 1]
-            ctx.prefill_layer(cfg, self.structs[li], h, pos, y, tail, key_bias,
-                              self.probs if tail else None)
-            h = y
-        if self.p == 0:
-            ctx.score_only(cfg, self.structs[0], h, pos, self.nt, key_bias, self.probs)
-        if fused_prune and smooth_step == 0:
-            ctx.prune_step(self.probs, h, pos, self.n2, self.n3, self.nt, self.k_total,
-                           out=self.prune)
-        else:
-            ctx.salience(self.probs, self.n2 + self.n3, out=self.prune["sal"])
-            if smooth_step > 1:
-                ctx.temporal_smooth(self.prune["sal"], self.sal_hat, smooth_step, smooth_k,
-                                    smooth_beta)
-                self.prune["sal"].copy_(self.sal_hat)
-            ctx.modality_budget(self.prune["sal"], self.n2, self.n3, self.k_total,
-                                out=self.prune["k2k3"])
-            ctx.select_topk(self.prune["sal"], self.prune["k2k3"], self.n2, self.n3, self.nt,
-                            self.k_total, out=self.prune["kept_idx"])
-            ctx.compact(h, pos, self.prune["kept_idx"], out=(self.prune["h"], self.prune["pos"]))
-        h, pk = self.prune["h"], self.prune["pos"]
-        for li in range(self.p, self.L):
-            y = self.h_kept[(li - self.p + 1) & 1]
-            ctx.prefill_layer(cfg, self.structs[li], h, pk, y)
-            h = y
-        return h
-
-    def _cold_start(self, x, pos, key_bias, k, beta):
-        """Step 1 of an episode: all tokens go through every layer; the salience observed on
-        the way seeds the smoothed state."""
-        h = x
-        if self.p == 0:
-            self.ctx.score_only(self.cfg, self.structs[0], h, pos, self.nt, key_bias, self.probs)
-            self.ctx.salience(self.probs, self.n2 + self.n3, out=self.prune["sal"])
-            self.ctx.temporal_smooth(self.prune["sal"], self.sal_hat, 1, k, beta)
-        for li in range(self.L):
-            tail = self.nt if li == self.p - 1 else 0
-            y = self.h_full[li & 1]
-            self.ctx.prefill_layer(self.cfg, self.structs[li], h, pos, y, tail, key_bias,
-                                   self.probs if tail else None)
-            h = y
-            if tail:
-                self.ctx.salience(self.probs, self.n2 + self.n3, out=self.prune["sal"])
-                self.ctx.temporal_smooth(self.prune["sal"], self.sal_hat, 1, k, beta)
-        return h
+        the unpruned prefill, later steps select on the smoothed salience.  ``on_the_fly``
+        reduces the scoring rows inside the scoring kernel (no probability tensor)."""
+        _dev(x, torch.bfloat16)
+        _dev(pos, torch.int32)
+        if key_bias is not None:
+            _dev(key_bias, torch.float32)
+        d = PrefillDesc(self.B, self.n2, self.n3, self.nt, self.k_total, 0, 0, self.L, self.p,
+                        smooth_step, smooth_k, smooth_beta, 0 if on_the_fly else 1,
+                        0 if fused_prune else 1)
+        y_ptr, rows = C.c_void_p(), C.c_int()
+        _check(load().mvla_prefill(self.ctx.handle, C.byref(self.cfg), self._layer_array,
+                                   C.byref(d), x.data_ptr(), pos.data_ptr(), _ptr(key_bias),
+                                   C.byref(self._buffers), C.byref(y_ptr), C.byref(rows)),
+               "mvla_prefill")
+        for t in self.h_kept + self.h_full:          # which of the plan's tensors holds the result
+            if t.data_ptr() == y_ptr.value:
+                assert t.shape[1] == rows.value
+                return t
+        raise RuntimeError("mvla_prefill returned a pointer outside the plan's buffers")
 
     def run_unpruned(self, x: torch.Tensor, pos: torch.Tensor):
         h = x

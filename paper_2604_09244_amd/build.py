@@ -9,7 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libmvla.so")
-SOURCES = ["api.hip", "prune_kernels.hip", "mask_kernels.hip", "layer_kernels.hip", "gemm.hip", "attention.hip"]
+SOURCES = ["api.hip", "prune_kernels.hip", "mask_kernels.hip", "layer_kernels.hip", "gemm.hip", "attention.hip",
+           "probe_kernels.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]

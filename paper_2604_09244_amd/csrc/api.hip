@@ -406,7 +406,7 @@ static int run_layer(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_
                       GEMM_WS(ctx), GEMM_PICK(ctx, M, 3 * D, D, EPI_QKV_ROPE), &rope, st));
     if (n_query_tail > 0 && !red) {
         TIMED(ctx, KID_SCORE_PROBS, M,
-              launch_score_probs(lb.qkv, 3 * D, lb.qkv + D, 3 * D, key_bias, B, S, H, dh,
+              launch_score_probs(lb.qkv, 3 * D, false, lb.qkv + D, 3 * D, key_bias, B, S, H, dh,
                                  n_query_tail, probs_out, 0, st));
     } else if (n_query_tail > 0) {
         // Column sums per 32-query tile go to the (still unused) MLP activation buffer, the
@@ -417,7 +417,7 @@ static int run_layer(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_
             salience_scratch_bytes(B, H, tiles, n_vis) > (size_t)M * D * 2)
             return MVLA_ENOMEM;
         TIMED(ctx, KID_SCORE_PROBS, M,
-              launch_score_probs(lb.qkv, 3 * D, lb.qkv + D, 3 * D, key_bias, B, S, H, dh,
+              launch_score_probs(lb.qkv, 3 * D, false, lb.qkv + D, 3 * D, key_bias, B, S, H, dh,
                                  n_query_tail, colsum, n_vis, st));
         if (red->kept_idx) {
             TIMED(ctx, KID_PRUNE_FUSED, B,
@@ -492,6 +492,126 @@ int mvla_prefill_layer_prune(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvl
     return mvla_compact(ctx, y, pos, kept_idx, B, S, k_total + n_text, cfg->D, h_out, pos_out);
 }
 
+// The whole pruned prefill: sequencing only, every step is one of the calls above.
+int mvla_prefill(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weights* layers,
+                 const mvla_prefill_desc* d, const void* x, const int32_t* pos,
+                 const float* key_bias, const mvla_prefill_buffers* buf, void** y_out,
+                 int* rows_out) {
+    if (!ctx || !cfg || !layers || !d || !x || !pos || !buf || !y_out || !rows_out)
+        return MVLA_EINVAL;
+    const int B = d->B, n2 = d->n2, n3 = d->n3, nt = d->n_text, L = d->n_layers, p = d->p;
+    if (B <= 0 || n2 < 0 || n3 < 0 || n2 + n3 <= 0 || nt <= 0 || L <= 0 || p < 0 || p > L)
+        return MVLA_EINVAL;
+    if ((long)n2 + n3 + nt > INT32_MAX / 4) return MVLA_EUNSUPPORTED;
+    const int n_vis = n2 + n3, S = n_vis + nt, K = d->k_total, S_kept = K + nt;
+    if (K < 0 || K > n_vis) return MVLA_EINVAL;
+    if (d->min2 < 0 || d->min3 < 0 || d->min2 > n2 || d->min3 > n3 || d->min2 + d->min3 > K)
+        return MVLA_EINVAL;
+    if (n2 > 16384 || n3 > 16384) return MVLA_EUNSUPPORTED;
+    const int t = d->smooth_step;
+    if (t < 0 || (t > 0 && (d->smooth_k < 1 || !(d->smooth_beta > 0.0 && d->smooth_beta < 1.0))))
+        return MVLA_EINVAL;
+    const bool smoothing = t > 0, cold = t == 1;
+    // the probability tensor exists only when asked for, or when there is no layer to carry
+    // the scoring (pruning before any layer)
+    const bool need_probs = d->materialise_probs != 0 || p == 0;
+    const bool fused_layer = !need_probs && !smoothing && !d->separate_prune_calls;
+    if (!buf->h_full[0] || !buf->h_full[1] || !buf->sal || !buf->k2k3 || !buf->kept_idx ||
+        !buf->pos_kept || (!cold && L > p && (!buf->h_kept[0] || !buf->h_kept[1])) ||
+        (!cold && L == p && !buf->h_kept[0]) || (need_probs && !buf->probs) ||
+        (smoothing && !buf->sal_hat))
+        return MVLA_EINVAL;
+    // every layer's descriptor and the workspace are checked before the first launch
+    for (int l = 0; l < L; ++l) {
+        const int rc = check_layer_args(ctx, cfg, &layers[l], x, pos, B, S, 0, nullptr, true);
+        if (rc) return rc;
+    }
+    if ((size_t)B * S > (size_t)INT32_MAX / 4) return MVLA_EUNSUPPORTED;
+    if (layer_buffers(nullptr, B, S, cfg->D, cfg->F).bytes > ctx->scratch_bytes ||
+        salience_scratch_bytes(B, cfg->H, nt, n_vis) > ctx->scratch_bytes)
+        return MVLA_ENOMEM;
+
+    int rc;
+    const void* h = x;
+    // ---- full-sequence layers 0 .. p-2, then the scoring layer (or pass) ------------------
+    if (p == 0) {
+        rc = mvla_score_only(ctx, cfg, &layers[0], x, pos, B, S, nt, key_bias, buf->probs);
+        if (rc) return rc;
+    }
+    for (int l = 0; l < p; ++l) {
+        void* y = buf->h_full[l & 1];
+        if (l < p - 1) {
+            rc = mvla_prefill_layer(ctx, cfg, &layers[l], h, pos, B, S, y, 0, nullptr, nullptr);
+        } else if (need_probs) {
+            rc = mvla_prefill_layer(ctx, cfg, &layers[l], h, pos, B, S, y, nt, key_bias, buf->probs);
+        } else if (fused_layer && !cold) {
+            rc = mvla_prefill_layer_prune(ctx, cfg, &layers[l], h, pos, B, S, y, n2, n3, nt, K,
+                                          d->min2, d->min3, key_bias, buf->sal, buf->k2k3,
+                                          buf->kept_idx, buf->h_kept[0], buf->pos_kept);
+        } else {
+            rc = mvla_prefill_layer_salience(ctx, cfg, &layers[l], h, pos, B, S, y, nt, key_bias,
+                                             n_vis, buf->sal);
+        }
+        if (rc) return rc;
+        h = y;
+    }
+    const bool pruned_already = p >= 1 && fused_layer && !cold;
+    // ---- the pruning step (unless the scoring layer carried it) ------------------------------
+    if (!pruned_already) {
+        if (need_probs && !smoothing && !d->separate_prune_calls) {
+            rc = mvla_prune_step(ctx, buf->probs, cfg->H, nt, h, pos, B, S, cfg->D, n2, n3, nt, K,
+                                 d->min2, d->min3, buf->sal, buf->k2k3, buf->kept_idx,
+                                 buf->h_kept[0], buf->pos_kept);
+            if (rc) return rc;
+        } else {
+            if (need_probs) {
+                rc = mvla_salience(ctx, buf->probs, B, cfg->H, nt, S, n_vis, buf->sal);
+                if (rc) return rc;
+            }
+            const float* score = buf->sal;
+            if (smoothing) {   // Eqs. 8-9: selection reads the smoothed state in place
+                rc = mvla_temporal_smooth(ctx, buf->sal, buf->sal_hat, (size_t)B * n_vis, t,
+                                          d->smooth_k, d->smooth_beta);
+                if (rc) return rc;
+                score = buf->sal_hat;
+            }
+            if (!cold) {
+                rc = mvla_modality_budget(ctx, score, B, n2, n3, K, d->min2, d->min3, buf->k2k3,
+                                          nullptr);
+                if (rc) return rc;
+                rc = mvla_select_topk(ctx, score, buf->k2k3, B, n2, n3, nt, K, buf->kept_idx);
+                if (rc) return rc;
+                rc = mvla_compact(ctx, h, pos, buf->kept_idx, B, S, S_kept, cfg->D, buf->h_kept[0],
+                                  buf->pos_kept);
+                if (rc) return rc;
+            }
+        }
+    }
+    // ---- remaining layers: on every token at the cold start, else on the kept tokens --------
+    if (cold) {
+        for (int l = p; l < L; ++l) {
+            void* y = buf->h_full[l & 1];
+            rc = mvla_prefill_layer(ctx, cfg, &layers[l], h, pos, B, S, y, 0, nullptr, nullptr);
+            if (rc) return rc;
+            h = y;
+        }
+        *y_out = const_cast<void*>(h);
+        *rows_out = S;
+        return MVLA_OK;
+    }
+    h = buf->h_kept[0];
+    for (int l = p; l < L; ++l) {
+        void* y = buf->h_kept[(l - p + 1) & 1];
+        rc = mvla_prefill_layer(ctx, cfg, &layers[l], h, buf->pos_kept, B, S_kept, y, 0, nullptr,
+                                nullptr);
+        if (rc) return rc;
+        h = y;
+    }
+    *y_out = const_cast<void*>(h);
+    *rows_out = S_kept;
+    return MVLA_OK;
+}
+
 int mvla_tune_layers(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weights* layers,
                      int n_layers, int B, int S) {
     if (!ctx || !cfg || !layers || n_layers <= 0 || B <= 0 || S <= 0) return MVLA_EINVAL;
@@ -501,6 +621,7 @@ int mvla_tune_layers(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_
                                   true);
         if (rc) return rc;
     }
+    if ((size_t)B * S > (size_t)INT32_MAX / 4) return MVLA_EUNSUPPORTED;
     const int D = cfg->D, F = cfg->F, M = B * S;
     const LayerBuffers lb = layer_buffers(ctx->scratch, B, S, D, F);
     if (lb.bytes > ctx->scratch_bytes) return MVLA_ENOMEM;
@@ -534,6 +655,8 @@ int mvla_tune_layers(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_
     const int reps = n_layers < 4 ? 4 : (n_layers > 8 ? 8 : n_layers);
     static const int kSplitChoices[3] = {0, 50, 101};
     int rc = MVLA_OK;
+    mvla_ctx::Tuned found_best[4];   // recorded in the context only when all four jobs succeeded
+    int n_found = 0;
     for (const Job& j : jobs) {
         float best_ms = 0.f;
         int best_cfg = -1, best_pct = 0;
@@ -555,7 +678,7 @@ int mvla_tune_layers(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_
                                                     j.K, j.C, j.ldc, j.R, j.ldr, j.epi, GEMM_WS(ctx), c,
                                                     kSplitChoices[sp],
                                                     j.epi == EPI_QKV_ROPE ? &rope : nullptr, st);
-                        if (lrc) rc = lrc;
+                        if (lrc) rc = lrc;   // (configurations that cannot run were skipped above)
                     }
                     float t = 0.f;
                     if (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
@@ -569,19 +692,19 @@ int mvla_tune_layers(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_
                     best_pct = kSplitChoices[sp];
                 }
             }
-        if (rc != MVLA_OK) break;
-        bool found = false;
-        for (auto& t : ctx->tuned)
-            if (t.M == M && t.N == j.N && t.K == j.K && t.epi == j.epi) {
-                t.cfg = best_cfg;
-                t.split_pct = best_pct;
-                found = true;
-            }
-        if (!found) ctx->tuned.push_back({M, j.N, j.K, j.epi, best_cfg, best_pct});
+        if (rc != MVLA_OK || best_cfg < 0) {
+            if (rc == MVLA_OK) rc = MVLA_EUNSUPPORTED;   // no configuration runs this shape
+            break;
+        }
+        found_best[n_found++] = {M, j.N, j.K, j.epi, best_cfg, best_pct};
     }
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
-    return rc;
+    if (rc != MVLA_OK) return rc;
+    for (int i = 0; i < n_found; ++i)
+        (void)mvla_set_gemm_choice(ctx, found_best[i].M, found_best[i].N, found_best[i].K,
+                                   found_best[i].epi, found_best[i].cfg, found_best[i].split_pct);
+    return MVLA_OK;
 }
 
 int mvla_set_gemm_choice(mvla_ctx* ctx, int M, int N, int K, int epilogue, int cfg, int split_pct) {
@@ -612,6 +735,53 @@ int mvla_tuned_choice(mvla_ctx* ctx, int M, int N, int K, int epilogue, int* cfg
     return MVLA_OK;
 }
 
+int mvla_peak_probe(mvla_ctx* ctx, int kind, void* buf, size_t bytes, int reps, double* result) {
+    if (!ctx || !result || reps <= 0 || kind < 0 || kind > 3) return MVLA_EINVAL;
+    if (kind != MVLA_PROBE_LAUNCH && (!buf || !aligned(buf, 16))) return MVLA_EINVAL;
+    if ((kind == MVLA_PROBE_READ || kind == MVLA_PROBE_COPY) && bytes < (1u << 20)) return MVLA_EINVAL;
+    if (kind == MVLA_PROBE_MFMA && bytes < 8192) return MVLA_EINVAL;
+    hipStream_t st = ctx->stream;
+    const int n_cu = device_cu_count();
+    const int mfma_iters = 4096;
+    const size_t half = (bytes / 2) & ~(size_t)255;
+    auto launch = [&]() -> int {
+        switch (kind) {
+            case MVLA_PROBE_READ: return launch_probe_read(buf, bytes & ~(size_t)15, nullptr, st);
+            case MVLA_PROBE_COPY: return launch_probe_copy(buf, static_cast<char*>(buf) + half, half, st);
+            case MVLA_PROBE_MFMA: return launch_probe_mfma(buf, n_cu, mfma_iters, nullptr, st);
+            default: return launch_probe_empty(st);
+        }
+    };
+    int rc = launch();   // untimed first launch
+    if (rc) return rc;
+    hipEvent_t e0, e1;
+    MVLA_HIP_CHECK(hipEventCreate(&e0));
+    if (hipEventCreate(&e1) != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        return MVLA_EHIP;
+    }
+    float ms = 0.f;
+    if (hipEventRecord(e0, st) != hipSuccess) rc = MVLA_EHIP;
+    for (int r = 0; r < reps && rc == MVLA_OK; ++r) rc = launch();
+    if (rc == MVLA_OK && (hipEventRecord(e1, st) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                          hipEventElapsedTime(&ms, e0, e1) != hipSuccess))
+        rc = MVLA_EHIP;
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc) return rc;
+    const double sec = (double)ms * 1e-3 / reps;
+    switch (kind) {
+        case MVLA_PROBE_READ: *result = (double)(bytes & ~(size_t)15) / sec * 1e-9; break;
+        case MVLA_PROBE_COPY: *result = 2.0 * (double)half / sec * 1e-9; break;
+        case MVLA_PROBE_MFMA:
+            // per wave and iteration: 16 products of 32 x 32 x 16, two flops per multiply-add
+            *result = (double)n_cu * 4 * mfma_iters * 16 * (2.0 * 32 * 32 * 16) / sec * 1e-12;
+            break;
+        default: *result = sec * 1e6; break;
+    }
+    return MVLA_OK;
+}
+
 int mvla_score_only(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weights* w,
                     const void* x, const int32_t* pos, int B, int S, int n_query_tail,
                     const float* key_bias, float* probs_out) {
@@ -627,15 +797,32 @@ int mvla_score_only(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_w
     TIMED(ctx, KID_RMSNORM, M,
           launch_rmsnorm(static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(w->g_attn), M, D,
                          cfg->rms_eps, lb.u, st));
-    // query and key projections only (first 2D rows of wqkv), stored with row stride 2D
-    const RopeEpilogue rope = {pos, w->rope_cos, w->rope_sin, nullptr, w->rope_len, S, lb.S_pad, D, dh};
+    // Keys of every row: the key rows of wqkv on the normalised input, rotated, into the k
+    // buffer [M, D].  Queries of the scoring rows only: those rows are normalised once more
+    // into a compact [B*n_query_tail, D] matrix (with their position ids beside it), projected
+    // with the query rows of wqkv and rotated; the scoring kernel reads that compact q.
+    const bf16_t* wqkv = static_cast<const bf16_t*>(w->wqkv);
+    const int Mq = B * n_query_tail;
+    bf16_t* k_buf = lb.qkv;                       // [M, D]
+    bf16_t* q_buf = lb.qkv + (size_t)M * D;       // [Mq, D]
+    bf16_t* u_tail = lb.attn;                     // [Mq, D]  (attention output buffer, unused here)
+    int32_t* pos_tail = reinterpret_cast<int32_t*>(lb.x1);   // [Mq]
+    const RopeEpilogue rope_k = {pos, w->rope_cos, w->rope_sin, nullptr, w->rope_len, S, lb.S_pad, D, dh};
     TIMED(ctx, KID_GEMM_QKV, M,
-          launch_gemm(lb.u, D, static_cast<const bf16_t*>(w->wqkv), M, 2 * D, D, lb.qkv, 2 * D,
-                      nullptr, 0, EPI_QKV_ROPE, GEMM_WS(ctx),
-                      GEMM_PICK(ctx, M, 2 * D, D, EPI_QKV_ROPE), &rope, st));
+          launch_gemm(lb.u, D, wqkv + (size_t)D * D, M, D, D, k_buf, D, nullptr, 0, EPI_QKV_ROPE,
+                      GEMM_WS(ctx), GEMM_PICK(ctx, M, D, D, EPI_QKV_ROPE), &rope_k, st));
+    TIMED(ctx, KID_RMSNORM, Mq,
+          launch_rmsnorm_tail(static_cast<const bf16_t*>(x), pos, static_cast<const bf16_t*>(w->g_attn),
+                              B, S, n_query_tail, D, cfg->rms_eps, u_tail, pos_tail, st));
+    const int nq_pad = (n_query_tail + 7) / 8 * 8;
+    const RopeEpilogue rope_q = {pos_tail, w->rope_cos, w->rope_sin, nullptr, w->rope_len,
+                                 n_query_tail, nq_pad, D, dh};
+    TIMED(ctx, KID_GEMM_QKV, Mq,
+          launch_gemm(u_tail, D, wqkv, Mq, D, D, q_buf, D, nullptr, 0, EPI_QKV_ROPE, GEMM_WS(ctx),
+                      GEMM_PICK(ctx, Mq, D, D, EPI_QKV_ROPE), &rope_q, st));
     TIMED(ctx, KID_SCORE_PROBS, M,
-          launch_score_probs(lb.qkv, 2 * D, lb.qkv + D, 2 * D, key_bias, B, S, H, dh,
-                             n_query_tail, probs_out, 0, st));
+          launch_score_probs(q_buf, D, true, k_buf, D, key_bias, B, S, H, dh, n_query_tail,
+                             probs_out, 0, st));
     return MVLA_OK;
 }
 

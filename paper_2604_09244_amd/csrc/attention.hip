@@ -29,7 +29,7 @@ constexpr int ATT_KT = 64;   // keys per tile
 __device__ __forceinline__ void att_dma16(const void* base, uint32_t off, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_addr),
                  "v"(off), "s"(base)
-                 : "memory");
+                 : "memory", "m0");
 }
 template <int N>
 __device__ __forceinline__ void att_wait_vm() {
@@ -285,8 +285,14 @@ static int launch_att(const bf16_t* q, const bf16_t* k, int ldqkv, const bf16_t*
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)DH);
     const size_t lds = (size_t)NS * (ATT_KT * (DH / 8) + DH * 8) * sizeof(uint4);
     auto kern = attention_kernel<DH, NS>;
-    MVLA_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    static bool lds_set[kMaxDevices] = {};   // the dynamic-LDS limit is raised once per device
+    int dev = 0;
+    MVLA_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices || !lds_set[dev]) {
+        MVLA_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+        if (dev >= 0 && dev < kMaxDevices) lds_set[dev] = true;
+    }
     hipLaunchKernelGGL(kern, grid, dim3(ATT_THREADS), lds, st, q, k, ldqkv, vt, S_pad, S, H,
                        scale_log2e, out, ldo);
     MVLA_HIP_CHECK(hipGetLastError());

@@ -46,6 +46,7 @@ struct mvla_ctx {
     std::vector<Tuned> tuned;
 };
 
+constexpr int kMaxDevices = 64;   // per-device one-time set-up flags
 constexpr int kCounterWords = 16384;
 constexpr size_t kCounterBytes = size_t(kCounterWords) * 4;
 
@@ -95,11 +96,16 @@ int launch_rmsnorm(const bf16_t* x, const bf16_t* gain, int M, int D, float eps,
                    hipStream_t st);
 int launch_rmsnorm_f32(const float* x, const bf16_t* gain, int M, int D, float eps, bf16_t* out,
                        hipStream_t st);
+// the last `tail` rows of each of B samples of S rows, normalised into out [B*tail, D]; their
+// position ids into pos_out [B*tail]
+int launch_rmsnorm_tail(const bf16_t* x, const int32_t* pos, const bf16_t* gain, int B, int S,
+                        int tail, int D, float eps, bf16_t* out, int32_t* pos_out, hipStream_t st);
 int launch_rope_table(double base, int rope_len, int dh, float* c, float* s, hipStream_t st);
-// scoring probabilities of the last nq rows: probs [B,H,nq,S] fp32
-int launch_score_probs(const bf16_t* q, int q_row_stride, const bf16_t* k, int k_row_stride,
-                       const float* key_bias, int B, int S, int H, int dh, int nq, float* out,
-                       int colsum_n, hipStream_t st);
+// scoring probabilities of the last nq rows: probs [B,H,nq,S] fp32.  q_tail_only: q holds just
+// those rows, nq per sample ([B*nq, q_row_stride]); otherwise all S rows of every sample.
+int launch_score_probs(const bf16_t* q, int q_row_stride, bool q_tail_only, const bf16_t* k,
+                       int k_row_stride, const float* key_bias, int B, int S, int H, int dh, int nq,
+                       float* out, int colsum_n, hipStream_t st);
 
 // gemm.hip:  C[M,N] = A[M,K] * W[N,K]^T  (bf16 in, fp32 accumulate)
 // EPI_QKV_ROPE: the q/k/v projection (N = 3D, or 2D for q and k alone).  Columns [0, 2D) are
@@ -121,6 +127,8 @@ struct RopeEpilogue {
 // partial: fp32 scratch of gemm_partial_bytes() for K-split tiles; counters: n_counters zeroed
 // arrival counters (left at zero again when the kernel ends).
 size_t gemm_partial_bytes();
+// compute units of the current device (256 when it cannot be asked, e.g. no device present)
+int device_cu_count();
 int launch_gemm(const bf16_t* A, int lda, const bf16_t* W, int M, int N, int K, void* C, int ldc,
                 const void* R, int ldr, int epilogue, float* partial, size_t partial_bytes,
                 uint32_t* counters, int n_counters, int force_cfg, int force_split_pct,
@@ -128,6 +136,12 @@ int launch_gemm(const bf16_t* A, int lda, const bf16_t* W, int M, int N, int K, 
 int gemm_num_configs();
 // whether tile configuration cfg can run this epilogue (the rotating one needs whole heads per tile)
 bool gemm_config_runs(int cfg, int epilogue, const RopeEpilogue* rope);
+
+// probe_kernels.hip: measurement kernels (streaming read / copy, matrix-core loop, empty launch)
+int launch_probe_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t st);
+int launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t st);
+int launch_probe_mfma(const void* operands, int n_cu, int iters, float* sink, hipStream_t st);
+int launch_probe_empty(hipStream_t st);
 
 // attention.hip: causal flash attention; q,k rows inside qkv (row stride ldqkv), vt [B,H,dh,S_pad]
 int launch_attention(const bf16_t* q, const bf16_t* k, int ldqkv, const bf16_t* vt, int S_pad,

@@ -43,7 +43,7 @@ namespace mvla {
 __device__ __forceinline__ void dma16(const void* g, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_addr),
                  "v"(g)
-                 : "memory");
+                 : "memory", "m0");
 }
 template <int N>
 __device__ __forceinline__ void wait_vm() {
@@ -666,7 +666,21 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
 }
 
 // ---- host side ------------------------------------------------------------------------------
-constexpr int kNumCUs = 256;
+// Compute units of the current device: sets how many workgroups are resident at once (the round
+// size of the tile plan) and the size of the K-split partial buffer.  Asked once; 256 (MI355X)
+// when there is no device to ask.
+int device_cu_count() {
+    static int cached = 0;
+    if (cached > 0) return cached;
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
+        (void)hipGetLastError();
+        return 256;
+    }
+    cached = n;
+    return n;
+}
 
 // Split of the tile set into whole-tile workgroups and K-split workgroups for `slots`
 // concurrently resident workgroups.
@@ -703,7 +717,7 @@ static int launch_cfg(const bf16_t* A, int lda, const bf16_t* W, int M, int N, i
                       float* partial, size_t partial_bytes, uint32_t* counters, int n_counters,
                       const RopeEpilogue& rope, hipStream_t st) {
     constexpr bool has_sk = !(WM * WN == 4 && ((BM / 32 + WM - 1) / WM) * (BN / WN / 32) >= 15);
-    GemmPlan plan = make_plan(M, N, K, BM, BN, BK, kNumCUs * slots_per_cu, has_sk ? sk_pct : 0);
+    GemmPlan plan = make_plan(M, N, K, BM, BN, BK, device_cu_count() * slots_per_cu, has_sk ? sk_pct : 0);
     if (plan.sk_blocks > 0) {
         const size_t need = (size_t)2 * plan.sk_blocks * BM * BN * sizeof(float);
         if (need > partial_bytes || plan.sk_tiles > n_counters) {  // no room: whole tiles only
@@ -717,12 +731,20 @@ static int launch_cfg(const bf16_t* A, int lda, const bf16_t* W, int M, int N, i
     const size_t epi_bytes = EpiGeom<BM, BN, WM, NS>::BYTES;
     const size_t lds = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
     dim3 block(WM * WN * 64);
+    // the dynamic-LDS limit of a kernel is raised once per device (the size is a constant of the
+    // instantiation), not on every launch
 #define MVLA_GEMM_LAUNCH(E)                                                                   \
     do {                                                                                      \
         auto kern = gemm_kernel<BM, BN, BK, WM, WN, NS, E>;                                       \
-        MVLA_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),               \
-                                           hipFuncAttributeMaxDynamicSharedMemorySize,        \
-                                           (int)lds));                                        \
+        static bool lds_set[kMaxDevices] = {};                                                \
+        int dev = 0;                                                                          \
+        MVLA_HIP_CHECK(hipGetDevice(&dev));                                                   \
+        if (dev < 0 || dev >= kMaxDevices || !lds_set[dev]) {                                 \
+            MVLA_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),           \
+                                               hipFuncAttributeMaxDynamicSharedMemorySize,    \
+                                               (int)lds));                                    \
+            if (dev >= 0 && dev < kMaxDevices) lds_set[dev] = true;                           \
+        }                                                                                     \
         hipLaunchKernelGGL(kern, dim3(grid), block, lds, st, A, lda, W, M, N, K, C, ldc, R,   \
                            ldr, plan, partial, counters, rope);                               \
     } while (0)
@@ -737,7 +759,7 @@ static int launch_cfg(const bf16_t* A, int lda, const bf16_t* W, int M, int N, i
 
 size_t gemm_partial_bytes() {
     // two partial tiles per K-split workgroup; 256x256 tiles on 256 slots == 128x128 on 512
-    return (size_t)2 * kNumCUs * 256 * 256 * sizeof(float);
+    return (size_t)2 * device_cu_count() * 256 * 256 * sizeof(float);
 }
 
 // Tile configurations and the time one round of them takes at K = 4096 on this chip (measured
@@ -768,7 +790,7 @@ constexpr float kSplitOverhead = 0.3f;  // cost of the partial-sum exchange, in 
 // round either as a full round or, when K-split, as its fill fraction plus the exchange cost.
 static float estimate_us(const TileCfg& c, int M, int N, int K) {
     const long tiles = (long)((M + c.BM - 1) / c.BM) * ((N + c.BN - 1) / c.BN);
-    const int slots = kNumCUs * c.slots_per_cu;
+    const int slots = device_cu_count() * c.slots_per_cu;
     const long full = tiles / slots, rem = tiles % slots;
     float rounds = (float)full;
     if (rem)
@@ -805,7 +827,8 @@ int launch_gemm(const bf16_t* A, int lda, const bf16_t* W, int M, int N, int K, 
         if (!rope || !rope->pos || !rope->rc || !rope->rs || rope->S <= 0 || rope->rope_len <= 0)
             return MVLA_EINVAL;
         if ((rope->dh != 64 && rope->dh != 128) || rope->D % rope->dh != 0) return MVLA_EUNSUPPORTED;
-        if (N != 3 * rope->D && N != 2 * rope->D) return MVLA_EINVAL;
+        // N = 3D: q, k, v; N = 2D: q and k; N = D: one of q, k alone (W points at its rows)
+        if (N != 3 * rope->D && N != 2 * rope->D && N != rope->D) return MVLA_EINVAL;
         if ((N == 3 * rope->D) != (rope->vt != nullptr)) return MVLA_EINVAL;
         if (M % rope->S != 0 || rope->S_pad < rope->S || rope->S_pad % 8 != 0) return MVLA_EINVAL;
     }

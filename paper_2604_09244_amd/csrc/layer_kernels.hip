@@ -26,13 +26,20 @@ __device__ __forceinline__ float block_sum(float v, float* sh) {
 }
 
 // IN_F32: the row is fp32 (the mid-layer residual stream), else bf16.
+// tail > 0: output row r is input row (r / tail) * S + S - tail + r % tail (the last `tail`
+// rows of every sample of S rows), and its position id is copied to pos_out[r].
 template <bool IN_F32>
 __global__ __launch_bounds__(NORM_THREADS) void rmsnorm_kernel(const void* __restrict__ xv,
                                                                const uint4* __restrict__ gain,
                                                                int row_vec /* D/8 */, float inv_d,
-                                                               float eps, uint4* __restrict__ out) {
+                                                               float eps, uint4* __restrict__ out,
+                                                               int S, int tail,
+                                                               const int32_t* __restrict__ pos,
+                                                               int32_t* __restrict__ pos_out) {
     __shared__ float sh[NORM_THREADS / 64];
-    const int row = blockIdx.x, tid = threadIdx.x;
+    const int orow = blockIdx.x, tid = threadIdx.x;
+    const int row = tail > 0 ? (orow / tail) * S + (S - tail) + orow % tail : orow;
+    if (tail > 0 && tid == 0) pos_out[orow] = pos[row];
     float vals[NORM_MAX_CHUNKS][8];
     float ss = 0.f;
 #pragma unroll
@@ -59,7 +66,7 @@ __global__ __launch_bounds__(NORM_THREADS) void rmsnorm_kernel(const void* __res
     }
     ss = block_sum(ss, sh);
     const float scale = 1.0f / sqrtf(ss * inv_d + eps);
-    uint4* orow = out + (size_t)row * row_vec;
+    uint4* optr = out + (size_t)orow * row_vec;
 #pragma unroll
     for (int k = 0; k < NORM_MAX_CHUNKS; ++k) {
         const int c = tid + k * NORM_THREADS;
@@ -71,7 +78,7 @@ __global__ __launch_bounds__(NORM_THREADS) void rmsnorm_kernel(const void* __res
             for (int i = 0; i < 4; ++i)
                 r[i] = pack_bf16x2(vals[k][2 * i] * scale * __uint_as_float(gw[i] << 16),
                                    vals[k][2 * i + 1] * scale * __uint_as_float(gw[i] & 0xFFFF0000u));
-            orow[c] = make_uint4(r[0], r[1], r[2], r[3]);
+            optr[c] = make_uint4(r[0], r[1], r[2], r[3]);
         }
     }
 }
@@ -83,11 +90,23 @@ static int launch_rmsnorm_any(const void* x, bool f32, const bf16_t* gain, int M
     if (f32)
         hipLaunchKernelGGL(rmsnorm_kernel<true>, dim3(M), dim3(NORM_THREADS), 0, st, x,
                            reinterpret_cast<const uint4*>(gain), D / 8, 1.0f / (float)D, eps,
-                           reinterpret_cast<uint4*>(out));
+                           reinterpret_cast<uint4*>(out), 0, 0, nullptr, nullptr);
     else
         hipLaunchKernelGGL(rmsnorm_kernel<false>, dim3(M), dim3(NORM_THREADS), 0, st, x,
                            reinterpret_cast<const uint4*>(gain), D / 8, 1.0f / (float)D, eps,
-                           reinterpret_cast<uint4*>(out));
+                           reinterpret_cast<uint4*>(out), 0, 0, nullptr, nullptr);
+    MVLA_HIP_CHECK(hipGetLastError());
+    return MVLA_OK;
+}
+
+int launch_rmsnorm_tail(const bf16_t* x, const int32_t* pos, const bf16_t* gain, int B, int S,
+                        int tail, int D, float eps, bf16_t* out, int32_t* pos_out, hipStream_t st) {
+    if (B <= 0 || tail <= 0) return MVLA_OK;
+    if (D % 8 != 0 || D / 8 > NORM_THREADS * NORM_MAX_CHUNKS) return MVLA_EUNSUPPORTED;
+    if (tail > S || !pos || !pos_out) return MVLA_EINVAL;
+    hipLaunchKernelGGL(rmsnorm_kernel<false>, dim3(B * tail), dim3(NORM_THREADS), 0, st, x,
+                       reinterpret_cast<const uint4*>(gain), D / 8, 1.0f / (float)D, eps,
+                       reinterpret_cast<uint4*>(out), S, tail, pos, pos_out);
     MVLA_HIP_CHECK(hipGetLastError());
     return MVLA_OK;
 }
@@ -140,8 +159,8 @@ constexpr int SC_THREADS = 256;
 // reduction then runs over H * tiles short rows and the [B,H,nq,S] tensor never exists.
 template <int DH, bool COLSUM>
 __global__ __launch_bounds__(SC_THREADS) void score_probs_kernel(
-    const bf16_t* __restrict__ q, int ldq, const bf16_t* __restrict__ k, int ldk,
-    const float* __restrict__ key_bias, int S, int H, int nq, float scale,
+    const bf16_t* __restrict__ q, int ldq, int q_rows /* per sample */, const bf16_t* __restrict__ k,
+    int ldk, const float* __restrict__ key_bias, int S, int H, int nq, float scale,
     float* __restrict__ probs, int n_out) {
     constexpr int STEPS = DH / 16;
     const int qt = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
@@ -154,7 +173,8 @@ __global__ __launch_bounds__(SC_THREADS) void score_probs_kernel(
     uint4 qf[STEPS];
     {
         const int qi = min(qi0 + fr, nq - 1);
-        const bf16_t* src = q + ((size_t)b * S + row0 + qi) * ldq + h * DH + fg * 8;
+        // q holds either all S rows of a sample or only its nq scoring rows
+        const bf16_t* src = q + ((size_t)b * q_rows + (q_rows - nq) + qi) * ldq + h * DH + fg * 8;
 #pragma unroll
         for (int st = 0; st < STEPS; ++st) qf[st] = *reinterpret_cast<const uint4*>(src + st * 16);
     }
@@ -261,8 +281,8 @@ constexpr int SCR_WAVES = SCR_THREADS / 64;
 
 template <int DH, int KBW, bool COLSUM>
 __global__ __launch_bounds__(SCR_THREADS) void score_probs_reg_kernel(
-    const bf16_t* __restrict__ q, int ldq, const bf16_t* __restrict__ k, int ldk,
-    const float* __restrict__ key_bias, int S, int H, int nq, float scale,
+    const bf16_t* __restrict__ q, int ldq, int q_rows /* per sample */, const bf16_t* __restrict__ k,
+    int ldk, const float* __restrict__ key_bias, int S, int H, int nq, float scale,
     float* __restrict__ probs, int n_out) {
     constexpr int STEPS = DH / 16;
     const int qt = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
@@ -272,7 +292,8 @@ __global__ __launch_bounds__(SCR_THREADS) void score_probs_reg_kernel(
     uint4 qf[STEPS];
     {
         const int qi = min(qi0 + fr, nq - 1);
-        const bf16_t* src = q + ((size_t)b * S + row0 + qi) * ldq + h * DH + fg * 8;
+        // q holds either all S rows of a sample or only its nq scoring rows
+        const bf16_t* src = q + ((size_t)b * q_rows + (q_rows - nq) + qi) * ldq + h * DH + fg * 8;
 #pragma unroll
         for (int st = 0; st < STEPS; ++st) qf[st] = *reinterpret_cast<const uint4*>(src + st * 16);
     }
@@ -388,14 +409,14 @@ __global__ __launch_bounds__(SCR_THREADS) void score_probs_reg_kernel(
 }
 
 template <int DH, bool COLSUM>
-static bool launch_score_reg(const bf16_t* q, int ldq, const bf16_t* k, int ldk,
+static bool launch_score_reg(const bf16_t* q, int ldq, int q_rows, const bf16_t* k, int ldk,
                              const float* key_bias, int B, int S, int H, int nq, float scale,
                              float* out, int n_out, hipStream_t st) {
     dim3 grid((nq + 31) / 32, H, B);
     const int need = ((S + 31) / 32 + SCR_WAVES - 1) / SCR_WAVES;  // key blocks per wave
 #define MVLA_SCR(KBW)                                                                       \
     hipLaunchKernelGGL((score_probs_reg_kernel<DH, KBW, COLSUM>), grid, dim3(SCR_THREADS), 0, st, \
-                       q, ldq, k, ldk, key_bias, S, H, nq, scale, out, n_out)
+                       q, ldq, q_rows, k, ldk, key_bias, S, H, nq, scale, out, n_out)
     if (need <= 3) MVLA_SCR(3);
     else if (need <= 6) MVLA_SCR(6);
     else if (need <= 8) MVLA_SCR(8);
@@ -405,27 +426,29 @@ static bool launch_score_reg(const bf16_t* q, int ldq, const bf16_t* k, int ldk,
 }
 
 template <int DH, bool COLSUM>
-static void launch_score_dh(const bf16_t* q, int ldq, const bf16_t* k, int ldk,
+static void launch_score_dh(const bf16_t* q, int ldq, int q_rows, const bf16_t* k, int ldk,
                             const float* key_bias, int B, int S, int H, int nq, float scale,
                             float* out, int n_out, hipStream_t st) {
     // register-resident single pass when the row fits, else two passes
-    if (launch_score_reg<DH, COLSUM>(q, ldq, k, ldk, key_bias, B, S, H, nq, scale, out, n_out, st))
+    if (launch_score_reg<DH, COLSUM>(q, ldq, q_rows, k, ldk, key_bias, B, S, H, nq, scale, out, n_out,
+                                     st))
         return;
     dim3 grid((nq + 31) / 32, H, B);
-    hipLaunchKernelGGL((score_probs_kernel<DH, COLSUM>), grid, dim3(SC_THREADS), 0, st, q, ldq, k,
-                       ldk, key_bias, S, H, nq, scale, out, n_out);
+    hipLaunchKernelGGL((score_probs_kernel<DH, COLSUM>), grid, dim3(SC_THREADS), 0, st, q, ldq, q_rows,
+                       k, ldk, key_bias, S, H, nq, scale, out, n_out);
 }
 
 // colsum_n == 0: out = probabilities [B,H,nq,S]; colsum_n > 0: out = per-tile column sums
 // [B, H, ceil(nq/32), colsum_n] over the first colsum_n key columns.
-int launch_score_probs(const bf16_t* q, int q_row_stride, const bf16_t* k, int k_row_stride,
-                       const float* key_bias, int B, int S, int H, int dh, int nq, float* out,
-                       int colsum_n, hipStream_t st) {
+int launch_score_probs(const bf16_t* q, int q_row_stride, bool q_tail_only, const bf16_t* k,
+                       int k_row_stride, const float* key_bias, int B, int S, int H, int dh, int nq,
+                       float* out, int colsum_n, hipStream_t st) {
     if (B <= 0 || nq <= 0) return MVLA_OK;
     const float scale = 1.0f / sqrtf((float)dh);
+    const int q_rows = q_tail_only ? nq : S;
 #define MVLA_SC(DH_, CS_)                                                                       \
-    launch_score_dh<DH_, CS_>(q, q_row_stride, k, k_row_stride, key_bias, B, S, H, nq, scale, out, \
-                              colsum_n, st)
+    launch_score_dh<DH_, CS_>(q, q_row_stride, q_rows, k, k_row_stride, key_bias, B, S, H, nq, scale, \
+                              out, colsum_n, st)
     if (dh == 128) {
         if (colsum_n > 0) MVLA_SC(128, true); else MVLA_SC(128, false);
     } else if (dh == 64) {

@@ -71,8 +71,10 @@ def test_smoothed_selection_in_an_episode(ctx):
         kb = W.scoring_bias(wl, device="cuda", step=t)
         y = plan.run(x, pos, kb, smooth_step=t)
         torch.cuda.synchronize()
-        # the raw salience of this step (recomputed: the plan overwrote its buffer with the state)
-        sal_t = ctx.salience(plan.probs, wl.n_vis).cpu().numpy()
+        # the raw salience of this step stays in the plan's buffer (selection reads the smoothed
+        # state in place); it is what mvla_salience gives for the written probabilities
+        assert torch.equal(ctx.salience(plan.probs, wl.n_vis), plan.prune["sal"])
+        sal_t = plan.prune["sal"].cpu().numpy()
         ref_hat = O.ema_indicator(ref_hat, sal_t, t)
         got = plan.sal_hat.cpu().numpy()
         assert np.max(np.abs(got - ref_hat) / ref_hat) <= 5e-6, t
