@@ -38,7 +38,8 @@ typedef enum {
     MVLA_EINVAL = -1,       /* null pointer, bad shape, bad alignment             */
     MVLA_ENOMEM = -2,       /* workspace too small for the requested shape        */
     MVLA_EHIP = -3,         /* HIP runtime / launch failure                       */
-    MVLA_EUNSUPPORTED = -4  /* shape outside what the kernels are built for       */
+    MVLA_EUNSUPPORTED = -4, /* shape outside what the kernels are built for       */
+    MVLA_ELIMIT = -5        /* shape beyond the fixed scratch of mvla_salience_noalloc */
 } mvla_status;
 
 typedef struct mvla_ctx mvla_ctx; /* opaque */
@@ -78,6 +79,22 @@ void mvla_destroy(mvla_ctx* ctx);
  * Summation order is fixed, so results are bit-reproducible run to run. */
 int mvla_salience(mvla_ctx* ctx, const float* attn, int B, int H, int Nq, int S, int n_vis,
                   float* sal);
+
+/* mvla_salience for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Takes no context: the kernel's scratch (row-split partial
+ * sums and arrival counters) is a fixed array inside the library, 16 MiB +
+ * 32 KiB on each GPU the call is used on, held until the process ends.  The
+ * call allocates nothing, enqueues two kernels on hip_stream (borrowed; NULL =
+ * default stream) of the current device and returns; results are identical to
+ * mvla_salience.  Shapes whose scratch need exceeds the array -- more than
+ * (n_vis + 64) * (H*Nq/32 + 2) * B floats of partial sums in 16 MiB, or more
+ * than 8192 (sample, 64-column chunk) pairs -- are rejected with MVLA_ELIMIT
+ * (all five workload shapes of the paper's setup fit).  All calls on one GPU
+ * share the array: calls that overlap in time on one GPU (two streams, two
+ * threads) race; issue them on one stream or order them yourself. */
+int mvla_salience_noalloc(void* hip_stream, const float* attn, int B, int H, int Nq, int S,
+                          int n_vis, float* sal);
 
 /* Split the visual keep budget between modalities by salience mass (Eq. 5:
  * m2 = |a_2D|_1 / (|a_2D|_1 + |a_3D|_1); Sec. 5.2: per-modality pruning

@@ -26,7 +26,7 @@ EXPORTS = [
     "mvla_modality_decompose", "mvla_feature_share", "mvla_mask_rules_default",
     "mvla_candidate_masks", "mvla_mask_indices", "mvla_prefill_layer_salience",
     "mvla_prefill_layer_prune", "mvla_tune_layers", "mvla_tuned_choice",
-    "mvla_set_gemm_choice", "mvla_prefill", "mvla_peak_probe",
+    "mvla_set_gemm_choice", "mvla_prefill", "mvla_peak_probe", "mvla_salience_noalloc",
 ]
 
 
@@ -103,6 +103,7 @@ def load() -> C.CDLL:
     lib.mvla_destroy.argtypes = [vp]
     lib.mvla_destroy.restype = None
     lib.mvla_salience.argtypes = [vp, vp, i, i, i, i, i, vp]
+    lib.mvla_salience_noalloc.argtypes = [vp, vp, i, i, i, i, i, vp]
     lib.mvla_modality_budget.argtypes = [vp, vp, i, i, i, i, i, i, vp, vp]
     lib.mvla_select_topk.argtypes = [vp, vp, vp, i, i, i, i, i, vp]
     lib.mvla_compact.argtypes = [vp, vp, vp, vp, i, i, i, i, vp, vp]
@@ -152,6 +153,17 @@ def _ptr(t: Optional[torch.Tensor]):
 def _dev(t: torch.Tensor, dtype) -> torch.Tensor:
     assert t.is_cuda and t.dtype == dtype and t.is_contiguous(), (t.device, t.dtype)
     return t
+
+
+def salience_noalloc(attn: torch.Tensor, n_vis: int, out: torch.Tensor) -> torch.Tensor:
+    """mvla_salience_noalloc on the current stream: no context, no workspace; ``out`` [B, n_vis]
+    must exist already (this wrapper allocates nothing either)."""
+    B, H, Nq, S = _dev(attn, torch.float32).shape
+    assert _dev(out, torch.float32).shape == (B, n_vis)
+    stream = torch.cuda.current_stream(attn.device).cuda_stream
+    _check(load().mvla_salience_noalloc(stream, attn.data_ptr(), B, H, Nq, S, n_vis,
+                                        out.data_ptr()), "mvla_salience_noalloc")
+    return out
 
 
 def pack_layer(w: Dict[str, torch.Tensor]) -> Dict[str, torch.Tensor]:

@@ -157,6 +157,7 @@ const char* mvla_strerror(int code) {
         case MVLA_ENOMEM: return "workspace too small for this shape";
         case MVLA_EHIP: return "HIP runtime or launch failure";
         case MVLA_EUNSUPPORTED: return "shape not supported by the compiled kernels";
+        case MVLA_ELIMIT: return "shape exceeds the fixed scratch of the allocation-free entry point";
         default: return "unknown status";
     }
 }

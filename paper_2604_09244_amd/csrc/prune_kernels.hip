@@ -239,6 +239,61 @@ int launch_prune_fused(const float* attn, int B, int H, int Nq, int S, int n2, i
 }
 
 // ---------------------------------------------------------------------------
+// Salience without a context or workspace, for callers that cannot allocate
+// device memory (code under graph capture, serving loops): the row-split
+// partial sums and the arrival counters live in a fixed array of this module.
+// Every GPU holds its own copy of the array until the process ends.
+// ---------------------------------------------------------------------------
+constexpr size_t kStaticCounterBytes = size_t(kCounterWords / 2) * 4;   // 32 KiB of arrival counters
+constexpr size_t kStaticPartialBytes = size_t(16) << 20;                // 16 MiB of partial sums
+static __device__ __align__(256) unsigned char scratch[kStaticCounterBytes + kStaticPartialBytes];
+// device address of `scratch` on each GPU (the array's name is only a host-side handle)
+static void* g_scratch_addr[kMaxDevices] = {};
+
+__global__ void clear_words_kernel(uint32_t* p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+}  // namespace mvla
+
+extern "C" int mvla_salience_noalloc(void* hip_stream, const float* attn, int B, int H, int Nq, int S,
+                                     int n_vis, float* sal) {
+    using namespace mvla;
+    if (!attn || !sal) return MVLA_EINVAL;
+    if (B <= 0 || H <= 0 || Nq <= 0 || S <= 0 || n_vis <= 0 || n_vis > S) return MVLA_EINVAL;
+    if ((reinterpret_cast<uintptr_t>(attn) & 3) || (reinterpret_cast<uintptr_t>(sal) & 3))
+        return MVLA_EINVAL;
+    // the fixed scratch bounds the shape: partial sums and one counter per (sample, column chunk)
+    const bool vec4 = (S % 4 == 0) && ((reinterpret_cast<uintptr_t>(attn) & 15) == 0);
+    int chunks, n_split, rps;
+    salience_shape(B, H * Nq, n_vis, vec4 ? 4 : 1, &chunks, &n_split, &rps);
+    const long n_counters = (long)B * chunks + B;
+    if (salience_scratch_bytes(B, H, Nq, n_vis) > kStaticPartialBytes ||
+        n_counters > (long)(kStaticCounterBytes / 4))
+        return MVLA_ELIMIT;
+    int dev = 0;
+    MVLA_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return MVLA_EUNSUPPORTED;
+    if (!g_scratch_addr[dev]) {   // once per device, with that device current
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return MVLA_EHIP;
+        g_scratch_addr[dev] = p;
+    }
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    uint32_t* counters = static_cast<uint32_t*>(g_scratch_addr[dev]);
+    float* partial = reinterpret_cast<float*>(static_cast<char*>(g_scratch_addr[dev]) + kStaticCounterBytes);
+    // the array keeps whatever the last call left: the counters this call uses start at zero
+    // (a kernel, not a memset, so that the call can be recorded into a graph)
+    hipLaunchKernelGGL(clear_words_kernel, dim3((unsigned)((n_counters + 255) / 256)), dim3(256), 0, st,
+                       counters, (int)n_counters);
+    MVLA_HIP_CHECK(hipGetLastError());
+    return launch_salience(attn, B, H, Nq, S, n_vis, sal, partial, counters, 0, st);
+}
+
+namespace mvla {
+
+// ---------------------------------------------------------------------------
 // Modality budget (paper Eq. 5): fp64 masses per sample, integer split.
 // ---------------------------------------------------------------------------
 constexpr int BUD_THREADS = 256;
