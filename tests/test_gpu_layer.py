@@ -447,3 +447,19 @@ def test_every_projection_kernel_configuration(ctx, cfg_id, split_pct):
                            bf16_floor_layer(x64, p_np, ow, wl.H, wl.rms_eps, wl.rope_base))
         ref, floor = _CFG_REF[S]
         assert_layer_close(y[0], ref, f"config {cfg_id} split {split_pct} S={S}", wl.D, floor)
+
+
+@pytest.mark.parametrize("S", [237, 544])
+def test_layer_runs_are_bit_reproducible(ctx, S):
+    """The same layer call repeated: every run must give the same bits (K-split pieces are summed
+    in piece order, direct loads are waited for by count: a miscounted wait or an ordering that
+    depends on timing shows up here long before it shows in the tolerance)."""
+    wl = W.WORKLOADS["single_view"]
+    packed, struct = device_layer(ctx, wl, W.layer_weights(wl, 3))
+    x, pos = W.hidden_states(wl, device="cuda")
+    xs, ps = x[:, :S].contiguous(), pos[:, :S].contiguous()
+    first = ctx.prefill_layer(layer_cfg(wl), struct, xs, ps).clone()
+    for _ in range(8):
+        again = ctx.prefill_layer(layer_cfg(wl), struct, xs, ps)
+        torch.cuda.synchronize()
+        assert torch.equal(again, first)
