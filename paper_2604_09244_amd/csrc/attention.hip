@@ -55,8 +55,12 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_kernel(
 
     extern __shared__ uint4 lds[];
 
-    // heavier (later) query tiles first
-    const int qtile = gridDim.x - 1 - blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    // Workgroups are dispatched in blockIdx order, x fastest.  Heads run along x and query tiles
+    // along y, heavier (later) tiles first: a sample's tiles then start in order of decreasing
+    // work across all its heads (the light ones fill the end instead of a heavy tile of the last
+    // head starting late), and because the head count is a multiple of the 8 XCDs that workgroup
+    // ids are dealt to, every tile of a head runs on the same XCD and finds its K/V in that L2.
+    const int qtile = gridDim.y - 1 - blockIdx.y, h = blockIdx.x, b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int fr = lane & 31, fg = lane >> 5;
     const int q0 = qtile * ATT_QT;
@@ -281,7 +285,7 @@ __global__ __launch_bounds__(ATT_THREADS, 2) void attention_kernel(
 template <int DH, int NS>
 static int launch_att(const bf16_t* q, const bf16_t* k, int ldqkv, const bf16_t* vt, int S_pad,
                       int B, int S, int H, bf16_t* out, int ldo, hipStream_t st) {
-    dim3 grid((S + ATT_QT - 1) / ATT_QT, H, B);
+    dim3 grid(H, (S + ATT_QT - 1) / ATT_QT, B);
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)DH);
     const size_t lds = (size_t)NS * (ATT_KT * (DH / 8) + DH * 8) * sizeof(uint4);
     auto kern = attention_kernel<DH, NS>;
