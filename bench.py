@@ -33,12 +33,15 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled
-# by what the same counter shows for a plain copy of known size (see the *_hbm_traffic.txt files
-# under profiles/).  Valid only for the GEMM source and tile configuration the counters were
+# Memory-side bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE + WRITE_SIZE, each
+# scaled by what the same counter shows for a plain copy of known size (see the *_hbm_traffic.txt
+# files under profiles/).  Valid only for the GEMM source and tile configuration the counters were
 # taken with: keyed by kernel shape, with a hash of gemm.hip and the configuration index the
-# set-up measurement must have chosen; anything else reports null.
+# set-up measurement chose in this run; anything else reports null.
 MEASURED_TRAFFIC = {
+    # (kernel, M, N, K): (gemm.hip hash, {tile configuration: bytes per launch})
+    ("gemm_gateup", 21504, 22016, 4096): ("b0d77fac85f9c83c", {0: 7099.4e6, 4: 6928.6e6}),   # ratio_sweep, keep 50 %
+    ("gemm_gateup", 4688, 22016, 4096): ("b0d77fac85f9c83c", {4: 1586.1e6}),                  # multi_view
 }
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
@@ -220,8 +223,10 @@ def main():
     roofline["kernel"] = f"gemm_gateup M={dom_tag} N={2 * wl.F} K={wl.D}"
     meas = MEASURED_TRAFFIC.get(("gemm_gateup", dom_tag, 2 * wl.F, wl.D))
     dom_cfg = ctx.tuned_choice(dom_tag, 2 * wl.F, wl.D, 3)[0]
-    roofline["traffic"] = (meas[0] if meas and meas[1] == gemm_source_hash() and meas[2] == dom_cfg
-                           else None)
+    roofline["traffic"] = (meas[1].get(dom_cfg) if meas and meas[0] == gemm_source_hash() else None)
+    if roofline["traffic"]:
+        roofline["traffic_note"] = ("FETCH_SIZE + WRITE_SIZE at the memory-side port of the L2s "
+                                    "(Infinity Cache and HBM behind it), see profiles/")
     roofline["avg_us"] = dom_ms * 1e3
     roofline["launches"] = len(by_tag[dom_tag])
     roofline["share_of_step"] = sum(by_tag[dom_tag]) * 1e-3 / (K * sec_dom)
