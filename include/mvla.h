@@ -409,6 +409,54 @@ int mvla_prefill(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weig
                  const float* key_bias, const mvla_prefill_buffers* buffers, void** y_out,
                  int* rows_out);
 
+/* One action-iteration step of the paper's own mask generation (Algorithm 1,
+ * all three stages; needs one 3D token per 2D token: S = 2 n_patch + n_text,
+ * and p >= 1): p layers on all tokens (the p-th scores the language queries),
+ * the salience and the four per-patch indicators of this step (Eq. 1 on the
+ * output of layer p-1; Eqs. 5-6), their smoothing over steps (Eqs. 8-9), and
+ * for t > 1 the candidate sets, fusion and masks (Sec. 4.1, 4.2, 4.4, Eq. 10),
+ * the index scan, the gather, and the remaining layers on the kept tokens.
+ * t = 1 is the cold start: nothing is pruned.  The kept length differs per
+ * sample; rows are padded at the end up to the longest sample of the step. */
+typedef struct {
+    int B, n_patch, n_text, n_layers, p;
+    int t;                        /* timestep, from 1                                   */
+    int smooth_k;                 /* paper: 7                                           */
+    double smooth_beta;           /* paper: 0.85                                        */
+    mvla_mask_rules rules;
+} mvla_masked_desc;
+
+/* Device buffers of mvla_masked_prefill_step, caller-owned, pairwise disjoint. */
+typedef struct {
+    void* h_full[2];     /* bf16 [B, S, D] each                                          */
+    void* h_kept[2];     /* bf16 [B, S, D] each (used as [B, S_pad, D])                   */
+    float* probs;        /* fp32 [B, H, n_text, S]                                        */
+    float* sal;          /* fp32 [B, 2 n_patch]                                           */
+    float* x_t;          /* fp32 [4, B, n_patch]: this step's M2D^S1, M3D^S1, M2D^S2, M3D^S2 */
+    float* x_hat;        /* fp32 [4, B, n_patch]: smoothed state, read (t > 1) and updated */
+    uint8_t* mask2d;     /* uint8 [B, n_patch]                                            */
+    uint8_t* mask3d;     /* uint8 [B, n_patch]                                            */
+    uint8_t* sem;        /* uint8 [B, n_patch] or NULL                                    */
+    int32_t* kept_len;   /* int32 [B]                                                     */
+    int32_t* kept_idx;   /* int32 [B * S] (used as [B, S_pad])                            */
+    int32_t* pos_kept;   /* int32 [B * S] (used as [B, S_pad])                            */
+} mvla_masked_buffers;
+
+/* Enqueue the step: exactly the sequence of the single calls above, no
+ * arithmetic of its own.  u: device fp32 [B, n_patch] uniform draws of this
+ * step (unused at t = 1).  For t > 1 the call copies the B kept lengths to
+ * lengths_out (HOST int32 [B]) and SYNCHRONISES the stream once, because the
+ * padded length S_pad = max_b length sizes the launches that follow; it cannot
+ * be captured into a graph.  *y_out (host): device pointer of the final hidden
+ * states, [B, *rows_out, D] with *rows_out = S_pad (S at t = 1); row i of sample
+ * b is valid for i < lengths_out[b].  Everything is checked before the first
+ * launch. */
+int mvla_masked_prefill_step(mvla_ctx* ctx, const mvla_layer_cfg* cfg,
+                             const mvla_layer_weights* layers, const mvla_masked_desc* desc,
+                             const void* x, const int32_t* pos, const float* key_bias,
+                             const float* u, const mvla_masked_buffers* buffers, void** y_out,
+                             int* rows_out, int32_t* lengths_out);
+
 /* ------------------------------------------------------------------------ */
 /* Measurement (the paper's overhead study, Table 4, reports the pruning    */
 /* method's own cost apart from the step latency; these calls give the same */

@@ -26,7 +26,7 @@ EXPORTS = [
     "mvla_modality_decompose", "mvla_feature_share", "mvla_mask_rules_default",
     "mvla_candidate_masks", "mvla_mask_indices", "mvla_prefill_layer_salience",
     "mvla_prefill_layer_prune", "mvla_tune_layers", "mvla_tuned_choice",
-    "mvla_set_gemm_choice", "mvla_prefill", "mvla_peak_probe", "mvla_salience_noalloc",
+    "mvla_set_gemm_choice", "mvla_prefill", "mvla_peak_probe", "mvla_salience_noalloc", "mvla_masked_prefill_step",
 ]
 
 
@@ -80,6 +80,21 @@ class PrefillBuffers(C.Structure):
                 ("kept_idx", C.c_void_p), ("pos_kept", C.c_void_p)]
 
 
+class MaskedDesc(C.Structure):
+    """mvla_masked_desc."""
+    _fields_ = [("B", C.c_int), ("n_patch", C.c_int), ("n_text", C.c_int), ("n_layers", C.c_int),
+                ("p", C.c_int), ("t", C.c_int), ("smooth_k", C.c_int), ("smooth_beta", C.c_double),
+                ("rules", MaskRules)]
+
+
+class MaskedBuffers(C.Structure):
+    """mvla_masked_buffers."""
+    _fields_ = [("h_full", C.c_void_p * 2), ("h_kept", C.c_void_p * 2), ("probs", C.c_void_p),
+                ("sal", C.c_void_p), ("x_t", C.c_void_p), ("x_hat", C.c_void_p),
+                ("mask2d", C.c_void_p), ("mask3d", C.c_void_p), ("sem", C.c_void_p),
+                ("kept_len", C.c_void_p), ("kept_idx", C.c_void_p), ("pos_kept", C.c_void_p)]
+
+
 PROBE_READ, PROBE_COPY, PROBE_MFMA, PROBE_LAUNCH = 0, 1, 2, 3
 
 
@@ -122,6 +137,10 @@ def load() -> C.CDLL:
     lib.mvla_prefill.argtypes = [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeightsC),
                                  C.POINTER(PrefillDesc), vp, vp, vp, C.POINTER(PrefillBuffers),
                                  C.POINTER(vp), C.POINTER(i)]
+    lib.mvla_masked_prefill_step.argtypes = [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeightsC),
+                                             C.POINTER(MaskedDesc), vp, vp, vp, vp,
+                                             C.POINTER(MaskedBuffers), C.POINTER(vp),
+                                             C.POINTER(i), vp]
     lib.mvla_peak_probe.argtypes = [vp, i, vp, sz, i, C.POINTER(C.c_double)]
     lib.mvla_score_only.argtypes = [vp, C.POINTER(LayerCfg), C.POINTER(LayerWeightsC), vp, vp,
                                     i, i, i, vp, vp]
@@ -551,10 +570,11 @@ class PrefillPlan:
 
 class MaskedPrefill:
     """One episode of action iterations with the masks of Algorithm 1 (needs one 3D token per
-    2D token and p >= 1).  Each ``step`` enqueues: p layers on all tokens, the four per-patch
-    indicators, their smoothing, and for t > 1 the masks, the index scan, the gather and the
-    remaining layers.  The kept length differs per sample; rows are padded at the end up to
-    the longest sample of the step, which takes one read-back of B integers."""
+    2D token and p >= 1): buffers for mvla_masked_prefill_step, which sequences the step (p
+    layers on all tokens, the four per-patch indicators, their smoothing, and for t > 1 the
+    masks, the index scan, the gather and the remaining layers).  The kept length differs per
+    sample; rows are padded at the end up to the longest sample of the step, which takes one
+    read-back of B integers inside the call."""
 
     def __init__(self, plan: PrefillPlan, rules: Optional[MaskRules] = None, k: int = 7,
                  beta: float = 0.85):
@@ -574,43 +594,43 @@ class MaskedPrefill:
         self.kept_idx = torch.empty(B * S, dtype=i32, device=dev)
         self.pos_kept = torch.empty(B * S, dtype=i32, device=dev)
         self.h_kept = [torch.empty(B * S * D, dtype=torch.bfloat16, device=dev) for _ in range(2)]
+        two = C.c_void_p * 2
+        self._buffers = MaskedBuffers(two(*[t.data_ptr() for t in plan.h_full]),
+                                      two(*[t.data_ptr() for t in self.h_kept]),
+                                      plan.probs.data_ptr(), self.sal.data_ptr(),
+                                      self.x_t.data_ptr(), self.x_hat.data_ptr(),
+                                      self.mask2d.data_ptr(), self.mask3d.data_ptr(),
+                                      self.sem.data_ptr(), self.kept_len.data_ptr(),
+                                      self.kept_idx.data_ptr(), self.pos_kept.data_ptr())
 
     def step(self, t: int, x: torch.Tensor, pos: torch.Tensor, u: torch.Tensor,
              key_bias: Optional[torch.Tensor] = None):
-        """Timestep t (1-based).  Returns (y [B, S_pad, D], lengths): row i of sample b is valid
-        for i < lengths[b]; at t == 1 nothing is pruned."""
+        """Timestep t (1-based): one call of mvla_masked_prefill_step.  Returns
+        (y [B, S_pad, D], lengths): row i of sample b is valid for i < lengths[b]; at t == 1
+        nothing is pruned."""
         pl = self.plan
-        ctx, cfg, B, P, D = pl.ctx, pl.cfg, pl.B, self.P, pl.cfg.D
-        h = x
-        for li in range(pl.p):
-            tail = pl.nt if li == pl.p - 1 else 0
-            y = pl.h_full[li & 1]
-            ctx.prefill_layer(cfg, pl.structs[li], h, pos, y, tail, key_bias,
-                              pl.probs if tail else None)
-            h = y
-        ctx.salience(pl.probs, 2 * P, out=self.sal)
-        ctx.feature_share(h, P, out=(self.x_t[0], self.x_t[1]))
-        ctx.modality_decompose(pl.probs, P, out=(self.x_t[2], self.x_t[3]))
-        ctx.temporal_smooth(self.x_t, self.x_hat, t, self.k, self.beta)
-        if t == 1:
-            for li in range(pl.p, pl.L):
-                y = pl.h_full[li & 1]
-                ctx.prefill_layer(cfg, pl.structs[li], h, pos, y)
-                h = y
-            return h, [pl.S] * B
-        ctx.candidate_masks(self.x_hat, self.sal, u, pl.nt, self.rules,
-                            out=(self.mask2d, self.mask3d, self.sem, self.kept_len))
-        lengths = self.kept_len.cpu().tolist()          # the one host read-back of the step
-        S_pad = max(lengths)
-        kept = self.kept_idx[:B * S_pad].view(B, S_pad)
-        ctx.mask_indices(self.mask2d, self.mask3d, pl.nt, S_pad, out=kept)
-        hk = self.h_kept[0][:B * S_pad * D].view(B, S_pad, D)
-        pk = self.pos_kept[:B * S_pad].view(B, S_pad)
-        ctx.compact(h, pos, kept, out=(hk, pk))
-        h = hk
-        for li in range(pl.p, pl.L):
-            y = self.h_kept[(li - pl.p + 1) & 1][:B * S_pad * D].view(B, S_pad, D)
-            ctx.prefill_layer(cfg, pl.structs[li], h, pk, y)
-            h = y
-        self.kept, self.pos_out = kept, pk
-        return h, lengths
+        B, S, D = pl.B, pl.S, pl.cfg.D
+        _dev(x, torch.bfloat16)
+        _dev(pos, torch.int32)
+        _dev(u, torch.float32)
+        if key_bias is not None:
+            _dev(key_bias, torch.float32)
+        d = MaskedDesc(B, self.P, pl.nt, pl.L, pl.p, t, self.k, self.beta, self.rules)
+        y_ptr, rows = C.c_void_p(), C.c_int()
+        lengths = (C.c_int32 * B)()
+        _check(load().mvla_masked_prefill_step(pl.ctx.handle, C.byref(pl.cfg), pl._layer_array,
+                                               C.byref(d), x.data_ptr(), pos.data_ptr(),
+                                               _ptr(key_bias), u.data_ptr(),
+                                               C.byref(self._buffers), C.byref(y_ptr),
+                                               C.byref(rows), lengths), "mvla_masked_prefill_step")
+        S_pad = rows.value
+        for buf in pl.h_full + self.h_kept:            # which buffer holds the result
+            if buf.data_ptr() == y_ptr.value:
+                y = buf.view(-1)[:B * S_pad * D].view(B, S_pad, D)
+                break
+        else:
+            raise RuntimeError("mvla_masked_prefill_step returned a pointer outside the buffers")
+        if t > 1:
+            self.kept = self.kept_idx[:B * S_pad].view(B, S_pad)
+            self.pos_out = self.pos_kept[:B * S_pad].view(B, S_pad)
+        return y, list(lengths)

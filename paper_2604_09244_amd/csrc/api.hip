@@ -613,6 +613,97 @@ int mvla_prefill(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weig
     return MVLA_OK;
 }
 
+// One action-iteration step with the masks of Algorithm 1: sequencing only.
+int mvla_masked_prefill_step(mvla_ctx* ctx, const mvla_layer_cfg* cfg,
+                             const mvla_layer_weights* layers, const mvla_masked_desc* d,
+                             const void* x, const int32_t* pos, const float* key_bias,
+                             const float* u, const mvla_masked_buffers* buf, void** y_out,
+                             int* rows_out, int32_t* lengths_out) {
+    if (!ctx || !cfg || !layers || !d || !x || !pos || !buf || !y_out || !rows_out || !lengths_out)
+        return MVLA_EINVAL;
+    const int B = d->B, P = d->n_patch, nt = d->n_text, L = d->n_layers, p = d->p, t = d->t;
+    if (B <= 0 || P <= 0 || nt <= 0 || L <= 0 || p < 1 || p > L || t < 1) return MVLA_EINVAL;
+    if (P > 16384) return MVLA_EUNSUPPORTED;
+    if ((long)2 * P + nt > INT32_MAX / 4) return MVLA_EUNSUPPORTED;
+    if (d->smooth_k < 1 || !(d->smooth_beta > 0.0 && d->smooth_beta < 1.0)) return MVLA_EINVAL;
+    if (d->rules.kmeans_max_iter < 1 || !(d->rules.tau_2d <= d->rules.tau_3d) ||
+        !(d->rules.bg_drop >= 0.f && d->rules.bg_drop <= 1.f))
+        return MVLA_EINVAL;
+    const int S = 2 * P + nt;
+    if (!buf->h_full[0] || !buf->h_full[1] || !buf->probs || !buf->sal || !buf->x_t || !buf->x_hat)
+        return MVLA_EINVAL;
+    if (t > 1 && (!u || !buf->h_kept[0] || !buf->h_kept[1] || !buf->mask2d || !buf->mask3d ||
+                  !buf->kept_len || !buf->kept_idx || !buf->pos_kept))
+        return MVLA_EINVAL;
+    for (int l = 0; l < L; ++l) {
+        const int rc = check_layer_args(ctx, cfg, &layers[l], x, pos, B, S, 0, nullptr, true);
+        if (rc) return rc;
+    }
+    if ((size_t)B * S > (size_t)INT32_MAX / 4) return MVLA_EUNSUPPORTED;
+    if (layer_buffers(nullptr, B, S, cfg->D, cfg->F).bytes > ctx->scratch_bytes ||
+        salience_scratch_bytes(B, cfg->H, nt, 2 * P) > ctx->scratch_bytes)
+        return MVLA_ENOMEM;
+
+    int rc;
+    const void* h = x;
+    for (int l = 0; l < p; ++l) {
+        void* y = buf->h_full[l & 1];
+        const bool score = l == p - 1;
+        rc = mvla_prefill_layer(ctx, cfg, &layers[l], h, pos, B, S, y, score ? nt : 0,
+                                score ? key_bias : nullptr, score ? buf->probs : nullptr);
+        if (rc) return rc;
+        h = y;
+    }
+    // the four per-patch indicators of this step (Eq. 1 on the output of layer p-1, Eqs. 5-6 on
+    // its language-query attention) and their smoothing (Eqs. 8-9)
+    const size_t BP = (size_t)B * P;
+    rc = mvla_salience(ctx, buf->probs, B, cfg->H, nt, S, 2 * P, buf->sal);
+    if (rc) return rc;
+    rc = mvla_feature_share(ctx, h, B, S, cfg->D, P, buf->x_t, buf->x_t + BP);
+    if (rc) return rc;
+    rc = mvla_modality_decompose(ctx, buf->probs, B, cfg->H, nt, S, P, buf->x_t + 2 * BP,
+                                 buf->x_t + 3 * BP);
+    if (rc) return rc;
+    rc = mvla_temporal_smooth(ctx, buf->x_t, buf->x_hat, 4 * BP, t, d->smooth_k, d->smooth_beta);
+    if (rc) return rc;
+    if (t == 1) {   // cold start: every token goes through every layer
+        for (int l = p; l < L; ++l) {
+            void* y = buf->h_full[l & 1];
+            rc = mvla_prefill_layer(ctx, cfg, &layers[l], h, pos, B, S, y, 0, nullptr, nullptr);
+            if (rc) return rc;
+            h = y;
+        }
+        for (int b = 0; b < B; ++b) lengths_out[b] = S;
+        *y_out = const_cast<void*>(h);
+        *rows_out = S;
+        return MVLA_OK;
+    }
+    rc = mvla_candidate_masks(ctx, buf->x_hat, buf->sal, u, B, P, nt, &d->rules, buf->mask2d,
+                              buf->mask3d, buf->sem, buf->kept_len);
+    if (rc) return rc;
+    // the kept length differs per sample: the one read-back of the step sizes the later launches
+    MVLA_HIP_CHECK(hipMemcpyAsync(lengths_out, buf->kept_len, (size_t)B * sizeof(int32_t),
+                                  hipMemcpyDeviceToHost, ctx->stream));
+    MVLA_HIP_CHECK(hipStreamSynchronize(ctx->stream));
+    int S_pad = 0;
+    for (int b = 0; b < B; ++b) S_pad = lengths_out[b] > S_pad ? lengths_out[b] : S_pad;
+    if (S_pad <= 0 || S_pad > S) return MVLA_EHIP;   // (every sample keeps its language tokens)
+    rc = mvla_mask_indices(ctx, buf->mask2d, buf->mask3d, B, P, nt, S_pad, buf->kept_idx);
+    if (rc) return rc;
+    rc = mvla_compact(ctx, h, pos, buf->kept_idx, B, S, S_pad, cfg->D, buf->h_kept[0], buf->pos_kept);
+    if (rc) return rc;
+    h = buf->h_kept[0];
+    for (int l = p; l < L; ++l) {
+        void* y = buf->h_kept[(l - p + 1) & 1];
+        rc = mvla_prefill_layer(ctx, cfg, &layers[l], h, buf->pos_kept, B, S_pad, y, 0, nullptr, nullptr);
+        if (rc) return rc;
+        h = y;
+    }
+    *y_out = const_cast<void*>(h);
+    *rows_out = S_pad;
+    return MVLA_OK;
+}
+
 int mvla_tune_layers(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_weights* layers,
                      int n_layers, int B, int S) {
     if (!ctx || !cfg || !layers || n_layers <= 0 || B <= 0 || S <= 0) return MVLA_EINVAL;
