@@ -886,26 +886,24 @@ int mvla_score_only(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_w
     if (lb.bytes > ctx->scratch_bytes) return MVLA_ENOMEM;
     const int M = B * S;
     hipStream_t st = ctx->stream;
-    TIMED(ctx, KID_RMSNORM, M,
-          launch_rmsnorm(static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(w->g_attn), M, D,
-                         cfg->rms_eps, lb.u, st));
     // Keys of every row: the key rows of wqkv on the normalised input, rotated, into the k
-    // buffer [M, D].  Queries of the scoring rows only: those rows are normalised once more
-    // into a compact [B*n_query_tail, D] matrix (with their position ids beside it), projected
-    // with the query rows of wqkv and rotated; the scoring kernel reads that compact q.
+    // buffer [M, D].  Queries of the scoring rows only: the norm kernel writes those rows a
+    // second time into a compact [B*n_query_tail, D] matrix (with their position ids beside it),
+    // which is projected with the query rows of wqkv and rotated; the scoring kernel reads that
+    // compact q.
     const bf16_t* wqkv = static_cast<const bf16_t*>(w->wqkv);
     const int Mq = B * n_query_tail;
     bf16_t* k_buf = lb.qkv;                       // [M, D]
     bf16_t* q_buf = lb.qkv + (size_t)M * D;       // [Mq, D]
     bf16_t* u_tail = lb.attn;                     // [Mq, D]  (attention output buffer, unused here)
     int32_t* pos_tail = reinterpret_cast<int32_t*>(lb.x1);   // [Mq]
+    TIMED(ctx, KID_RMSNORM, M,
+          launch_rmsnorm_tail(static_cast<const bf16_t*>(x), pos, static_cast<const bf16_t*>(w->g_attn),
+                              B, S, n_query_tail, D, cfg->rms_eps, lb.u, u_tail, pos_tail, st));
     const RopeEpilogue rope_k = {pos, w->rope_cos, w->rope_sin, nullptr, w->rope_len, S, lb.S_pad, D, dh};
     TIMED(ctx, KID_GEMM_QKV, M,
           launch_gemm(lb.u, D, wqkv + (size_t)D * D, M, D, D, k_buf, D, nullptr, 0, EPI_QKV_ROPE,
                       GEMM_WS(ctx), GEMM_PICK(ctx, M, D, D, EPI_QKV_ROPE), &rope_k, st));
-    TIMED(ctx, KID_RMSNORM, Mq,
-          launch_rmsnorm_tail(static_cast<const bf16_t*>(x), pos, static_cast<const bf16_t*>(w->g_attn),
-                              B, S, n_query_tail, D, cfg->rms_eps, u_tail, pos_tail, st));
     const int nq_pad = (n_query_tail + 7) / 8 * 8;
     const RopeEpilogue rope_q = {pos_tail, w->rope_cos, w->rope_sin, nullptr, w->rope_len,
                                  n_query_tail, nq_pad, D, dh};

@@ -96,10 +96,11 @@ int launch_rmsnorm(const bf16_t* x, const bf16_t* gain, int M, int D, float eps,
                    hipStream_t st);
 int launch_rmsnorm_f32(const float* x, const bf16_t* gain, int M, int D, float eps, bf16_t* out,
                        hipStream_t st);
-// the last `tail` rows of each of B samples of S rows, normalised into out [B*tail, D]; their
-// position ids into pos_out [B*tail]
+// all B*S rows normalised into out; the last `tail` rows of each sample a second time, packed,
+// into out_tail [B*tail, D], their position ids into pos_out [B*tail]
 int launch_rmsnorm_tail(const bf16_t* x, const int32_t* pos, const bf16_t* gain, int B, int S,
-                        int tail, int D, float eps, bf16_t* out, int32_t* pos_out, hipStream_t st);
+                        int tail, int D, float eps, bf16_t* out, bf16_t* out_tail, int32_t* pos_out,
+                        hipStream_t st);
 int launch_rope_table(double base, int rope_len, int dh, float* c, float* s, hipStream_t st);
 // scoring probabilities of the last nq rows: probs [B,H,nq,S] fp32.  q_tail_only: q holds just
 // those rows, nq per sample ([B*nq, q_row_stride]); otherwise all S rows of every sample.

@@ -26,20 +26,26 @@ __device__ __forceinline__ float block_sum(float v, float* sh) {
 }
 
 // IN_F32: the row is fp32 (the mid-layer residual stream), else bf16.
-// tail > 0: output row r is input row (r / tail) * S + S - tail + r % tail (the last `tail`
-// rows of every sample of S rows), and its position id is copied to pos_out[r].
+// tail > 0: the last `tail` rows of every sample of S rows are written a second time, packed
+// into out_tail [B*tail, D], and their position ids are copied to pos_out [B*tail] (the scoring
+// pass projects queries for those rows only).
 template <bool IN_F32>
 __global__ __launch_bounds__(NORM_THREADS) void rmsnorm_kernel(const void* __restrict__ xv,
                                                                const uint4* __restrict__ gain,
                                                                int row_vec /* D/8 */, float inv_d,
                                                                float eps, uint4* __restrict__ out,
                                                                int S, int tail,
+                                                               uint4* __restrict__ out_tail,
                                                                const int32_t* __restrict__ pos,
                                                                int32_t* __restrict__ pos_out) {
     __shared__ float sh[NORM_THREADS / 64];
-    const int orow = blockIdx.x, tid = threadIdx.x;
-    const int row = tail > 0 ? (orow / tail) * S + (S - tail) + orow % tail : orow;
-    if (tail > 0 && tid == 0) pos_out[orow] = pos[row];
+    const int row = blockIdx.x, tid = threadIdx.x;
+    int trow = -1;                       // row of the packed tail matrix, if this is a tail row
+    if (tail > 0) {
+        const int b = row / S, s_ = row - b * S;
+        if (s_ >= S - tail) trow = b * tail + s_ - (S - tail);
+    }
+    if (trow >= 0 && tid == 0) pos_out[trow] = pos[row];
     float vals[NORM_MAX_CHUNKS][8];
     float ss = 0.f;
 #pragma unroll
@@ -66,7 +72,8 @@ __global__ __launch_bounds__(NORM_THREADS) void rmsnorm_kernel(const void* __res
     }
     ss = block_sum(ss, sh);
     const float scale = 1.0f / sqrtf(ss * inv_d + eps);
-    uint4* optr = out + (size_t)orow * row_vec;
+    uint4* optr = out + (size_t)row * row_vec;
+    uint4* tptr = out_tail + (size_t)(trow >= 0 ? trow : 0) * row_vec;
 #pragma unroll
     for (int k = 0; k < NORM_MAX_CHUNKS; ++k) {
         const int c = tid + k * NORM_THREADS;
@@ -79,6 +86,7 @@ __global__ __launch_bounds__(NORM_THREADS) void rmsnorm_kernel(const void* __res
                 r[i] = pack_bf16x2(vals[k][2 * i] * scale * __uint_as_float(gw[i] << 16),
                                    vals[k][2 * i + 1] * scale * __uint_as_float(gw[i] & 0xFFFF0000u));
             optr[c] = make_uint4(r[0], r[1], r[2], r[3]);
+            if (trow >= 0) tptr[c] = make_uint4(r[0], r[1], r[2], r[3]);
         }
     }
 }
@@ -90,23 +98,11 @@ static int launch_rmsnorm_any(const void* x, bool f32, const bf16_t* gain, int M
     if (f32)
         hipLaunchKernelGGL(rmsnorm_kernel<true>, dim3(M), dim3(NORM_THREADS), 0, st, x,
                            reinterpret_cast<const uint4*>(gain), D / 8, 1.0f / (float)D, eps,
-                           reinterpret_cast<uint4*>(out), 0, 0, nullptr, nullptr);
+                           reinterpret_cast<uint4*>(out), 0, 0, nullptr, nullptr, nullptr);
     else
         hipLaunchKernelGGL(rmsnorm_kernel<false>, dim3(M), dim3(NORM_THREADS), 0, st, x,
                            reinterpret_cast<const uint4*>(gain), D / 8, 1.0f / (float)D, eps,
-                           reinterpret_cast<uint4*>(out), 0, 0, nullptr, nullptr);
-    MVLA_HIP_CHECK(hipGetLastError());
-    return MVLA_OK;
-}
-
-int launch_rmsnorm_tail(const bf16_t* x, const int32_t* pos, const bf16_t* gain, int B, int S,
-                        int tail, int D, float eps, bf16_t* out, int32_t* pos_out, hipStream_t st) {
-    if (B <= 0 || tail <= 0) return MVLA_OK;
-    if (D % 8 != 0 || D / 8 > NORM_THREADS * NORM_MAX_CHUNKS) return MVLA_EUNSUPPORTED;
-    if (tail > S || !pos || !pos_out) return MVLA_EINVAL;
-    hipLaunchKernelGGL(rmsnorm_kernel<false>, dim3(B * tail), dim3(NORM_THREADS), 0, st, x,
-                       reinterpret_cast<const uint4*>(gain), D / 8, 1.0f / (float)D, eps,
-                       reinterpret_cast<uint4*>(out), S, tail, pos, pos_out);
+                           reinterpret_cast<uint4*>(out), 0, 0, nullptr, nullptr, nullptr);
     MVLA_HIP_CHECK(hipGetLastError());
     return MVLA_OK;
 }
@@ -118,6 +114,20 @@ int launch_rmsnorm(const bf16_t* x, const bf16_t* gain, int M, int D, float eps,
 int launch_rmsnorm_f32(const float* x, const bf16_t* gain, int M, int D, float eps, bf16_t* out,
                        hipStream_t st) {
     return launch_rmsnorm_any(x, true, gain, M, D, eps, out, st);
+}
+
+int launch_rmsnorm_tail(const bf16_t* x, const int32_t* pos, const bf16_t* gain, int B, int S,
+                        int tail, int D, float eps, bf16_t* out, bf16_t* out_tail, int32_t* pos_out,
+                        hipStream_t st) {
+    if (B <= 0 || S <= 0) return MVLA_OK;
+    if (D % 8 != 0 || D / 8 > NORM_THREADS * NORM_MAX_CHUNKS) return MVLA_EUNSUPPORTED;
+    if (tail <= 0 || tail > S || !pos || !pos_out || !out_tail) return MVLA_EINVAL;
+    hipLaunchKernelGGL(rmsnorm_kernel<false>, dim3(B * S), dim3(NORM_THREADS), 0, st, x,
+                       reinterpret_cast<const uint4*>(gain), D / 8, 1.0f / (float)D, eps,
+                       reinterpret_cast<uint4*>(out), S, tail, reinterpret_cast<uint4*>(out_tail), pos,
+                       pos_out);
+    MVLA_HIP_CHECK(hipGetLastError());
+    return MVLA_OK;
 }
 
 // ---------------------------------------------------------------------------
