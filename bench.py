@@ -366,7 +366,7 @@ def main():
                       max_kept_tokens=max(max(l) for l in lens),
                       mask_step_us={n: 1e3 * sum(macc[n]) / (n_steps - 1) for n in mk if n in macc})
 
-    # ---- CPU oracle on a bounded sample: sample 0, whole path, all layers up to 4 --------------
+    # ---- CPU oracle on a bounded sample: sample 0, whole path, the first 12 layers at most -----
     cpu = None
     if not args.no_cpu_baseline:
         import numpy as np
@@ -376,7 +376,7 @@ def main():
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count()])
         except Exception:
             cores = os.cpu_count()
-        Lc = min(wl.L, 4)
+        Lc = min(wl.L, 12)   # 10 - 20 s of CPU work on the 32-layer workloads
         pc = min(wl.p, Lc)
         f64 = lambda t: t.detach().to("cpu", torch.float64).numpy()
         ow = [{k: f64(v) for k, v in W.layer_weights(wl, l, device=dev).items()} for l in range(Lc)]
