@@ -25,9 +25,13 @@ struct FusedPrune {
     uint32_t* sample_counters;  // one arrival counter per sample (kept at zero between calls)
 };
 template <bool COHERENT>
-__device__ void finish_sample(const float* sal_b, const FusedPrune& f, int b, uint32_t* keys);
+__device__ __forceinline__ void finish_sample(const float* sal_b, const FusedPrune& f, int b,
+                                              uint32_t* keys);
 
 constexpr int SAL_THREADS = 256;
+constexpr int SEL_THREADS = 256;    // selection (also the tail of the fused kernel)
+constexpr int SEL_MAX_N = 16384;    // largest segment the selection stages in LDS
+constexpr int SEL_SMALL_N = 64;     // up to here a direct rank count beats the threshold search (measured)
 constexpr int SAL_LPR = 16;                        // lanes per row-group
 constexpr int SAL_GROUPS = SAL_THREADS / SAL_LPR;  // 16 row-groups per block
 
@@ -208,11 +212,27 @@ static int launch_salience_any(const float* attn, int B, int H, int Nq, int S, i
     if (fused) {
         f = *fused;
         f.sample_counters = counters + (size_t)B * chunks;
-        lds = (size_t)max(max(f.n2, f.n3), 1) * 4;
+        lds = (size_t)max(f.n2 + f.n3, 1) * 4;   // selection keys of both segments
     }
+    // (the fused variants keep the keys of both segments in LDS: up to 128 KiB, above the default
+    // limit of a kernel, which is raised once per device)
 #define MVLA_SAL(V, F)                                                                          \
-    hipLaunchKernelGGL((salience_kernel<V, F>), grid, dim3(SAL_THREADS), lds, st, attn, R, S, n_vis, \
-                       rps, n_split, inv_rows, sal, partial, counters, f)
+    do {                                                                                        \
+        auto kern = salience_kernel<V, F>;                                                      \
+        if (F) {                                                                                \
+            static bool lds_set[kMaxDevices] = {};                                              \
+            int dev = 0;                                                                        \
+            MVLA_HIP_CHECK(hipGetDevice(&dev));                                                 \
+            if (dev < 0 || dev >= kMaxDevices || !lds_set[dev]) {                               \
+                MVLA_HIP_CHECK(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),         \
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize,  \
+                                                   2 * SEL_MAX_N * 4));                         \
+                if (dev >= 0 && dev < kMaxDevices) lds_set[dev] = true;                         \
+            }                                                                                   \
+        }                                                                                       \
+        hipLaunchKernelGGL(kern, grid, dim3(SAL_THREADS), lds, st, attn, R, S, n_vis, rps,      \
+                           n_split, inv_rows, sal, partial, counters, f);                       \
+    } while (0)
     if (vec4) {
         if (fused) MVLA_SAL(4, true); else MVLA_SAL(4, false);
     } else {
@@ -298,12 +318,20 @@ namespace mvla {
 // ---------------------------------------------------------------------------
 constexpr int BUD_THREADS = 256;
 
+// Workgroup barrier for data that is exchanged through LDS only: it waits for this wave's LDS
+// operations, not for its outstanding global stores.  (__syncthreads() waits for those too --
+// a full write round trip whenever budget or index stores are in flight, several times per
+// sample in the tail of the fused kernel.)
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 __device__ inline double block_sum_f64(double v, double* sh) {
     // fixed-shape tree: wave shuffle then 4 partials in LDS
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    __syncthreads();
+    lds_barrier();
     if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
-    __syncthreads();
+    lds_barrier();
     double t = 0.0;
     for (int w = 0; w < BUD_THREADS / 64; ++w) t += sh[w];
     return t;
@@ -362,8 +390,6 @@ int launch_budget(const float* sal, int B, int n2, int n3, int k_total, int min2
 // contiguous index range, so a block prefix sum of its keep counts gives
 // output slots that are already in ascending index order -- no sort.
 // ---------------------------------------------------------------------------
-constexpr int SEL_THREADS = 256;
-constexpr int SEL_MAX_N = 16384;
 
 __device__ inline uint32_t sal_key(float x) {
     uint32_t u = __float_as_uint(x);
@@ -378,36 +404,86 @@ __device__ inline uint32_t block_scan_incl(uint32_t v, uint32_t* wsum) {
         const uint32_t t = __shfl_up(v, o);
         if (lane >= o) v += t;
     }
-    __syncthreads();
+    lds_barrier();
     if (lane == 63) wsum[wave] = v;
-    __syncthreads();
+    lds_barrier();
     uint32_t add = 0;
     for (int w = 0; w < wave; ++w) add += wsum[w];
     return v + add;
 }
 
-template <bool COHERENT>
-__device__ void select_segment(const float* __restrict__ seg, int n, int k, int idx_offset,
-                               int32_t* __restrict__ out, uint32_t* keys /*LDS [n]*/,
-                               uint32_t* hist /*LDS [256]*/, uint32_t* wsum /*LDS [4]*/,
-                               uint32_t* bcast /*LDS [4]*/) {
+// Short segments (at most one token per thread; used up to SEL_SMALL_N): thread i ranks key i
+// directly -- the keys above it plus the equal keys at a lower index -- and keeps it when that
+// rank is below k.  No threshold search: n comparisons per thread instead of four histogram
+// passes with their scans.  Every lane reads the same key in a step (an LDS broadcast).
+// Threads are in index order, so the keep flags' prefix count is the output slot.
+__device__ __forceinline__ void select_small(const uint32_t* keys /*LDS [n]*/, int n, int k, int idx_offset,
+                             int32_t* __restrict__ out, uint32_t* wsum /*LDS [4]*/) {
+    const int i = threadIdx.x, lane = i & 63, wave = i >> 6;
+    lds_barrier();   // the keys are in LDS
+    const uint32_t my = i < n ? keys[i] : 0u;
+    // keys before i count when >= my, keys after i when > my, i.e. >= my + 1 (a key of all ones
+    // is a NaN, invalid input: its threshold wraps and the token is dropped)
+    const uint32_t my1 = my + 1u;
+    const int w0 = min(wave * 64, n), w1 = min(w0 + 64, n);   // the indices this wave's lanes hold
+    int rank = 0;
+    // 32 keys per batch, so that the LDS reads of a batch are in flight together (read one by
+    // one, their latency is all the loop does); batches below or above the wave's own indices
+    // compare against one threshold
+    constexpr int BATCH = 32;
+    for (int j = 0; j < n; j += BATCH) {
+        uint32_t v[BATCH];
+        const bool full = j + BATCH <= n;
+        if (full) {
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) v[u] = keys[j + u];
+        } else {
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) v[u] = j + u < n ? keys[j + u] : 0u;
+        }
+        if (j + BATCH <= w0) {
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) rank += v[u] >= my;
+        } else if (j >= w1 && full) {
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) rank += v[u] >= my1;
+        } else {
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u)
+                rank += (j + u < n) && v[u] >= (j + u < i ? my : my1);
+        }
+    }
+    const bool keep = i < n && rank < k;
+    const unsigned long long bal = __ballot(keep);
+    if (lane == 0) wsum[wave] = (uint32_t)__popcll(bal);
+    lds_barrier();
+    uint32_t slot = (uint32_t)__popcll(bal & ((1ull << lane) - 1ull));
+    for (int w = 0; w < wave; ++w) slot += wsum[w];
+    if (keep) out[slot] = idx_offset + i;
+}
+
+// Selection among n keys that already sit in LDS (written by this workgroup; the first barrier
+// below orders those writes before the reads).
+__device__ __forceinline__ void select_from_keys(const uint32_t* keys /*LDS [n]*/, int n, int k, int idx_offset,
+                                 int32_t* __restrict__ out, uint32_t* hist /*LDS [256]*/,
+                                 uint32_t* wsum /*LDS [4]*/, uint32_t* bcast /*LDS [4]*/) {
     const int tid = threadIdx.x;
-    for (int i = tid; i < n; i += SEL_THREADS)
-        keys[i] = sal_key(COHERENT ? __hip_atomic_load(&seg[i], __ATOMIC_RELAXED,
-                                                       __HIP_MEMORY_SCOPE_AGENT)
-                                   : seg[i]);
     if (k <= 0) return;
     if (k > n) k = n;
+    if (n <= SEL_SMALL_N) {
+        select_small(keys, n, k, idx_offset, out, wsum);
+        return;
+    }
     uint32_t prefix = 0, prefix_mask = 0;
     uint32_t remaining = (uint32_t)k;  // rank (1-based, from the top) of T among matching keys
     for (int shift = 24; shift >= 0; shift -= 8) {
         hist[tid] = 0;
-        __syncthreads();
+        lds_barrier();
         for (int i = tid; i < n; i += SEL_THREADS) {
             const uint32_t key = keys[i];
             if ((key & prefix_mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
         }
-        __syncthreads();
+        lds_barrier();
         // suffix counts from the top digit down: thread t looks at digit 255-t
         const uint32_t mine = hist[255 - tid];
         const uint32_t incl = block_scan_incl(mine, wsum);
@@ -416,11 +492,11 @@ __device__ void select_segment(const float* __restrict__ seg, int n, int k, int 
             bcast[0] = (uint32_t)(255 - tid);
             bcast[1] = remaining - excl;
         }
-        __syncthreads();
+        lds_barrier();
         prefix |= bcast[0] << shift;
         prefix_mask |= 255u << shift;
         remaining = bcast[1];
-        __syncthreads();
+        lds_barrier();
     }
     const uint32_t T = prefix;
     const uint32_t need_eq = remaining;  // how many keys equal to T are kept
@@ -447,6 +523,13 @@ __device__ void select_segment(const float* __restrict__ seg, int n, int k, int 
     }
 }
 
+__device__ __forceinline__ void select_segment(const float* __restrict__ seg, int n, int k, int idx_offset,
+                               int32_t* __restrict__ out, uint32_t* keys /*LDS [n]*/,
+                               uint32_t* hist, uint32_t* wsum, uint32_t* bcast) {
+    for (int i = threadIdx.x; i < n; i += SEL_THREADS) keys[i] = sal_key(seg[i]);
+    select_from_keys(keys, n, k, idx_offset, out, hist, wsum, bcast);
+}
+
 __global__ __launch_bounds__(SEL_THREADS) void select_kernel(const float* __restrict__ sal,
                                                              const int32_t* __restrict__ k2k3,
                                                              int n2, int n3, int n_text,
@@ -463,9 +546,9 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(const float* __rest
     k2 = min(max(k2, max(0, k_total - n3)), min(n2, k_total));
     const int k3 = k_total - k2;
     if (which == 0) {
-        select_segment<false>(sal + (size_t)b * (n2 + n3), n2, k2, 0, row, keys, hist, wsum, bcast);
+        select_segment(sal + (size_t)b * (n2 + n3), n2, k2, 0, row, keys, hist, wsum, bcast);
     } else if (which == 1) {
-        select_segment<false>(sal + (size_t)b * (n2 + n3) + n2, n3, k3, n2, row + k2, keys, hist,
+        select_segment(sal + (size_t)b * (n2 + n3) + n2, n3, k3, n2, row + k2, keys, hist,
                               wsum, bcast);
     } else {
         for (int i = threadIdx.x; i < n_text; i += SEL_THREADS) row[k_total + i] = n2 + n3 + i;
@@ -475,7 +558,8 @@ __global__ __launch_bounds__(SEL_THREADS) void select_kernel(const float* __rest
 // Budget and selection of one sample by one workgroup (tail of the fused kernel).  Same
 // summation order as budget_kernel, same selection as select_kernel.
 template <bool COHERENT>
-__device__ void finish_sample(const float* sal_b, const FusedPrune& f, int b, uint32_t* keys) {
+__device__ __forceinline__ void finish_sample(const float* sal_b, const FusedPrune& f, int b,
+                                              uint32_t* keys) {
     __shared__ double sh_d[BUD_THREADS / 64];
     __shared__ uint32_t hist[256];
     __shared__ uint32_t wsum[SEL_THREADS / 64];
@@ -485,9 +569,19 @@ __device__ void finish_sample(const float* sal_b, const FusedPrune& f, int b, ui
         return COHERENT ? __hip_atomic_load(&sal_b[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
                         : sal_b[i];
     };
+    // one pass over the sample's scores feeds both the masses and the selection keys of both
+    // segments (keys [0, n2) and [n2, n2 + n3) of the LDS array)
     double a2 = 0.0, a3 = 0.0;
-    for (int i = threadIdx.x; i < f.n2; i += BUD_THREADS) a2 += (double)ld(i);
-    for (int i = threadIdx.x; i < f.n3; i += BUD_THREADS) a3 += (double)ld(f.n2 + i);
+    for (int i = threadIdx.x; i < f.n2; i += BUD_THREADS) {
+        const float v = ld(i);
+        a2 += (double)v;
+        keys[i] = sal_key(v);
+    }
+    for (int i = threadIdx.x; i < f.n3; i += BUD_THREADS) {
+        const float v = ld(f.n2 + i);
+        a3 += (double)v;
+        keys[f.n2 + i] = sal_key(v);
+    }
     a2 = block_sum_f64(a2, sh_d);
     a3 = block_sum_f64(a3, sh_d);
     if (threadIdx.x == 0) {
@@ -498,13 +592,12 @@ __device__ void finish_sample(const float* sal_b, const FusedPrune& f, int b, ui
         f.k2k3[2 * b + 1] = f.k_total - k2;
         sh_k2 = k2;
     }
-    __syncthreads();
+    lds_barrier();
     const int k2 = sh_k2;
     int32_t* row = f.kept_idx + (size_t)b * (f.k_total + f.n_text);
-    select_segment<COHERENT>(sal_b, f.n2, k2, 0, row, keys, hist, wsum, bcast);
-    __syncthreads();
-    select_segment<COHERENT>(sal_b + f.n2, f.n3, f.k_total - k2, f.n2, row + k2, keys, hist, wsum,
-                             bcast);
+    select_from_keys(keys, f.n2, k2, 0, row, hist, wsum, bcast);
+    lds_barrier();
+    select_from_keys(keys + f.n2, f.n3, f.k_total - k2, f.n2, row + k2, hist, wsum, bcast);
     for (int i = threadIdx.x; i < f.n_text; i += SEL_THREADS)
         row[f.k_total + i] = f.n2 + f.n3 + i;
 }

@@ -186,6 +186,31 @@ def test_prune_step_equals_separate_calls_and_oracle(ctx, name):
     assert np.array_equal(kept.cpu().numpy(), O.select_topk(s_np, rk, wl.n2, wl.n3, wl.nt))
 
 
+def test_prune_step_with_the_largest_segments(ctx):
+    """Both segments at the 16384-token limit: the fused kernel keeps the keys of both in LDS
+    (128 KiB).  Equal to the separate calls and to the oracle's selection."""
+    n2 = n3 = 16384
+    nt, H, D, k_total = 8, 2, 64, 9000
+    S = n2 + n3 + nt
+    g = torch.Generator(device="cuda").manual_seed(77)
+    p = torch.rand(1, H, nt, S, device="cuda", generator=g) ** 4
+    p = (p / p.sum(-1, keepdim=True)).contiguous()
+    x = torch.randn(1, S, D, device="cuda", generator=g).to(torch.bfloat16)
+    pos = torch.arange(S, dtype=torch.int32, device="cuda")[None].contiguous()
+    out = ctx.prune_step(p, x, pos, n2, n3, nt, k_total)
+    sal = ctx.salience(p, n2 + n3)
+    k2k3 = ctx.modality_budget(sal, n2, n3, k_total)
+    kept = ctx.select_topk(sal, k2k3, n2, n3, nt, k_total)
+    torch.cuda.synchronize()
+    assert torch.equal(out["sal"], sal) and torch.equal(out["k2k3"], k2k3)
+    assert torch.equal(out["kept_idx"], kept)
+    s_np = sal.cpu().numpy()
+    rk, _ = O.modality_budget(s_np, n2, n3, k_total)
+    assert np.array_equal(k2k3.cpu().numpy(), rk)
+    assert np.array_equal(kept.cpu().numpy(), O.select_topk(s_np, rk, n2, n3, nt))
+    assert torch.equal(out["h"][0], x[0][kept[0].long()])
+
+
 def test_argument_errors_launch_nothing(ctx):
     sal = torch.ones(2, 20, device="cuda")
     k = torch.zeros(2, 2, dtype=torch.int32, device="cuda")
