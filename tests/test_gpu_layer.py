@@ -352,10 +352,11 @@ def test_layer_ratio_sweep_full_launch_shape(big_ctx):
     assert np.max(np.abs(to64(sal) - ref) / ref) <= 1e-5
 
 
-@pytest.mark.parametrize("keep", [150, 700])
+@pytest.mark.parametrize("keep", [150, 500, 700])
 def test_layer_ratio_sweep_kept_lengths(big_ctx, keep):
-    """Kept-token layer at B = 16 for two of the sweep's keep ratios (S' = 448, 1856) with
-    gathered position ids; the oracle checks sample 3."""
+    """Kept-token layer at B = 16 for three of the sweep's keep ratios (S' = 448, 1344 -- the
+    one the benchmark's headline runs at -- and 1856) with gathered position ids; the oracle
+    checks sample 3."""
     wl = W.with_keep(W.WORKLOADS["ratio_sweep"], keep)
     w_cpu = W.layer_weights(wl, 5)
     x, _ = W.hidden_states(wl, device="cuda")
@@ -368,6 +369,16 @@ def test_layer_ratio_sweep_kept_lengths(big_ctx, keep):
     torch.cuda.synchronize()
     check_layer(y[3], to64(xs[3]), pos_np[3], oracle_weights(w_cpu), wl,
                 f"ratio_sweep keep={keep} b=3 S'={wl.S_kept}")
+
+
+def test_pipeline_ratio_sweep_staged_sample0(big_ctx):
+    """The benchmark's headline shape (B = 16, S = 2624 -> S' = 1344 at keep 50 %), four of the
+    32 layers (pruning after layer 2, two kept-token layers) through the one-call entry point;
+    the oracle follows sample 0."""
+    from dataclasses import replace
+    wl = replace(W.with_keep(W.WORKLOADS["ratio_sweep"], 500), L=4)
+    ov = _staged_pipeline_parity(big_ctx, wl, 16, n_oracle=1, on_the_fly=True)
+    assert ov > 0.9
 
 
 def test_action_iteration_sequence(ctx):
