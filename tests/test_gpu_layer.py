@@ -371,6 +371,13 @@ def test_layer_ratio_sweep_kept_lengths(big_ctx, keep):
                 f"ratio_sweep keep={keep} b=3 S'={wl.S_kept}")
 
 
+def test_layer_ratio_sweep_headline_shape_with_measured_choices(big_ctx):
+    """Kept-token layer of the benchmark's headline (B = 16, S' = 1344, gathered position ids)
+    with the projection kernels the set-up measurement picks, as the benchmark runs it."""
+    wl = W.with_keep(W.WORKLOADS["ratio_sweep"], 500)
+    _launch_shape_case(big_ctx, wl, wl.S_kept, 3, (5,), True, gathered=True, bias=False)
+
+
 def test_pipeline_ratio_sweep_staged_sample0(big_ctx):
     """The benchmark's headline shape (B = 16, S = 2624 -> S' = 1344 at keep 50 %), four of the
     32 layers (pruning after layer 2, two kept-token layers) through the one-call entry point;
