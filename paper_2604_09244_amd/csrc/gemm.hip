@@ -278,15 +278,123 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
 
         // every thread of the workgroup has left the previous segment's LDS reads behind
         __syncthreads();
+        // ... and nothing the compiler keeps count of (a previous segment's epilogue loads and
+        // stores) is outstanding any more: a wait it placed for those inside the main loop would
+        // also wait for the loop's direct loads, which it does not see
+        __builtin_amdgcn_s_waitcnt(0);
         // ---- prologue: NS-1 slabs in flight, then one more behind the first barrier ---------
 #pragma unroll
         for (int s = 0; s < NS - 1; ++s) MVLA_ISSUE(k0 + s, s)
         uint4 af0[FM], bf0[FN], af1[FM], bf1[FN];
         wait_vm<(NS - 2) * P>();
         __syncthreads();
-        MVLA_ISSUE(k0 + NS - 1, NS - 1)
+        if constexpr (NS >= 3 && KS == 4 && P >= 4) {   // (the loop's first three k-steps issue the rest)
+            const int koff = min(k0 + NS - 1, k1 - 1) * BK;
+            const uint32_t soff = (uint32_t)(NS - 1) * STAGE * 16u;
+#pragma unroll
+            for (int r = 0; r < P / 4; ++r) {
+                if (r < A_LD) dma16(a_src[r < A_LD ? r : 0] + koff, a_lds[r < A_LD ? r : 0] + soff);
+                else dma16(b_src[r < P ? r - A_LD : 0] + koff, b_lds[r < P ? r - A_LD : 0] + soff);
+            }
+        } else {
+            MVLA_ISSUE(k0 + NS - 1, NS - 1)
+        }
         MVLA_READ_FRAGS(af0, bf0, 0, 0)
         int stage = 0;
+        // Four-wave shapes (registers to spare).  The load unit of a CU takes one 64-lane direct
+        // load per 16 clocks, so the 64 loads of a 256x256x64 slab need 1024 clocks of it -- two
+        // k-steps.  Issued all in the last k-step (as the other shapes do), they kept the waves
+        // standing at load issue instead of feeding the matrix core: 1100 - 1800 clocks for that
+        // k-step instead of 512 (cycle counters in a working copy).  Here a slab's fragments are
+        // read two k-steps ahead -- those of k-steps 2 and 3 during k-step 0, those of the next
+        // slab's k-steps 0 and 1 during k-step 3, one LDS read after each MFMA -- so the stage is
+        // free after k-step 0 and the loads of slab kt+2 go out a third each over k-steps 1, 2
+        // and 3, with the wait for slab kt+1 before the last.
+        constexpr bool DEEP = WM * WN == 4 && NS == 2 && KS == 4 && P >= 3;
+        // Shapes with three stages always have a free one: the loads of a slab go out a quarter
+        // per k-step (the last k-step of one iteration and the first three of the next) instead
+        // of all in one, for the same reason.
+        constexpr bool SPREAD4 = NS >= 3 && KS == 4 && P >= 4;
+        constexpr int NR = 2 * (FM + FN);   // fragment reads of two k-steps
+// read number R of the fragments of k-steps SA (first FM + FN reads, into AFA/BFA) and
+// SB (the rest, into AFB/BFB) of stage STG
+#define MVLA_READ_ONE(AFA, BFA, AFB, BFB, STG, SA, SB, R)                                      \
+    {                                                                                          \
+        const uint4* As_ = lds + (STG) * STAGE;                                                \
+        const uint4* Bs_ = As_ + BM * CPR;                                                     \
+        const int set_ = (R) / (FM + FN), idx_ = (R) % (FM + FN);                              \
+        const int ks_ = set_ == 0 ? (SA) : (SB);                                               \
+        if (idx_ < FM) {                                                                       \
+            const int ii_ = idx_ < FM ? idx_ : 0;                                              \
+            const uint4 v_ = As_[a_row[ii_] * CPR + ((ks_ * 2 + fg) ^ swz<CPR>(a_row[ii_]))];  \
+            if (set_ == 0) AFA[ii_] = v_; else AFB[ii_] = v_;                                  \
+        } else {                                                                               \
+            const int jj_ = idx_ >= FM ? idx_ - FM : 0;                                        \
+            const uint4 v_ = Bs_[b_row[jj_] * CPR + ((ks_ * 2 + fg) ^ swz<CPR>(b_row[jj_]))];  \
+            if (set_ == 0) BFA[jj_] = v_; else BFB[jj_] = v_;                                  \
+        }                                                                                      \
+    }
+// the MFMAs of one k-step; after MFMA n comes fragment read n (of NRD) of (RSTG; SA, SB), and
+// the direct loads [L0, L1) of slab KT into stage STG are dealt out evenly
+#define MVLA_STEP(AF, BF, NRD, AFA, BFA, AFB, BFB, RSTG, SA, SB, KT, STG, L0, L1)            \
+    {                                                                                          \
+        const int koff = min((KT), k1 - 1) * BK;                                               \
+        const uint32_t soff = (uint32_t)(STG) * STAGE * 16u;                                   \
+        constexpr int NL_ = (L1) - (L0);                                                       \
+        constexpr int EVERY_ = NL_ > 0 && (FM * FN) / (NL_ > 0 ? NL_ : 1) > 0 ? (FM * FN) / (NL_ > 0 ? NL_ : 1) : 1; \
+        int n_ = 0, l_ = (L0);                                                                 \
+        _Pragma("unroll") for (int i = 0; i < FM; ++i) _Pragma("unroll") for (int j = 0; j < FN; ++j) { \
+            acc[i][j] = mfma32(BF[j], AF[i], acc[i][j]);                                       \
+            if (n_ < (NRD)) MVLA_READ_ONE(AFA, BFA, AFB, BFB, RSTG, SA, SB, n_)                \
+            if (n_ % EVERY_ == EVERY_ - 1 && l_ < (L1)) {                                      \
+                if (l_ < A_LD) dma16(a_src[l_ < A_LD ? l_ : 0] + koff, a_lds[l_ < A_LD ? l_ : 0] + soff); \
+                else dma16(b_src[l_ < P ? l_ - A_LD : 0] + koff, b_lds[l_ < P ? l_ - A_LD : 0] + soff);   \
+                ++l_;                                                                          \
+            }                                                                                  \
+            __builtin_amdgcn_sched_barrier(0);                                                 \
+            ++n_;                                                                              \
+        }                                                                                      \
+        _Pragma("unroll") for (int r = FM * FN; r < (NRD); ++r)                                \
+            MVLA_READ_ONE(AFA, BFA, AFB, BFB, RSTG, SA, SB, r)                                 \
+        _Pragma("unroll") for (int r = 0; r < P; ++r)                                          \
+            if (r >= l_ && r < (L1)) {                                                         \
+                if (r < A_LD) dma16(a_src[r < A_LD ? r : 0] + koff, a_lds[r < A_LD ? r : 0] + soff); \
+                else dma16(b_src[r - A_LD] + koff, b_lds[r - A_LD] + soff);                    \
+            }                                                                                  \
+    }
+        if constexpr (DEEP) {
+            uint4 af2[FM], bf2[FN], af3[FM], bf3[FN];
+            constexpr int L1_ = P / 3, L2_ = 2 * P / 3;
+            MVLA_READ_FRAGS(af1, bf1, 0, 1)
+            for (int kt = k0; kt < k1; ++kt) {
+                const int nstage = stage ^ 1;
+                // k-step 0, reading the fragments of k-steps 2 and 3: after it this slab is in registers
+                MVLA_STEP(af0, bf0, NR, af2, bf2, af3, bf3, stage, 2, 3, kt + 2, stage, 0, 0)
+                __syncthreads();   // ... for every wave: the stage is free for slab kt+2
+                MVLA_STEP(af1, bf1, 0, af2, bf2, af3, bf3, stage, 2, 3, kt + 2, stage, 0, L1_)
+                MVLA_STEP(af2, bf2, 0, af2, bf2, af3, bf3, stage, 2, 3, kt + 2, stage, L1_, L2_)
+                // slab kt+1 has landed for every wave (the two thirds of slab kt+2 may be in flight)
+                wait_vm<L2_>();
+                __syncthreads();
+                // k-step 3, reading the fragments of k-steps 0 and 1 of the next slab
+                MVLA_STEP(af3, bf3, NR, af0, bf0, af1, bf1, nstage, 0, 1, kt + 2, stage, L2_, P)
+                stage = nstage;
+            }
+        } else if constexpr (SPREAD4) {
+            constexpr int Q1 = P / 4, Q2 = P / 2, Q3 = 3 * P / 4;
+            for (int kt = k0; kt < k1; ++kt) {
+                const int nstage = stage + 1 == NS ? 0 : stage + 1;
+                const int pstage = stage == 0 ? NS - 1 : stage - 1;   // freed one iteration ago
+                MVLA_STEP(af0, bf0, FM + FN, af1, bf1, af1, bf1, stage, 1, 1, kt + NS - 1, pstage, Q1, Q2)
+                MVLA_STEP(af1, bf1, FM + FN, af0, bf0, af0, bf0, stage, 2, 2, kt + NS - 1, pstage, Q2, Q3)
+                MVLA_STEP(af0, bf0, FM + FN, af1, bf1, af1, bf1, stage, 3, 3, kt + NS - 1, pstage, Q3, P)
+                // slab kt+1 has landed for every wave; slab kt's stage is free for slab kt+NS
+                wait_vm<(NS - 2) * P>();
+                __syncthreads();
+                MVLA_STEP(af1, bf1, FM + FN, af0, bf0, af0, bf0, nstage, 0, 0, kt + NS, stage, 0, Q1)
+                stage = nstage;
+            }
+        } else
         for (int kt = k0; kt < k1; ++kt) {
             const int nstage = stage + 1 == NS ? 0 : stage + 1;
 #pragma unroll
@@ -315,6 +423,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
 #undef MVLA_MFMA
 #undef MVLA_MFMA_ISSUE
 #undef MVLA_SPREAD_READS
+#undef MVLA_READ_ONE
+#undef MVLA_STEP
 
         // ---- K-split tiles: park the partial sums; the last piece to arrive finishes --------
         // (the four-wave 128x128-per-wave shape keeps its register budget for the main loop:

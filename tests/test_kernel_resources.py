@@ -96,6 +96,52 @@ def _waits_among_mfmas(lines, kernel_prefix):
     return found
 
 
+def _waits_in_innermost_mfma_loops(lines, kernel_prefix):
+    """Per kernel: the compiler's own vmcnt waits inside the innermost loops that hold MFMA
+    instructions (label ... backward branch, no loop inside), wherever in the loop they stand."""
+    starts = [i for i, l in enumerate(lines) if re.match(r"^%s.*:" % kernel_prefix, l)]
+    found, n_loops = {}, 0
+    for a0, b0 in zip(starts, starts[1:] + [len(lines)]):
+        k = lines[a0:b0]
+        k = k[:next((i for i, l in enumerate(k) if "s_endpgm" in l), len(k))]
+        labels = {m.group(1): i for i, l in enumerate(k)
+                  for m in [re.match(r"^(\.LBB\d+_\d+):", l)] if m}
+        loops = []
+        for i, l in enumerate(k):
+            m = re.search(r"s_c?branch\w* (\.LBB\d+_\d+)", l)
+            if m and m.group(1) in labels and labels[m.group(1)] < i:
+                loops.append((labels[m.group(1)], i))
+        for a, b in loops:
+            if any(a2 >= a and b2 <= b and (a2, b2) != (a, b) for a2, b2 in loops):
+                continue
+            body = k[a:b]
+            if sum("v_mfma" in x for x in body) < 8:
+                continue
+            n_loops += 1
+            in_asm, waits = False, []
+            for x in body:
+                if "ASMSTART" in x:
+                    in_asm = True
+                elif "ASMEND" in x:
+                    in_asm = False
+                elif not in_asm and "s_waitcnt" in x and "vmcnt" in x:
+                    waits.append(x.strip())
+            if waits:
+                found[lines[a0].split(":")[0]] = waits
+    return found, n_loops
+
+
+def test_no_compiler_vmcnt_wait_inside_the_projection_main_loops(tmp_path):
+    """A wait at the head of the main loop (for loads or stores of a previous tile's epilogue
+    that the compiler still counts) stands before the loop's first MFMA in program order, yet
+    runs every iteration and waits for the direct loads just issued.  The kernel clears the
+    compiler's count once per tile; no main loop of any configuration may hold such a wait."""
+    found, n_loops = _waits_in_innermost_mfma_loops(_device_assembly("gemm.hip", tmp_path),
+                                                    "_ZN4mvla11gemm_kernelI")
+    assert n_loops == 28
+    assert not found, found
+
+
 @pytest.mark.parametrize("src,prefix,n_kernels", [("gemm.hip", "_ZN4mvla11gemm_kernelI", 28),
                                                   ("attention.hip", "_ZN4mvla16attention_kernelI", 2)])
 def test_no_compiler_wait_catches_the_direct_loads(src, prefix, n_kernels, tmp_path):
