@@ -718,57 +718,88 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
                 }
                 continue;
             }
+            // Items are taken U at a time: the residual reads of a batch are in flight together
+            // (one by one, every item waited a full memory round trip for its own: 32 of them in
+            // a row per thread and tile in the projections that add a residual).
+            // (eight at a time where the accumulators sit in the second register file; four, or two
+            // on the eight-wave 256x256 shape, where they share the file with the batch)
+            constexpr bool ROOMY = WM * WN == 4 && !(NS == 2 && BM == 128 && BN == 128);   // one workgroup per CU
+            constexpr int U = EPI == EPI_SILU_MUL ? 2 : ROOMY ? 8
+                              : (FM * FN >= 8 || EPI == EPI_RES_F32_TO_BF16 || WM * WN == 4) ? 2 : 4;
 #pragma unroll 1
-            for (int it = tid; it < ITEMS; it += NT) {
-                const int r = it / (OUT_COLS / 8), c8 = it % (OUT_COLS / 8);
-                const int row = m0 + prow0 + r;
-                const int ocol = out_n0 + c8 * 8;
-                if (row >= M || ocol >= out_N) continue;
-                if (PASSES > 1 && prow0 + r < pass * TM) continue;   // written by the pass before
-                float x[8];
-                if (EPI == EPI_SILU_MUL) {
-                    // gate block [64q, 64q+32) and up block [64q+32, 64q+64) of the tile
-                    const int oc = c8 * 8;                      // output column within the tile
-                    const float* g = tile + r * LDT + (oc >> 5) * 64 + (oc & 31);
-                    const float4 g0 = *reinterpret_cast<const float4*>(g);
-                    const float4 g1 = *reinterpret_cast<const float4*>(g + 4);
-                    const float4 u0 = *reinterpret_cast<const float4*>(g + 32);
-                    const float4 u1 = *reinterpret_cast<const float4*>(g + 36);
-                    const float gv[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
-                    const float uv[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
+            for (int it0 = tid; it0 < ITEMS; it0 += U * NT) {
+                int r_[U], row_[U], ocol_[U], c8_[U];
+                bool ok_[U];
+                uint4 rb_[U];           // bf16 residual (8 values)
+                float4 rf_[U][2];       // fp32 residual
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) x[e] = gv[e] / (1.f + __expf(-gv[e])) * uv[e];
-                } else {
-                    const float* t = tile + r * LDT + c8 * 8;
-                    const float4 t0 = *reinterpret_cast<const float4*>(t);
-                    const float4 t1 = *reinterpret_cast<const float4*>(t + 4);
-                    x[0] = t0.x; x[1] = t0.y; x[2] = t0.z; x[3] = t0.w;
-                    x[4] = t1.x; x[5] = t1.y; x[6] = t1.z; x[7] = t1.w;
-                }
-                if (EPI == EPI_RES_BF16_TO_F32) {
-                    const uint4 rv = *reinterpret_cast<const uint4*>(
-                        static_cast<const bf16_t*>(Rv) + (size_t)row * ldr + ocol);
-                    const uint32_t rw[4] = {rv.x, rv.y, rv.z, rv.w};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        x[2 * e] += __uint_as_float(rw[e] << 16);
-                        x[2 * e + 1] += __uint_as_float(rw[e] & 0xFFFF0000u);
-                    }
-                    float4* dst = reinterpret_cast<float4*>(static_cast<float*>(Cv) +
-                                                            (size_t)row * ldc + ocol);
-                    dst[0] = make_float4(x[0], x[1], x[2], x[3]);
-                    dst[1] = make_float4(x[4], x[5], x[6], x[7]);
-                } else {
-                    if (EPI == EPI_RES_F32_TO_BF16) {
+                for (int u = 0; u < U; ++u) {
+                    const int it = it0 + u * NT;
+                    r_[u] = it / (OUT_COLS / 8);
+                    c8_[u] = it % (OUT_COLS / 8);
+                    row_[u] = m0 + prow0 + r_[u];
+                    ocol_[u] = out_n0 + c8_[u] * 8;
+                    ok_[u] = it < ITEMS && row_[u] < M && ocol_[u] < out_N &&
+                             !(PASSES > 1 && prow0 + r_[u] < pass * TM);   // (written by the pass before)
+                    if (EPI == EPI_RES_BF16_TO_F32 && ok_[u])
+                        rb_[u] = *reinterpret_cast<const uint4*>(
+                            static_cast<const bf16_t*>(Rv) + (size_t)row_[u] * ldr + ocol_[u]);
+                    if (EPI == EPI_RES_F32_TO_BF16 && ok_[u]) {
                         const float4* rp = reinterpret_cast<const float4*>(
-                            static_cast<const float*>(Rv) + (size_t)row * ldr + ocol);
-                        const float4 r0 = rp[0], r1 = rp[1];
-                        x[0] += r0.x; x[1] += r0.y; x[2] += r0.z; x[3] += r0.w;
-                        x[4] += r1.x; x[5] += r1.y; x[6] += r1.z; x[7] += r1.w;
+                            static_cast<const float*>(Rv) + (size_t)row_[u] * ldr + ocol_[u]);
+                        rf_[u][0] = rp[0];
+                        rf_[u][1] = rp[1];
                     }
-                    *reinterpret_cast<uint4*>(static_cast<bf16_t*>(Cv) + (size_t)row * ldc + ocol) =
-                        make_uint4(pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]),
-                                   pack_bf16x2(x[4], x[5]), pack_bf16x2(x[6], x[7]));
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (!ok_[u]) continue;
+                    const int r = r_[u], c8 = c8_[u];
+                    float x[8];
+                    if (EPI == EPI_SILU_MUL) {
+                        // gate block [64q, 64q+32) and up block [64q+32, 64q+64) of the tile
+                        const int oc = c8 * 8;                      // output column within the tile
+                        const float* g = tile + r * LDT + (oc >> 5) * 64 + (oc & 31);
+                        const float4 g0 = *reinterpret_cast<const float4*>(g);
+                        const float4 g1 = *reinterpret_cast<const float4*>(g + 4);
+                        const float4 u0 = *reinterpret_cast<const float4*>(g + 32);
+                        const float4 u1 = *reinterpret_cast<const float4*>(g + 36);
+                        const float gv[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+                        const float uv[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
+                        // SiLU(g) u = g u / (1 + e^-g); the hardware reciprocal (1 ulp) is far inside
+                        // what the bf16 result keeps
+#pragma unroll
+                        for (int e = 0; e < 8; ++e)
+                            x[e] = gv[e] * uv[e] * __builtin_amdgcn_rcpf(1.f + __expf(-gv[e]));
+                    } else {
+                        const float* t = tile + r * LDT + c8 * 8;
+                        const float4 t0 = *reinterpret_cast<const float4*>(t);
+                        const float4 t1 = *reinterpret_cast<const float4*>(t + 4);
+                        x[0] = t0.x; x[1] = t0.y; x[2] = t0.z; x[3] = t0.w;
+                        x[4] = t1.x; x[5] = t1.y; x[6] = t1.z; x[7] = t1.w;
+                    }
+                    if (EPI == EPI_RES_BF16_TO_F32) {
+                        const uint32_t rw[4] = {rb_[u].x, rb_[u].y, rb_[u].z, rb_[u].w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            x[2 * e] += __uint_as_float(rw[e] << 16);
+                            x[2 * e + 1] += __uint_as_float(rw[e] & 0xFFFF0000u);
+                        }
+                        float4* dst = reinterpret_cast<float4*>(static_cast<float*>(Cv) +
+                                                                (size_t)row_[u] * ldc + ocol_[u]);
+                        dst[0] = make_float4(x[0], x[1], x[2], x[3]);
+                        dst[1] = make_float4(x[4], x[5], x[6], x[7]);
+                    } else {
+                        if (EPI == EPI_RES_F32_TO_BF16) {
+                            const float4 r0 = rf_[u][0], r1 = rf_[u][1];
+                            x[0] += r0.x; x[1] += r0.y; x[2] += r0.z; x[3] += r0.w;
+                            x[4] += r1.x; x[5] += r1.y; x[6] += r1.z; x[7] += r1.w;
+                        }
+                        *reinterpret_cast<uint4*>(static_cast<bf16_t*>(Cv) + (size_t)row_[u] * ldc +
+                                                  ocol_[u]) =
+                            make_uint4(pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]),
+                                       pack_bf16x2(x[4], x[5]), pack_bf16x2(x[6], x[7]));
+                    }
                 }
             }
         }
@@ -821,13 +852,14 @@ static GemmPlan make_plan(int M, int N, int K, int BM, int BN, int BK, int slots
     return p;
 }
 
-template <int BM, int BN, int BK, int WM, int WN, int NS>
-static int launch_cfg(const bf16_t* A, int lda, const bf16_t* W, int M, int N, int K, void* C,
-                      int ldc, const void* R, int ldr, int epi, int slots_per_cu, int sk_pct,
-                      float* partial, size_t partial_bytes, uint32_t* counters, int n_counters,
-                      const RopeEpilogue& rope, hipStream_t st) {
-    constexpr bool has_sk = !(WM * WN == 4 && ((BM / 32 + WM - 1) / WM) * (BN / WN / 32) >= 15);
-    GemmPlan plan = make_plan(M, N, K, BM, BN, BK, device_cu_count() * slots_per_cu, has_sk ? sk_pct : 0);
+// Which part of the tile plan a launch covers: all of it, or -- when two kernels of the same tile
+// size share one plan -- the whole tiles only, or the K-split tiles of the last round only.
+enum PlanPart { PLAN_ALL = 0, PLAN_WHOLE_TILES = 1, PLAN_SPLIT_TILES = 2 };
+
+// The plan for a tile shape, with the K-split dropped when the workspace has no room for it.
+static GemmPlan plan_for(int M, int N, int K, int BM, int BN, int BK, int slots, int sk_pct,
+                         size_t partial_bytes, int n_counters) {
+    GemmPlan plan = make_plan(M, N, K, BM, BN, BK, slots, sk_pct);
     if (plan.sk_blocks > 0) {
         const size_t need = (size_t)2 * plan.sk_blocks * BM * BN * sizeof(float);
         if (need > partial_bytes || plan.sk_tiles > n_counters) {  // no room: whole tiles only
@@ -836,7 +868,26 @@ static int launch_cfg(const bf16_t* A, int lda, const bf16_t* W, int M, int N, i
             plan.sk_tiles = plan.sk_blocks = 0;
         }
     }
+    return plan;
+}
+
+template <int BM, int BN, int BK, int WM, int WN, int NS>
+static int launch_cfg(const bf16_t* A, int lda, const bf16_t* W, int M, int N, int K, void* C,
+                      int ldc, const void* R, int ldr, int epi, int slots_per_cu, int sk_pct,
+                      float* partial, size_t partial_bytes, uint32_t* counters, int n_counters,
+                      const RopeEpilogue& rope, hipStream_t st, PlanPart part = PLAN_ALL) {
+    constexpr bool has_sk = !(WM * WN == 4 && ((BM / 32 + WM - 1) / WM) * (BN / WN / 32) >= 15);
+    GemmPlan plan = plan_for(M, N, K, BM, BN, BK, device_cu_count() * slots_per_cu,
+                             (has_sk || part != PLAN_ALL) ? sk_pct : 0, partial_bytes, n_counters);
+    if (part == PLAN_WHOLE_TILES) {
+        plan.sk_tiles = plan.sk_blocks = 0;         // (their tiles are left to the other launch)
+    } else if (part == PLAN_SPLIT_TILES) {
+        if (plan.sk_blocks == 0) return MVLA_OK;
+        plan.dp_grid = 0;                           // workgroup ids start at the K-split workgroups
+    }
+    if (!has_sk && plan.sk_blocks > 0) return MVLA_EINVAL;
     const int grid = plan.dp_grid + plan.sk_blocks;
+    if (grid == 0) return MVLA_OK;
     const size_t stage_bytes = (size_t)NS * (BM + BN) * (BK / 8) * sizeof(uint4);
     const size_t epi_bytes = EpiGeom<BM, BN, WM, NS>::BYTES;
     const size_t lds = stage_bytes > epi_bytes ? stage_bytes : epi_bytes;
@@ -885,8 +936,9 @@ static const TileCfg kCfgs[kNumCfgs] = {
     {256, 128, 1, 62.f, true},    // K-slab 64, eight waves of 64x64, three stages
     {128, 128, 2, 67.f, true},    // K-slab 64, four waves of 64x64, two stages, two workgroups per CU
     {128, 128, 1, 35.f, true},    // K-slab 64, eight waves of 32x64, three stages
-    {256, 256, 1, 98.f, false},   // K-slab 64, four waves of 128x128 (accumulators fill the second
-                                  // register file, a third less LDS traffic per MFMA), whole tiles only
+    {256, 256, 1, 98.f, true},    // K-slab 64, four waves of 128x128 (accumulators fill the second
+                                  // register file, a third less LDS traffic per MFMA); a K-split last
+                                  // round runs on the eight-wave kernel of the same tile size
     {192, 128, 1, 50.f, true},    // K-slab 64, eight waves of 96x32, three stages (row counts just over
                                   // 2x256 with few column tiles: three row tiles, K-split over all CUs)
     {288, 192, 1, 92.f, false},   // K-slab 64, four waves of 160x96 (the two wave rows overlap by one
@@ -966,7 +1018,17 @@ int launch_gemm(const bf16_t* A, int lda, const bf16_t* W, int M, int N, int K, 
         case 1: return launch_cfg<256, 128, 64, 4, 2, 3>(MVLA_ARGS);
         case 2: return launch_cfg<128, 128, 64, 2, 2, 2>(MVLA_ARGS);
         case 3: return launch_cfg<128, 128, 64, 4, 2, 3>(MVLA_ARGS);
-        case 4: return launch_cfg<256, 256, 64, 2, 2, 2>(MVLA_ARGS);
+        case 4: {
+            // four waves of 128x128 have no registers for the K-split exchange: when the last round
+            // is to be cut, its tiles go to the eight-wave kernel of the same tile size in a second
+            // launch (same plan, same tile numbering)
+            const GemmPlan pl = plan_for(M, N, K, 256, 256, 64, device_cu_count(), split_pct,
+                                         partial_bytes, n_counters);
+            if (pl.sk_blocks == 0) return launch_cfg<256, 256, 64, 2, 2, 2>(MVLA_ARGS);
+            const int rc = launch_cfg<256, 256, 64, 2, 2, 2>(MVLA_ARGS, PLAN_WHOLE_TILES);
+            if (rc) return rc;
+            return launch_cfg<256, 256, 64, 2, 4, 2>(MVLA_ARGS, PLAN_SPLIT_TILES);
+        }
         case 5: return launch_cfg<192, 128, 64, 2, 4, 3>(MVLA_ARGS);
         default: return launch_cfg<288, 192, 64, 2, 2, 2>(MVLA_ARGS);
     }
