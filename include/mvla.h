@@ -328,8 +328,9 @@ int mvla_tune_layers(mvla_ctx* ctx, const mvla_layer_cfg* cfg, const mvla_layer_
 /* Record a choice by hand (e.g. one measured in an earlier run, for identical
  * summation order across runs): configuration index 0 .. 6 (256x256 on eight waves,
  * 256x128, 128x128 two per CU, 128x128 on eight waves, 256x256 on four waves, 192x128,
- * 288x192 on four waves; the two four-wave shapes run whole tiles only and ignore the
- * K-split threshold; a shape whose tiles do not hold whole heads is not used for the
+ * 288x192 on four waves; the 288x192 shape runs whole tiles only and ignores the K-split
+ * threshold, the four-wave 256x256 shape hands a K-split last round to the eight-wave
+ * kernel of the same tile size in a second launch; a shape whose tiles do not hold whole heads is not used for the
  * q/k/v projection, whatever is recorded) and the K-split
  * threshold in percent (0 never, 101 whenever the last round of tiles is not
  * full); cfg < 0 removes the record.  Host-side only, nothing is launched. */
