@@ -467,6 +467,35 @@ def test_every_projection_kernel_configuration(ctx, cfg_id, split_pct):
         assert_layer_close(y[0], ref, f"config {cfg_id} split {split_pct} S={S}", wl.D, floor)
 
 
+@pytest.mark.parametrize("D,H,F", [(128, 2, 64), (256, 4, 128), (256, 4, 1024)])
+def test_every_projection_kernel_configuration_at_short_contractions(D, H, F):
+    """The main loops run their slabs in a ring that is primed for several slabs ahead: K = 64
+    (one slab), 128, 256 and 1024, forced on every tile configuration with and without the
+    K-split, rows not a multiple of any tile (B = 3 x S = 37).  Against the oracle layer at the
+    stated bar.  (Configurations whose tiles do not divide the q/k/v sections leave that
+    projection to the built-in choice.)"""
+    from dataclasses import replace
+    wl = replace(W.WORKLOADS["tiny"], D=D, H=H, dh=D // H, F=F, n2=16, n3=16, nt=5, B=3, seed=11)
+    ctx = mv.Context(wl.B, wl.S, wl.D, wl.H, wl.F, wl.nt)
+    w_cpu = W.layer_weights(wl, 0)
+    packed, struct = device_layer(ctx, wl, w_cpu)
+    ow = oracle_weights(w_cpu)
+    x, pos = W.hidden_states(wl, device="cuda")
+    M = wl.B * wl.S
+    refs = [O.decoder_layer(to64(x[b]), pos[b].cpu().numpy(), ow, wl.H, wl.rms_eps, wl.rope_base)[0]
+            for b in range(wl.B)]
+    shapes = [(3 * wl.D, wl.D, 0), (wl.D, wl.D, 1), (wl.D, wl.F, 2), (2 * wl.F, wl.D, 3)]
+    for cfg_id in range(7):
+        for split_pct in (0, 101):
+            for N, K, epi in shapes:
+                ctx.set_gemm_choice(M, N, K, epi, cfg_id, split_pct)
+            y = ctx.prefill_layer(layer_cfg(wl), struct, x, pos)
+            torch.cuda.synchronize()
+            for b in range(wl.B):
+                assert_layer_close(y[b], refs[b], f"D={D} F={F} config {cfg_id} split {split_pct} b={b}", wl.D)
+    ctx.close()
+
+
 @pytest.mark.parametrize("S", [237, 544])
 def test_layer_runs_are_bit_reproducible(ctx, S):
     """The same layer call repeated: every run must give the same bits (K-split pieces are summed
