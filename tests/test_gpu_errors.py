@@ -99,3 +99,47 @@ def test_probe_argument_errors(tiny_plan):
     for kind in (mv.PROBE_READ, mv.PROBE_COPY, mv.PROBE_MFMA, mv.PROBE_LAUNCH):
         assert lib.mvla_peak_probe(h, kind, buf.data_ptr(), buf.numel(), 2, C.byref(out)) == 0
         assert np.isfinite(out.value) and out.value > 0
+
+
+def test_masked_step_rejects_bad_descriptions(tiny_plan):
+    """mvla_masked_prefill_step: every invalid description or missing buffer returns before a
+    launch; a valid first step (cold start, nothing pruned) still runs afterwards."""
+    wl, ctx, plan, x, pos = tiny_plan
+    ep = mv.MaskedPrefill(plan)
+    lib = mv.load()
+    u = W.uniform_draws(wl, device="cuda", B=plan.B, step=1)
+
+    def call(desc, x_=x, u_=u, buffers=None, lengths=True):
+        y_ptr, rows = C.c_void_p(), C.c_int()
+        ln = (C.c_int32 * plan.B)()
+        return lib.mvla_masked_prefill_step(
+            ctx.handle, C.byref(plan.cfg), plan._layer_array, C.byref(desc),
+            x_.data_ptr() if x_ is not None else None, pos.data_ptr(), None,
+            u_.data_ptr() if u_ is not None else None,
+            C.byref(buffers if buffers is not None else ep._buffers), C.byref(y_ptr), C.byref(rows),
+            ln if lengths else None)
+
+    def desc(**kw):
+        f = dict(B=plan.B, n_patch=plan.n2, n_text=plan.nt, n_layers=plan.L, p=plan.p, t=2,
+                 smooth_k=7, smooth_beta=0.85, rules=mv.MaskRules.default())
+        f.update(kw)
+        return mv.MaskedDesc(*[f[name] for name, _ in mv.MaskedDesc._fields_])
+
+    for kw in (dict(B=0), dict(n_patch=0), dict(n_text=0), dict(n_layers=0), dict(p=0),
+               dict(p=plan.L + 1), dict(t=0), dict(smooth_k=0), dict(smooth_beta=1.0),
+               dict(rules=mv.MaskRules.default(kmeans_max_iter=0)),
+               dict(rules=mv.MaskRules.default(tau_2d=0.5, tau_3d=0.1)),
+               dict(rules=mv.MaskRules.default(bg_drop=1.5))):
+        assert call(desc(**kw)) == EINVAL, kw
+    assert call(desc(n_patch=16385)) == -4                       # more patches than the LDS stages
+    assert call(desc(), x_=None) == EINVAL
+    assert call(desc(), u_=None) == EINVAL                       # t > 1 needs the draws
+    assert call(desc(), lengths=False) == EINVAL
+    for field in ("probs", "sal", "x_t", "x_hat", "mask2d", "kept_len", "kept_idx", "pos_kept"):
+        b = mv.MaskedBuffers.from_buffer_copy(ep._buffers)
+        setattr(b, field, None)
+        assert call(desc(), buffers=b) == EINVAL, field
+    torch.cuda.synchronize()
+    y, lengths = ep.step(1, x, pos, u)
+    torch.cuda.synchronize()
+    assert y.shape[1] == plan.S and lengths == [plan.S] * plan.B
