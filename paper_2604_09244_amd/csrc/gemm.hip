@@ -65,6 +65,19 @@ __device__ __forceinline__ f32q_t ld16_coherent(const float* p) {
     asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=v"(v) : "v"(p) : "memory");
     return v;
 }
+// Output (and residual) of the epilogues as a bounds-checked buffer: a lane whose byte offset lies
+// at or beyond the record count is dropped (stores) or reads zeros (loads) by the hardware.  A
+// lane that has nothing to write gets the offset OOB_OFFSET instead of a branch around its store:
+// the stream of memory instructions is then the same for every lane, and the compiler's count of
+// outstanding ones -- which places the waits for the residual reads -- is exact (a store that may
+// or may not have been issued makes it wait for the stores before as well: loads and stores
+// return in issue order).
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+constexpr int OOB_OFFSET = 0x7FFF0000;
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t buffer_of(const void* base, int bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes > 0 ? bytes : 0, 0x00020000);
+}
 __device__ __forceinline__ void settle(f32q_t& a, f32q_t& b, f32q_t& c, f32q_t& d) {
     asm volatile("s_waitcnt vmcnt(0)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d)::"memory");
 }
@@ -551,15 +564,20 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
         // ---- epilogue through LDS: the MFMAs are issued with the weight fragment as the first
         // operand, so a lane of an accumulator block holds one tile row and its registers four
         // consecutive columns at a time: the tile is laid down as fp32 rows with 16-byte stores,
-        // then every thread takes 8 consecutive columns of a row, so the residual is read and the
-        // result written with 16-byte accesses on whole cache lines.  A pass covers as many tile
-        // rows as the LDS holds (a whole number of wave rows); only the waves owning them write.
+        // then every thread takes 8 consecutive columns of a row (4 where an fp32 matrix is read or
+        // written), so the residual is read and the result written with one access per lane on
+        // whole consecutive cache lines.  A pass covers as many tile rows as the LDS holds (a whole
+        // number of wave rows); only the waves owning them write.
         using EG = EpiGeom<BM, BN, WM, NS>;
         constexpr int LDT = EG::LDT, PASSES = EG::PASSES, RP = EG::RP;
         constexpr int OUT_COLS = EPI == EPI_SILU_MUL ? BN / 2 : BN;   // output columns per tile
         static_assert(RP % 16 == 0, "row groups of 8 come in pairs");
         constexpr int ITEMS = RP * OUT_COLS / 8;                      // 8-column items per pass
         float* tile = reinterpret_cast<float*>(lds);
+        // (the epilogue's per-thread indices are computed here, not before the main loop, where
+        // the compiler would otherwise put them and keep them in registers the loop needs)
+        int etid = tid;
+        asm volatile("" : "+v"(etid));
         const int out_n0 = EPI == EPI_SILU_MUL ? n0 / 2 : n0;
         const int out_N = EPI == EPI_SILU_MUL ? N / 2 : N;
 #pragma unroll 1
@@ -576,10 +594,100 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
             if (PREFETCH && n0 < 2 * rope.D) {
 #pragma unroll
                 for (int q = 0; q < NB * QB; ++q) {
-                    const int row = m0 + prow0 + min((tid + q * NT) / PER_ROW, RP - 1);
+                    const int row = m0 + prow0 + min((etid + q * NT) / PER_ROW, RP - 1);
                     pos_pre[q] = rope.pos[min(row, M - 1)];
                 }
             }
+            // This pass's part of the output as a bounds-checked buffer (rows of the pass that
+            // exist, the tile's columns that exist); offsets are relative to its first element.
+            constexpr int ES = EPI == EPI_RES_BF16_TO_F32 ? 4 : 2;           // bytes per output element
+            const int rows_here = min(RP, M - m0 - prow0);                    // (may be <= 0)
+            const int cols_here = min(OUT_COLS, out_N - out_n0);
+            const int r_lo = PASSES > 1 ? max(pass * TM - prow0, 0) : 0;      // rows below: the pass before wrote them
+            const __amdgpu_buffer_rsrc_t c_buf = buffer_of(
+                static_cast<char*>(Cv) + ((size_t)(m0 + prow0) * ldc + out_n0) * ES,
+                rows_here > 0 ? ((rows_here - 1) * ldc + cols_here) * ES : 0);
+            // Residual epilogues: an item is 4 columns of a row (16 bytes of fp32: a wave's load
+            // or store covers consecutive whole cache lines; with 8-column items a lane's two
+            // 16-byte fp32 accesses lay 32 bytes apart and a store burst of that form takes 1.4-1.8
+            // times as long).  Items go in batches of RU whose residual reads are in flight
+            // together, the first batch requested before the tile is laid down; reads and stores
+            // are unconditional buffer accesses (behind a per-item branch the compiler made each
+            // read wait for the one before it -- a memory round trip per item -- and behind
+            // conditional stores for the stores before it).
+            constexpr bool RES = EPI == EPI_RES_BF16_TO_F32 || EPI == EPI_RES_F32_TO_BF16;
+            // (register room: the four-wave 256x256 shape has its accumulators in the second
+            // register file and takes 16 items per batch; the others 16 registers' worth; shapes
+            // with no registers to spare request after the lay-down)
+            constexpr bool BIG = WM * WN == 4 && BM == 256 && BN == 256;
+            constexpr bool TIGHT = (WM * WN == 8 && BM == 256 && BN == 256) || BM == 288 ||
+                                   (WM * WN == 4 && BM == 128);
+            constexpr int IPR = OUT_COLS / 4;                                 // items per tile row
+            constexpr int RPT = (RP * IPR + NT - 1) / NT;                     // items per thread and pass
+            constexpr int RREG = EPI == EPI_RES_BF16_TO_F32 ? 2 : 4;          // registers per item
+            constexpr int RES_ES = EPI == EPI_RES_BF16_TO_F32 ? 2 : 4;        // bytes per residual element
+            constexpr int RU_MAX = BIG ? 16 : 16 / RREG;
+            constexpr int RU = RPT < RU_MAX ? RPT : RU_MAX, RNB = (RPT + RU - 1) / RU;
+            // item k of this thread: row r of the pass and first column c4 of the tile.  Where the
+            // threads of the workgroup cover whole rows, the column is the same for every item
+            // and the row advances by a constant: no divisions, offsets by one addition.
+            constexpr bool WHOLE_ROWS = NT % IPR == 0;
+            constexpr int RSTEP = WHOLE_ROWS ? NT / IPR : 0;
+            int ftid = etid;   // (thread index as the items' second half sees it: set after the lay-down)
+            auto item_rc = [&](int t, int k, int& r, int& c4) __attribute__((always_inline)) {
+                if (WHOLE_ROWS) {
+                    r = t / IPR + k * RSTEP;
+                    c4 = (t % IPR) * 4;
+                } else {
+                    const int it = t + k * NT;
+                    r = it / IPR;
+                    c4 = (it % IPR) * 4;
+                }
+            };
+            const __amdgpu_buffer_rsrc_t r_buf = buffer_of(
+                RES ? static_cast<const char*>(Rv) + ((size_t)(m0 + prow0) * ldr + out_n0) * RES_ES : nullptr,
+                RES && rows_here > 0 ? ((rows_here - 1) * ldr + cols_here) * RES_ES : 0);
+            u32x2_t rh_[RES ? RU : 1];    // bf16 residual (4 values)
+            u32x4_t rf_[RES ? RU : 1];    // fp32 residual
+            auto res_request = [&](int b) __attribute__((always_inline)) {
+#pragma unroll
+                for (int u = 0; u < RU; ++u) {
+                    int r, c4;
+                    item_rc(etid, b * RU + u, r, c4);
+                    const int off = (min(r, RP - 1) * ldr + c4) * RES_ES;   // (beyond the records: zeros)
+                    if (EPI == EPI_RES_BF16_TO_F32)
+                        rh_[u] = __builtin_amdgcn_raw_buffer_load_b64(r_buf, off, 0, 0);
+                    else
+                        rf_[u] = __builtin_amdgcn_raw_buffer_load_b128(r_buf, off, 0, 0);
+                }
+            };
+            auto res_finish = [&](int b) __attribute__((always_inline)) {
+#pragma unroll
+                for (int u = 0; u < RU; ++u) {
+                    int r, c4;
+                    item_rc(ftid, b * RU + u, r, c4);
+                    const bool ok = r >= r_lo && r < rows_here && c4 < cols_here;
+                    const int off = ok ? (r * ldc + c4) * ES : OOB_OFFSET;
+                    const float4 t = *reinterpret_cast<const float4*>(tile + min(r, RP - 1) * LDT + c4);
+                    if (EPI == EPI_RES_BF16_TO_F32) {
+                        const u32x2_t h = rh_[u];
+                        const u32x4_t o = {__float_as_uint(t.x + __uint_as_float(h.x << 16)),
+                                           __float_as_uint(t.y + __uint_as_float(h.x & 0xFFFF0000u)),
+                                           __float_as_uint(t.z + __uint_as_float(h.y << 16)),
+                                           __float_as_uint(t.w + __uint_as_float(h.y & 0xFFFF0000u))};
+                        __builtin_amdgcn_raw_buffer_store_b128(o, c_buf, off, 0, 0);
+                    } else {
+                        const u32x4_t q = rf_[u];
+                        const u32x2_t o = {pack_bf16x2(t.x + __uint_as_float(q.x), t.y + __uint_as_float(q.y)),
+                                           pack_bf16x2(t.z + __uint_as_float(q.z), t.w + __uint_as_float(q.w))};
+                        __builtin_amdgcn_raw_buffer_store_b64(o, c_buf, off, 0, 0);
+                    }
+                    // (items stay in order: with nothing conditional left the scheduler would
+                    // otherwise read the tile rows of all items first and run out of registers)
+                    if (u % 4 == 3) __builtin_amdgcn_sched_barrier(0);
+                }
+            };
+            if constexpr (RES && !TIGHT) res_request(0);
             __syncthreads();   // previous readers of the LDS (fragments or the last pass) are done
             if (PASSES == 1 || wm == pass) {
 #pragma unroll
@@ -596,6 +704,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
                         }
             }
             __syncthreads();
+            // (what the items need beyond their residual is computed from here on, not before
+            // the lay-down, where it would be held in registers across it)
+            asm volatile("" : "+v"(ftid));
             if (EPI == EPI_QKV_ROPE) {
                 const int DH = rope.dh, HALF = DH >> 1, CPH = HALF >> 3;   // 16-byte chunks per half head
                 if (n0 < 2 * rope.D) {
@@ -603,10 +714,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
                     // their partners dh/2 further on (tiles hold whole heads: BN % dh == 0; a row
                     // has BN/16 items whatever dh is).  Items are taken a few at a time so that the
                     // table rows of a batch are in flight together.
-                    bf16_t* Cb = static_cast<bf16_t*>(Cv);
 #pragma unroll
                     for (int jb = 0; jb < NB; ++jb) {
-                        const int it0 = tid + jb * QB * NT;
+                        const int it0 = etid + jb * QB * NT;
                         int r[QB], col[QB], c8[QB], p[QB];
                         bool ok[QB];
 #pragma unroll
@@ -617,8 +727,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
                             c8[u] = (rest % CPH) * 8;
                             col[u] = (rest / CPH) * DH + c8[u];   // column in the tile
                             const int row = m0 + prow0 + r[u];
-                            ok[u] = it < RP * PER_ROW && row < M && n0 + col[u] < N &&
-                                    !(PASSES > 1 && prow0 + r[u] < pass * TM);
+                            ok[u] = it < RP * PER_ROW && r[u] >= r_lo && r[u] < rows_here && col[u] < cols_here;
                             p[u] = PREFETCH ? pos_pre[PREFETCH ? jb * QB + u : 0] : rope.pos[min(row, M - 1)];
                         }
                         float4 cs[QB][2], sn[QB][2];
@@ -632,7 +741,6 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
                         }
 #pragma unroll
                         for (int u = 0; u < QB; ++u) {
-                            if (!ok[u]) continue;
                             const float* ta = tile + r[u] * LDT + col[u];
                             const float4 a0 = *reinterpret_cast<const float4*>(ta);
                             const float4 a1 = *reinterpret_cast<const float4*>(ta + 4);
@@ -652,154 +760,118 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(
                                 wb[e] = pack_bf16x2(b[2 * e] * c[2 * e] + a[2 * e] * sv[2 * e],
                                                     b[2 * e + 1] * c[2 * e + 1] + a[2 * e + 1] * sv[2 * e + 1]);
                             }
-                            bf16_t* dst = Cb + (size_t)(m0 + prow0 + r[u]) * ldc + n0 + col[u];
-                            *reinterpret_cast<uint4*>(dst) = make_uint4(wa[0], wa[1], wa[2], wa[3]);
-                            *reinterpret_cast<uint4*>(dst + HALF) = make_uint4(wb[0], wb[1], wb[2], wb[3]);
+                            const int off = ok[u] ? (r[u] * ldc + col[u]) * 2 : OOB_OFFSET;
+                            const u32x4_t oa = {wa[0], wa[1], wa[2], wa[3]}, ob = {wb[0], wb[1], wb[2], wb[3]};
+                            __builtin_amdgcn_raw_buffer_store_b128(oa, c_buf, off, 0, 0);
+                            __builtin_amdgcn_raw_buffer_store_b128(ob, c_buf, off + HALF * 2, 0, 0);
+                            __builtin_amdgcn_sched_barrier(0);   // (one item's tile reads at a time: registers)
                         }
                     }
                 } else {
                     // v columns, transposed into vt[b, h, d, s]: an item is one column and one
-                    // group of 8 tokens aligned in s (one 16-byte store).  Groups are found from
-                    // candidate rows 8 apart; where a sample does not start on a multiple of 8 rows
-                    // they straddle the candidates, and the groups cut by the ends of the pass are
-                    // stored token by token by the two passes (or tiles) that hold their rows.
-                    // Lanes run over 32 columns x 2 groups: LDS reads without bank conflicts.
-                    const int H = rope.D / DH, S = rope.S;
+                    // group of 8 tokens aligned in s (one 16-byte store).  The rows of the pass are
+                    // walked sample by sample (a uniform loop: one division per sample, none per
+                    // item); within a sample's rows the groups are [8j, 8j+8) of its tokens, the
+                    // groups cut by the ends of the rows are stored token by token by the two
+                    // passes (or tiles) that hold their rows, and whoever stores a sample's last
+                    // token clears the padding behind it.  A half-wave runs over 32 columns, the
+                    // two halves over alternate groups: LDS reads without bank conflicts.
+                    const int H = rope.D / DH, S = rope.S, S_pad = rope.S_pad;
                     const int g_base = m0 + prow0;                                  // global row of LDS row 0
                     const int g_lo = m0 + (PASSES > 1 ? max(prow0, pass * TM) : 0);  // rows this pass owns
                     const int g_hi = min(g_base + RP, M);
-                    const int step = min(8, S);           // samples shorter than 8 tokens: one candidate each
-                    const int k_items = ((RP + step - 1) / step + 2) & ~1;   // + the clamped tail, kept even
+                    constexpr int NW = NT / 64, NCH = BN / 32;     // waves; 32-column chunks of the tile
+                    constexpr int WPC = NW > NCH ? NW / NCH : 1;   // waves sharing a chunk (over groups)
+                    const int vlane = ftid & 63, vwave = ftid >> 6;
+                    const int g_first = (vlane >> 5) + 2 * (NW > NCH ? vwave / NCH : 0);
+                    constexpr int G_STEP = 2 * WPC;
+                    for (int g_a = g_lo; g_a < g_hi;) {
+                        const int bs = g_a / S, g_s = bs * S, g_e = min(g_hi, g_s + S);
+                        const int s_a = g_a - g_s, s_e = g_e - g_s;   // tokens [s_a, s_e) of sample bs are ours
+                        const int r_off = g_s - g_base;               // LDS row of token s: s + r_off
+                        const int j_hi = (s_e + 7) >> 3;
 #pragma unroll 1
-                    for (int it = tid; it < BN * k_items; it += NT) {
-                        const int d = (it >> 1) % BN, k = ((it >> 1) / BN) * 2 + (it & 1);
-                        if (g_lo >= g_hi || n0 + d >= N) continue;
-                        const int cand = min(g_lo + step * k, g_hi - 1);
-                        const int bs = cand / S;
-                        int s_al = (cand - bs * S) & ~7;
-                        if (k > 0) {   // the same group as the candidate before (only at the clamped tail)?
-                            const int prev = min(g_lo + step * (k - 1), g_hi - 1) - bs * S;
-                            if (prev >= 0 && (prev & ~7) == s_al) continue;
-                        }
-                        const int vcol = n0 - 2 * rope.D + d, hd = vcol / DH, dd = vcol - hd * DH;
-                        bf16_t* dst = rope.vt + ((size_t)(bs * H + hd) * DH + dd) * rope.S_pad;
-                        // A sample's short last group can lie between two candidates: the item of
-                        // the group before it takes it along.
-                        const int n_groups = (s_al + 8 < S && cand + 8 >= (bs + 1) * S) ? 2 : 1;
+                        for (int ch = NW > NCH ? vwave % NCH : vwave; ch < NCH && (NW <= NCH || vwave < WPC * NCH);
+                             ch += NW) {
+                            const int d = ch * 32 + (vlane & 31);
+                            const int vcol = n0 - 2 * rope.D + d, hd = vcol / DH, dd = vcol - hd * DH;
+                            bf16_t* dst = rope.vt + ((size_t)(bs * H + hd) * DH + dd) * S_pad;
+                            const float* src = tile + r_off * LDT + d;     // (+ s * LDT: token s)
+                            if (n0 + d >= N) continue;
 #pragma unroll 1
-                        for (int rep = 0; rep < n_groups; ++rep, s_al += 8) {
-                            const int g0 = bs * S + s_al;        // global row of the group's first token
-                            const int n_tok = min(8, S - s_al);  // tokens of the group that exist
-                            float v[8];
+                            for (int j = (s_a >> 3) + g_first; j < j_hi; j += G_STEP) {
+                                const int s_al = j * 8;
+                                const int lo = max(s_a, s_al), hi = min(s_e, s_al + 8);
+                                if (lo == s_al && hi == s_al + 8) {          // a whole group of ours
+                                    const float* q = src + s_al * LDT;
+                                    *reinterpret_cast<uint4*>(dst + s_al) =
+                                        make_uint4(pack_bf16x2(q[0], q[LDT]), pack_bf16x2(q[2 * LDT], q[3 * LDT]),
+                                                   pack_bf16x2(q[4 * LDT], q[5 * LDT]),
+                                                   pack_bf16x2(q[6 * LDT], q[7 * LDT]));
+                                    if (hi == S)
+                                        for (int z = s_al + 8; z < S_pad; z += 8)
+                                            *reinterpret_cast<uint4*>(dst + z) = make_uint4(0, 0, 0, 0);
+                                } else if (lo == s_al && hi == S) {          // the sample's short last group, all ours
+                                    float v[8];
 #pragma unroll
-                            for (int i = 0; i < 8; ++i) {
-                                const int g = g0 + i;
-                                v[i] = (i < n_tok && g >= g_lo && g < g_hi) ? tile[(g - g_base) * LDT + d] : 0.f;
-                            }
-                            if (g0 >= g_lo && g0 + n_tok <= g_hi) {
-                                *reinterpret_cast<uint4*>(dst + s_al) =
-                                    make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]),
-                                               pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
-                                if (s_al + 8 >= S)   // the sample's last token: clear the rest of the padding
-                                    for (int z = s_al + 8; z < rope.S_pad; z += 8)
+                                    for (int i = 0; i < 8; ++i)
+                                        v[i] = s_al + i < hi ? src[min(s_al + i, hi - 1) * LDT] : 0.f;
+                                    *reinterpret_cast<uint4*>(dst + s_al) =
+                                        make_uint4(pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]),
+                                                   pack_bf16x2(v[4], v[5]), pack_bf16x2(v[6], v[7]));
+                                    for (int z = s_al + 8; z < S_pad; z += 8)
                                         *reinterpret_cast<uint4*>(dst + z) = make_uint4(0, 0, 0, 0);
-                            } else {
+                                } else {                                     // cut by the ends of our rows
 #pragma unroll 1
-                                for (int i = 0; i < n_tok; ++i) {
-                                    const int g = g0 + i;
-                                    if (g < g_lo || g >= g_hi) continue;
-                                    dst[s_al + i] = (bf16_t)(pack_bf16x2(v[i], 0.f) & 0xFFFFu);
-                                    if (s_al + i == S - 1)
-                                        for (int z = S; z < rope.S_pad; ++z) dst[z] = 0;
+                                    for (int t = lo; t < hi; ++t) {
+                                        dst[t] = (bf16_t)(pack_bf16x2(src[t * LDT], 0.f) & 0xFFFFu);
+                                        if (t == S - 1)
+                                            for (int z = S; z < S_pad; ++z) dst[z] = 0;
+                                    }
                                 }
                             }
                         }
+                        g_a = g_e;
                     }
                 }
                 continue;
             }
-            // Items are taken U at a time: the residual reads of a batch are in flight together
-            // (one by one, every item waited a full memory round trip for its own: 32 of them in
-            // a row per thread and tile in the projections that add a residual).
-            // (eight at a time where the accumulators sit in the second register file; four, or two
-            // on the eight-wave 256x256 shape, where they share the file with the batch)
-            constexpr bool ROOMY = WM * WN == 4 && !(NS == 2 && BM == 128 && BN == 128);   // one workgroup per CU
-            constexpr int U = EPI == EPI_SILU_MUL ? 2 : ROOMY ? 8
-                              : (FM * FN >= 8 || EPI == EPI_RES_F32_TO_BF16 || WM * WN == 4) ? 2 : 4;
+            if constexpr (RES) {
+                if constexpr (TIGHT) res_request(0);
 #pragma unroll 1
-            for (int it0 = tid; it0 < ITEMS; it0 += U * NT) {
-                int r_[U], row_[U], ocol_[U], c8_[U];
-                bool ok_[U];
-                uint4 rb_[U];           // bf16 residual (8 values)
-                float4 rf_[U][2];       // fp32 residual
+                for (int b = 0; b < RNB; ++b) {
+                    res_finish(b);
+                    if (b + 1 < RNB) res_request(b + 1);
+                }
+                continue;
+            }
+            // SiLU(gate) * up: 8 output columns per item (16 bytes of bf16), two items at a time
+            constexpr int U = 2;
+#pragma unroll 1
+            for (int it0 = etid; it0 < ITEMS; it0 += U * NT) {
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int it = it0 + u * NT;
-                    r_[u] = it / (OUT_COLS / 8);
-                    c8_[u] = it % (OUT_COLS / 8);
-                    row_[u] = m0 + prow0 + r_[u];
-                    ocol_[u] = out_n0 + c8_[u] * 8;
-                    ok_[u] = it < ITEMS && row_[u] < M && ocol_[u] < out_N &&
-                             !(PASSES > 1 && prow0 + r_[u] < pass * TM);   // (written by the pass before)
-                    if (EPI == EPI_RES_BF16_TO_F32 && ok_[u])
-                        rb_[u] = *reinterpret_cast<const uint4*>(
-                            static_cast<const bf16_t*>(Rv) + (size_t)row_[u] * ldr + ocol_[u]);
-                    if (EPI == EPI_RES_F32_TO_BF16 && ok_[u]) {
-                        const float4* rp = reinterpret_cast<const float4*>(
-                            static_cast<const float*>(Rv) + (size_t)row_[u] * ldr + ocol_[u]);
-                        rf_[u][0] = rp[0];
-                        rf_[u][1] = rp[1];
-                    }
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    if (!ok_[u]) continue;
-                    const int r = r_[u], c8 = c8_[u];
+                    const int r = min(it / (OUT_COLS / 8), RP - 1), c8 = it % (OUT_COLS / 8);
+                    const bool ok = it < ITEMS && r >= r_lo && r < rows_here && c8 * 8 < cols_here;
+                    // gate block [64q, 64q+32) and up block [64q+32, 64q+64) of the tile
+                    const int oc = c8 * 8;                      // output column within the tile
+                    const float* g = tile + r * LDT + (oc >> 5) * 64 + (oc & 31);
+                    const float4 g0 = *reinterpret_cast<const float4*>(g);
+                    const float4 g1 = *reinterpret_cast<const float4*>(g + 4);
+                    const float4 u0 = *reinterpret_cast<const float4*>(g + 32);
+                    const float4 u1 = *reinterpret_cast<const float4*>(g + 36);
+                    const float gv[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+                    const float uv[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
+                    // SiLU(g) u = g u / (1 + e^-g); the hardware reciprocal (1 ulp) is far inside
+                    // what the bf16 result keeps
                     float x[8];
-                    if (EPI == EPI_SILU_MUL) {
-                        // gate block [64q, 64q+32) and up block [64q+32, 64q+64) of the tile
-                        const int oc = c8 * 8;                      // output column within the tile
-                        const float* g = tile + r * LDT + (oc >> 5) * 64 + (oc & 31);
-                        const float4 g0 = *reinterpret_cast<const float4*>(g);
-                        const float4 g1 = *reinterpret_cast<const float4*>(g + 4);
-                        const float4 u0 = *reinterpret_cast<const float4*>(g + 32);
-                        const float4 u1 = *reinterpret_cast<const float4*>(g + 36);
-                        const float gv[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
-                        const float uv[8] = {u0.x, u0.y, u0.z, u0.w, u1.x, u1.y, u1.z, u1.w};
-                        // SiLU(g) u = g u / (1 + e^-g); the hardware reciprocal (1 ulp) is far inside
-                        // what the bf16 result keeps
 #pragma unroll
-                        for (int e = 0; e < 8; ++e)
-                            x[e] = gv[e] * uv[e] * __builtin_amdgcn_rcpf(1.f + __expf(-gv[e]));
-                    } else {
-                        const float* t = tile + r * LDT + c8 * 8;
-                        const float4 t0 = *reinterpret_cast<const float4*>(t);
-                        const float4 t1 = *reinterpret_cast<const float4*>(t + 4);
-                        x[0] = t0.x; x[1] = t0.y; x[2] = t0.z; x[3] = t0.w;
-                        x[4] = t1.x; x[5] = t1.y; x[6] = t1.z; x[7] = t1.w;
-                    }
-                    if (EPI == EPI_RES_BF16_TO_F32) {
-                        const uint32_t rw[4] = {rb_[u].x, rb_[u].y, rb_[u].z, rb_[u].w};
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            x[2 * e] += __uint_as_float(rw[e] << 16);
-                            x[2 * e + 1] += __uint_as_float(rw[e] & 0xFFFF0000u);
-                        }
-                        float4* dst = reinterpret_cast<float4*>(static_cast<float*>(Cv) +
-                                                                (size_t)row_[u] * ldc + ocol_[u]);
-                        dst[0] = make_float4(x[0], x[1], x[2], x[3]);
-                        dst[1] = make_float4(x[4], x[5], x[6], x[7]);
-                    } else {
-                        if (EPI == EPI_RES_F32_TO_BF16) {
-                            const float4 r0 = rf_[u][0], r1 = rf_[u][1];
-                            x[0] += r0.x; x[1] += r0.y; x[2] += r0.z; x[3] += r0.w;
-                            x[4] += r1.x; x[5] += r1.y; x[6] += r1.z; x[7] += r1.w;
-                        }
-                        *reinterpret_cast<uint4*>(static_cast<bf16_t*>(Cv) + (size_t)row_[u] * ldc +
-                                                  ocol_[u]) =
-                            make_uint4(pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]),
-                                       pack_bf16x2(x[4], x[5]), pack_bf16x2(x[6], x[7]));
-                    }
+                    for (int e = 0; e < 8; ++e)
+                        x[e] = gv[e] * uv[e] * __builtin_amdgcn_rcpf(1.f + __expf(-gv[e]));
+                    const u32x4_t o = {pack_bf16x2(x[0], x[1]), pack_bf16x2(x[2], x[3]),
+                                       pack_bf16x2(x[4], x[5]), pack_bf16x2(x[6], x[7])};
+                    __builtin_amdgcn_raw_buffer_store_b128(o, c_buf, ok ? (r * ldc + oc) * 2 : OOB_OFFSET, 0, 0);
                 }
             }
         }
@@ -985,6 +1057,7 @@ int launch_gemm(const bf16_t* A, int lda, const bf16_t* W, int M, int N, int K, 
     if (K < 64 || K % 64 != 0 || lda % 8 != 0) return MVLA_EUNSUPPORTED;
     if (epilogue == EPI_SILU_MUL && N % 64 != 0) return MVLA_EUNSUPPORTED;
     if (N % 8 != 0 || ldc % 8 != 0 || (R && ldr % 8 != 0)) return MVLA_EUNSUPPORTED;
+    if (ldc > (1 << 20) || ldr > (1 << 20)) return MVLA_EUNSUPPORTED;   // (32-bit byte offsets inside a tile)
     if (epilogue == EPI_QKV_ROPE) {
         if (!rope || !rope->pos || !rope->rc || !rope->rs || rope->S <= 0 || rope->rope_len <= 0)
             return MVLA_EINVAL;
