@@ -42,8 +42,8 @@ MEASURED_TRAFFIC = {
     # (kernel, M, N, K): (gemm.hip hash, {tile configuration: bytes per launch})
     # configuration: (tile configuration, whether the last round is cut along K); with the cut the
     # figure is the sum over the two launches that make up the projection
-    ("gemm_gateup", 21504, 22016, 4096): ("5bd3a368bdc2e4c0", {(4, False): 6749.1e6, (4, True): 6514.1e6}),   # ratio_sweep, keep 50 %
-    ("gemm_gateup", 4688, 22016, 4096): ("5bd3a368bdc2e4c0", {(4, False): 1586.1e6, (4, True): 1868.1e6}),     # multi_view
+    ("gemm_gateup", 21504, 22016, 4096): ("0c8bd64d5c24849d", {(4, False): 6763.0e6, (4, True): 6514.5e6}),   # ratio_sweep, keep 50 %
+    ("gemm_gateup", 4688, 22016, 4096): ("0c8bd64d5c24849d", {(4, False): 1586.3e6, (4, True): 1865.3e6}),     # multi_view
 }
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
