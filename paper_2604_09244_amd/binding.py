@@ -394,10 +394,14 @@ class Context:
         for k in ("wqkv", "wo", "w_gateup", "w_down", "g_attn", "g_mlp"):
             _dev(packed[k], torch.bfloat16)
         c, s = rope
-        return LayerWeightsC(packed["wqkv"].data_ptr(), packed["wo"].data_ptr(),
-                             packed["w_gateup"].data_ptr(), packed["w_down"].data_ptr(),
-                             packed["g_attn"].data_ptr(), packed["g_mlp"].data_ptr(),
-                             c.data_ptr(), s.data_ptr(), c.shape[0])
+        w = LayerWeightsC(packed["wqkv"].data_ptr(), packed["wo"].data_ptr(),
+                          packed["w_gateup"].data_ptr(), packed["w_down"].data_ptr(),
+                          packed["g_attn"].data_ptr(), packed["g_mlp"].data_ptr(),
+                          c.data_ptr(), s.data_ptr(), c.shape[0])
+        # the descriptor holds bare device addresses: the tensors live as long as it does (a caller
+        # that passes a temporary would otherwise leave it pointing at freed memory)
+        w._keep_alive = (packed, rope)
+        return w
 
     def prefill_layer(self, cfg: LayerCfg, w: LayerWeightsC, x: torch.Tensor, pos: torch.Tensor,
                       y: Optional[torch.Tensor] = None, n_query_tail: int = 0,
