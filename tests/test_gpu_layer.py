@@ -467,12 +467,13 @@ def test_every_projection_kernel_configuration(ctx, cfg_id, split_pct):
         assert_layer_close(y[0], ref, f"config {cfg_id} split {split_pct} S={S}", wl.D, floor)
 
 
-@pytest.mark.parametrize("D,H,F", [(128, 2, 64), (256, 4, 128), (256, 4, 1024)])
+@pytest.mark.parametrize("D,H,F", [(128, 2, 64), (256, 4, 128), (256, 4, 1024), (192, 3, 128)])
 def test_every_projection_kernel_configuration_at_short_contractions(D, H, F):
     """The main loops run their slabs in a ring that is primed for several slabs ahead: K = 64
     (one slab), 128, 256 and 1024, forced on every tile configuration with and without the
-    K-split, rows not a multiple of any tile (B = 3 x S = 37).  Against the oracle layer at the
-    stated bar.  (Configurations whose tiles do not divide the q/k/v sections leave that
+    K-split, rows not a multiple of any tile (B = 3 x S = 37); D = 192 adds output widths that
+    end inside a tile column of every shape (192 and 576 columns) and three heads of 64.  Against
+    the oracle layer at the stated bar.  (Configurations whose tiles do not divide the q/k/v sections leave that
     projection to the built-in choice.)"""
     from dataclasses import replace
     wl = replace(W.WORKLOADS["tiny"], D=D, H=H, dh=D // H, F=F, n2=16, n3=16, nt=5, B=3, seed=11)
