@@ -236,7 +236,7 @@ typedef struct {
     int D;         /* hidden size, multiple of 64, at most 8192                */
     int H;         /* attention heads                                          */
     int dh;        /* head dim: 64 or 128; H*dh == D                           */
-    int F;         /* MLP width, multiple of 64                                */
+    int F;         /* MLP width, multiple of 64, at most 2^20                  */
     float rms_eps; /* RMSNorm epsilon                                          */
 } mvla_layer_cfg;
 
